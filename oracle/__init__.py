@@ -1,0 +1,167 @@
+"""CPU oracle for the batched maze hot path -- TEST INFRASTRUCTURE ONLY.
+
+Thin numpy/ctypes front end of ``maze_oracle.c`` (plain C, one env at a time,
+byte-per-cell grids, rewards and GAE in double).  Only the tests, the smoke
+check and the ``cpu_baseline`` leg of the benchmark may import this package;
+the product (the HIP library and its binding) never does, and this package
+imports nothing of the product.
+
+The C file is compiled with gcc into ``liboracle.so`` next to it (``build()``);
+if the library is missing it is built on first use.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "maze_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile maze_oracle.c with gcc (no contraction, IEEE arithmetic)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", tmp, _SRC]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        _lib = ctypes.CDLL(_LIB)
+        _lib.orc_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a: np.ndarray | None):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _req(a, dtype, shape=None):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    if shape is not None and tuple(a.shape) != tuple(shape):
+        raise ValueError(f"expected shape {tuple(shape)}, got {tuple(a.shape)}")
+    return a
+
+
+def num_threads() -> int:
+    return int(_load().orc_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().orc_set_num_threads(ctypes.c_int(int(n)))
+
+
+@dataclass
+class Levels:
+    """A batch of levels: the free parameters of the maze (Section 2.2)."""
+    walls: np.ndarray      # int8 [N,H,W], 1 = wall
+    agent_xy: np.ndarray   # int32 [N,2] start (x,y)
+    agent_dir: np.ndarray  # int8 [N] start heading 0..3
+    goal_xy: np.ndarray    # int32 [N,2]
+
+
+class MazeOracle:
+    """Batched student maze: reset to given levels, step, render."""
+
+    def __init__(self, N: int, H: int, W: int, view: int, max_steps: int):
+        if view % 2 != 1:
+            raise ValueError("view must be odd")
+        self.N, self.H, self.W, self.view, self.max_steps = N, H, W, view, max_steps
+        self.levels: Levels | None = None
+
+    def reset_to_levels(self, walls, agent_xy, agent_dir, goal_xy) -> None:
+        N, H, W = self.N, self.H, self.W
+        self.levels = Levels(_req(walls, np.int8, (N, H, W)).copy(),
+                             _req(agent_xy, np.int32, (N, 2)).copy(),
+                             _req(agent_dir, np.int8, (N,)).copy(),
+                             _req(goal_xy, np.int32, (N, 2)).copy())
+        self.xy = self.levels.agent_xy.copy()
+        self.dir = self.levels.agent_dir.copy()
+        self.t = np.zeros(N, np.int32)
+
+    def render_obs(self) -> np.ndarray:
+        L, k = self.levels, self.view
+        obs = np.empty((self.N, k, k, 3), np.int8)
+        _load().orc_maze_render(self.N, self.H, self.W, k, _p(L.walls), _p(L.goal_xy),
+                                _p(self.xy), _p(self.dir), _p(obs))
+        return obs
+
+    def step(self, actions, n_steps: int = 1, want_obs: bool = True):
+        """actions int8 [n_steps,N] -> reward f32, done u8 [n_steps,N], obs or None."""
+        L, k, N = self.levels, self.view, self.N
+        actions = _req(actions, np.int8, (n_steps, N))
+        reward = np.empty((n_steps, N), np.float32)
+        done = np.empty((n_steps, N), np.uint8)
+        obs = np.empty((n_steps, N, k, k, 3), np.int8) if want_obs else None
+        _load().orc_maze_rollout(N, self.H, self.W, k, self.max_steps, n_steps,
+                                 _p(L.walls), _p(L.agent_xy), _p(L.agent_dir), _p(L.goal_xy),
+                                 _p(self.xy), _p(self.dir), _p(self.t),
+                                 _p(actions), _p(reward), _p(done), _p(obs))
+        return reward, done, obs
+
+    def get_state(self):
+        return self.xy.copy(), self.dir.copy(), self.t.copy()
+
+    def get_levels(self) -> Levels:
+        L = self.levels
+        return Levels(L.walls.copy(), L.agent_xy.copy(), L.agent_dir.copy(), L.goal_xy.copy())
+
+
+class EditorOracle:
+    """Batched teacher design env: n_walls walls, then agent, then goal."""
+
+    def __init__(self, N: int, H: int, W: int, n_walls: int):
+        self.N, self.H, self.W, self.n_walls = N, H, W, n_walls
+
+    def reset(self, agent_dir_init) -> None:
+        N, H, W = self.N, self.H, self.W
+        self.dir_init = _req(agent_dir_init, np.int8, (N,)).copy()
+        self.walls = np.empty((N, H, W), np.int8)
+        self.agent_xy = np.empty((N, 2), np.int32)
+        self.agent_dir = np.empty(N, np.int8)
+        self.goal_xy = np.empty((N, 2), np.int32)
+        self.t = np.empty(N, np.int32)
+        _load().orc_editor_reset(N, H, W, _p(self.walls), _p(self.agent_xy), _p(self.agent_dir),
+                                 _p(self.goal_xy), _p(self.t))
+
+    def step(self, actions, n_steps: int = 1, want_obs: bool = True):
+        """actions int32 [n_steps,N] -> obs i8 [n_steps,N,H,W,3] (or None), t i32, done u8."""
+        N, H, W = self.N, self.H, self.W
+        actions = _req(actions, np.int32, (n_steps, N))
+        obs = np.empty((n_steps, N, H, W, 3), np.int8) if want_obs else None
+        t_out = np.empty((n_steps, N), np.int32)
+        done = np.empty((n_steps, N), np.uint8)
+        _load().orc_editor_rollout(N, H, W, self.n_walls, n_steps, _p(self.dir_init),
+                                   _p(self.walls), _p(self.agent_xy), _p(self.agent_dir),
+                                   _p(self.goal_xy), _p(self.t), _p(actions),
+                                   _p(obs), _p(t_out), _p(done))
+        return obs, t_out, done
+
+    def get_levels(self) -> Levels:
+        return Levels(self.walls.copy(), self.agent_xy.copy(), self.agent_dir.copy(),
+                      self.goal_xy.copy())
+
+
+def compute_gae(rewards, values, dones, gamma: float, lam: float):
+    """rewards f32 [T,N], values f32 [T+1,N], dones u8 [T,N] -> (adv, returns) float64 [T,N]."""
+    rewards = _req(rewards, np.float32)
+    T, N = rewards.shape
+    values = _req(values, np.float32, (T + 1, N))
+    dones = _req(dones, np.uint8, (T, N))
+    adv = np.empty((T, N), np.float64)
+    ret = np.empty((T, N), np.float64)
+    _load().orc_gae(T, N, ctypes.c_double(gamma), ctypes.c_double(lam),
+                    _p(rewards), _p(values), _p(dones), _p(adv), _p(ret))
+    return adv, ret

@@ -1,0 +1,302 @@
+/*
+ * CPU oracle for the batched maze hot path.  TEST INFRASTRUCTURE ONLY: the
+ * product (the HIP library) never includes, links or calls anything here.
+ *
+ * One env at a time, one byte per grid cell, scalar loops, no bit tricks,
+ * no blocking.  Each function is the plain definition of one operation of the
+ * tensorised maze benchmark of the paper (Section 3, "Maze as an Accelerated
+ * Petri Dish"; environment interface Section 2.2; PPO+GAE Appendix "Choice of
+ * Architecture and Hyperparameters").  Where the paper is silent the reading
+ * taken is written next to the code.
+ *
+ * Conventions: x = column (grows right), y = row (grows down); interior cells
+ * 0<=x<W, 0<=y<H; everything outside the interior is wall.  Arrays are
+ * row-major [y][x].  dir: 0 = +x, 1 = +y, 2 = -x, 3 = -y.
+ *
+ * Floating point: rewards and GAE are evaluated in double (the paper fixes no
+ * precision); rewards are rounded once to float at the end because the
+ * interface type is float32.
+ *
+ * Parity pins (tests/, "not gpu"): BFS shortest paths on hand-built mazes,
+ * scripted levels with known step counts and rewards, rotation / turn
+ * invariants, hand-derived observation crops, GAE closed forms, editor
+ * scripted cases.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* unit vectors of the four headings, index = dir */
+static const int DX[4] = { 1, 0, -1, 0 };
+static const int DY[4] = { 0, 1, 0, -1 };
+
+enum { CELL_WALL = 0, CELL_GOAL = 1, CELL_EMPTY = 2 };
+
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void orc_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* Is (x,y) a wall for the env whose grid is `walls` (H*W bytes)?  Anything
+ * outside the interior is wall: a WxH interior is a (W+2)x(H+2) MiniGrid
+ * room whose border is solid, and the view may reach further out still. */
+static int is_wall(const int8_t *walls, int H, int W, int x, int y)
+{
+    if (x < 0 || x >= W || y < 0 || y >= H) return 1;
+    return walls[y * W + x] != 0;
+}
+
+/* ---------------------------------------------------------------------------
+ * Student dynamics, one env, one step (Section 3: goal-reaching maze based on
+ * MiniGrid; episode cap, Section 4 "S5 policies": 250 steps).
+ *
+ *   t <- t+1
+ *   action 0: turn left, 1: turn right, 2: forward if the cell ahead is free;
+ *   any other value: nothing (the step still counts)
+ *   reached = agent on goal;  reward = 1 - 0.9*t/max_steps if reached else 0
+ *   done = reached or t >= max_steps
+ *   if done: agent back to the level's start pose, t <- 0 (same level)
+ * ------------------------------------------------------------------------- */
+static void step_one(int H, int W, int max_steps, const int8_t *walls,
+                     int sx, int sy, int sdir, int gx, int gy,
+                     int *x, int *y, int *dir, int *t, int action,
+                     float *reward, uint8_t *done)
+{
+    *t += 1;
+    if (action == 0) {
+        *dir = (*dir + 3) % 4;
+    } else if (action == 1) {
+        *dir = (*dir + 1) % 4;
+    } else if (action == 2) {
+        int cx = *x + DX[*dir];
+        int cy = *y + DY[*dir];
+        if (!is_wall(walls, H, W, cx, cy)) {
+            *x = cx;
+            *y = cy;
+        }
+    }
+    int reached = (*x == gx && *y == gy);
+    double r = 0.0;
+    if (reached) r = 1.0 - 0.9 * (double)(*t) / (double)max_steps;
+    *reward = (float)r;
+    int d = reached || (*t >= max_steps);
+    *done = (uint8_t)d;
+    if (d) {
+        *x = sx;
+        *y = sy;
+        *dir = sdir;
+        *t = 0;
+    }
+}
+
+/* ---------------------------------------------------------------------------
+ * Egocentric k x k observation of one env in its current pose (Section 3:
+ * "partially-observable").  View row 0 is the row farthest ahead, the agent
+ * sits in row k-1, column k/2, looking towards row 0.  View column 0 is on
+ * the agent's far left.  Each cell is one-hot over (wall, goal, empty); the
+ * agent's own cell shows what it stands on (empty, or goal never happens after
+ * a step because that ends the episode).  No occlusion.
+ * ------------------------------------------------------------------------- */
+static void render_one(int H, int W, int k, const int8_t *walls, int gx, int gy,
+                       int x, int y, int dir, int8_t *obs /* [k][k][3] */)
+{
+    int rdir = (dir + 1) % 4; /* heading of the agent's right hand */
+    for (int r = 0; r < k; ++r) {
+        for (int c = 0; c < k; ++c) {
+            int ahead = (k - 1) - r;
+            int side = c - k / 2;
+            int wx = x + ahead * DX[dir] + side * DX[rdir];
+            int wy = y + ahead * DY[dir] + side * DY[rdir];
+            int cell;
+            if (is_wall(walls, H, W, wx, wy)) cell = CELL_WALL;
+            else if (wx == gx && wy == gy) cell = CELL_GOAL;
+            else cell = CELL_EMPTY;
+            int8_t *o = obs + ((size_t)r * k + c) * 3;
+            o[0] = (cell == CELL_WALL);
+            o[1] = (cell == CELL_GOAL);
+            o[2] = (cell == CELL_EMPTY);
+        }
+    }
+}
+
+/* Batched single step over N envs.  State (xy, dir, t) is updated in place. */
+void orc_maze_step(int N, int H, int W, int max_steps,
+                   const int8_t *walls /* [N,H,W] */,
+                   const int32_t *start_xy /* [N,2] */, const int8_t *start_dir /* [N] */,
+                   const int32_t *goal_xy /* [N,2] */,
+                   int32_t *xy /* [N,2] */, int8_t *dir /* [N] */, int32_t *t /* [N] */,
+                   const int8_t *actions /* [N] */,
+                   float *reward /* [N] */, uint8_t *done /* [N] */)
+{
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        int x = xy[2 * n], y = xy[2 * n + 1], d = dir[n], tt = t[n];
+        step_one(H, W, max_steps, walls + (size_t)n * H * W,
+                 start_xy[2 * n], start_xy[2 * n + 1], start_dir[n],
+                 goal_xy[2 * n], goal_xy[2 * n + 1],
+                 &x, &y, &d, &tt, actions[n], &reward[n], &done[n]);
+        xy[2 * n] = x;
+        xy[2 * n + 1] = y;
+        dir[n] = (int8_t)d;
+        t[n] = tt;
+    }
+}
+
+/* Batched observation of the current state. */
+void orc_maze_render(int N, int H, int W, int k,
+                     const int8_t *walls, const int32_t *goal_xy,
+                     const int32_t *xy, const int8_t *dir,
+                     int8_t *obs /* [N,k,k,3] */)
+{
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        render_one(H, W, k, walls + (size_t)n * H * W, goal_xy[2 * n], goal_xy[2 * n + 1],
+                   xy[2 * n], xy[2 * n + 1], dir[n], obs + (size_t)n * k * k * 3);
+    }
+}
+
+/* n_steps of (step, then observe the state after the step and its reset).
+ * actions [n_steps,N]; reward, done [n_steps,N]; obs [n_steps,N,k,k,3] or NULL. */
+void orc_maze_rollout(int N, int H, int W, int k, int max_steps, int n_steps,
+                      const int8_t *walls, const int32_t *start_xy, const int8_t *start_dir,
+                      const int32_t *goal_xy, int32_t *xy, int8_t *dir, int32_t *t,
+                      const int8_t *actions, float *reward, uint8_t *done, int8_t *obs)
+{
+    for (int s = 0; s < n_steps; ++s) {
+        orc_maze_step(N, H, W, max_steps, walls, start_xy, start_dir, goal_xy, xy, dir, t,
+                      actions + (size_t)s * N, reward + (size_t)s * N, done + (size_t)s * N);
+        if (obs)
+            orc_maze_render(N, H, W, k, walls, goal_xy, xy, dir,
+                            obs + (size_t)s * N * k * k * 3);
+    }
+}
+
+/* ---------------------------------------------------------------------------
+ * Teacher's design MDP (Section 2.2: the teacher's decision process is its own
+ * environment whose final instance becomes the student's level).
+ *
+ * Placement order: n_walls wall steps, then the agent, then the goal.  Action
+ * = cell index in row-major order, clamped into range.  A wall on a wall
+ * changes nothing; the agent clears the wall under it; a goal aimed at the
+ * agent's cell moves on cyclically to the next cell, and clears a wall under
+ * it.  After the goal is placed further steps change nothing.
+ *
+ * agent_xy / goal_xy hold -1,-1 until placed.
+ * ------------------------------------------------------------------------- */
+static void editor_step_one(int H, int W, int n_walls, int8_t *walls,
+                            int32_t *agent_xy, int8_t *agent_dir, int32_t *goal_xy,
+                            int32_t *t, int dir_init, int action)
+{
+    int cells = H * W;
+    int a = action;
+    if (a < 0) a = 0;
+    if (a > cells - 1) a = cells - 1;
+    if (*t < n_walls) {
+        walls[a] = 1;
+    } else if (*t == n_walls) {
+        agent_xy[0] = a % W;
+        agent_xy[1] = a / W;
+        *agent_dir = (int8_t)dir_init;
+        walls[a] = 0;
+    } else if (*t == n_walls + 1) {
+        int j = a;
+        while (j % W == agent_xy[0] && j / W == agent_xy[1]) j = (j + 1) % cells;
+        goal_xy[0] = j % W;
+        goal_xy[1] = j / W;
+        walls[j] = 0;
+    }
+    if (*t < n_walls + 2) *t += 1;
+}
+
+/* Full-grid teacher observation: channels (wall, goal, agent). */
+static void editor_obs_one(int H, int W, const int8_t *walls, const int32_t *agent_xy,
+                           const int32_t *goal_xy, int8_t *obs /* [H][W][3] */)
+{
+    for (int y = 0; y < H; ++y) {
+        for (int x = 0; x < W; ++x) {
+            int8_t *o = obs + ((size_t)y * W + x) * 3;
+            o[0] = walls[y * W + x] != 0;
+            o[1] = (goal_xy[0] == x && goal_xy[1] == y);
+            o[2] = (agent_xy[0] == x && agent_xy[1] == y);
+        }
+    }
+}
+
+void orc_editor_reset(int N, int H, int W, int8_t *walls, int32_t *agent_xy, int8_t *agent_dir,
+                      int32_t *goal_xy, int32_t *t)
+{
+    for (int n = 0; n < N; ++n) {
+        for (int c = 0; c < H * W; ++c) walls[(size_t)n * H * W + c] = 0;
+        agent_xy[2 * n] = agent_xy[2 * n + 1] = -1;
+        goal_xy[2 * n] = goal_xy[2 * n + 1] = -1;
+        agent_dir[n] = 0;
+        t[n] = 0;
+    }
+}
+
+/* n_steps editor steps.  actions [n_steps,N] int32; obs [n_steps,N,H,W,3];
+ * t_out, done [n_steps,N] (either may be NULL). */
+void orc_editor_rollout(int N, int H, int W, int n_walls, int n_steps,
+                        const int8_t *dir_init /* [N] */,
+                        int8_t *walls, int32_t *agent_xy, int8_t *agent_dir, int32_t *goal_xy,
+                        int32_t *t, const int32_t *actions,
+                        int8_t *obs, int32_t *t_out, uint8_t *done)
+{
+    for (int s = 0; s < n_steps; ++s) {
+#pragma omp parallel for schedule(static)
+        for (int n = 0; n < N; ++n) {
+            editor_step_one(H, W, n_walls, walls + (size_t)n * H * W, agent_xy + 2 * n,
+                            agent_dir + n, goal_xy + 2 * n, t + n, dir_init[n],
+                            actions[(size_t)s * N + n]);
+            if (obs)
+                editor_obs_one(H, W, walls + (size_t)n * H * W, agent_xy + 2 * n, goal_xy + 2 * n,
+                               obs + ((size_t)s * N + n) * H * W * 3);
+            if (t_out) t_out[(size_t)s * N + n] = t[n];
+            if (done) done[(size_t)s * N + n] = (t[n] == n_walls + 2);
+        }
+    }
+}
+
+/* ---------------------------------------------------------------------------
+ * Generalised advantage estimation (Appendix "Choice of Architecture and
+ * Hyperparameters": PPO with GAE, gamma and lambda_GAE of the hyperparameter
+ * table).  Per env, backwards in time, in double:
+ *   delta_t = r_t + gamma * V_{t+1} * (1-d_t) - V_t
+ *   A_t     = delta_t + gamma*lambda * (1-d_t) * A_{t+1},   A_T = 0
+ *   ret_t   = A_t + V_t
+ * d_t = 1 cuts both the bootstrap and the trace (a time-out counts as an end).
+ * ------------------------------------------------------------------------- */
+void orc_gae(int T, int N, double gamma, double lambda,
+             const float *rewards /* [T,N] */, const float *values /* [T+1,N] */,
+             const uint8_t *dones /* [T,N] */,
+             double *adv /* [T,N] */, double *ret /* [T,N] or NULL */)
+{
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        double A = 0.0;
+        for (int s = T - 1; s >= 0; --s) {
+            size_t i = (size_t)s * N + n;
+            double nd = dones[i] ? 0.0 : 1.0;
+            double delta = (double)rewards[i] + gamma * (double)values[i + N] * nd
+                           - (double)values[i];
+            A = delta + gamma * lambda * nd * A;
+            adv[i] = A;
+            if (ret) ret[i] = A + (double)values[i];
+        }
+    }
+}
