@@ -1,0 +1,167 @@
+/*
+ * maze_cdna4 -- batched MiniGrid-style maze environment for AMD CDNA4 (gfx950).
+ *
+ * C ABI of the data-parallel hot path of unsupervised-environment-design
+ * training on mazes (the "AMaze" benchmark of the minimax paper, Section 3):
+ * the student's step + egocentric observation, the teacher's sequential level
+ * editor (Section 2.2), and generalised advantage estimation (appendix on
+ * hyperparameters).  All compute runs in HIP kernels; this header has no C++
+ * or framework types in it.
+ *
+ * Conventions shared by every call
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; the library
+ *     never frees or retains them beyond the call, except the workspace given
+ *     to *_create, which must stay alive until *_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls validate their arguments on the host, enqueue kernels on `stream`
+ *     and return without synchronising.  Two calls on the same context must be
+ *     ordered by the caller (same stream, or events).
+ *   - Return value: MAZE_OK (0) or a negative MAZE_E* code; nothing aborts or
+ *     throws.  maze_strerror() names a code.
+ *   - Coordinates: x = column (grows right), y = row (grows down); interior
+ *     cells 0 <= x < W, 0 <= y < H; everything outside the interior is wall.
+ *     Heading: 0 = +x, 1 = +y, 2 = -x, 3 = -y.  Batched arrays are env-major
+ *     within a time step: [n_steps][N]...
+ */
+#ifndef MAZE_CDNA4_H
+#define MAZE_CDNA4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MAZE_OK       0
+#define MAZE_EINVAL  (-1)   /* argument out of range                         */
+#define MAZE_ENULL   (-2)   /* required pointer is NULL                       */
+#define MAZE_ESIZE   (-3)   /* grid/view too large for the packed layout, or
+                               workspace too small                             */
+#define MAZE_EHIP    (-4)   /* a HIP runtime call failed                      */
+
+typedef struct maze_ctx maze_ctx;       /* small host-side handle */
+typedef struct editor_ctx editor_ctx;   /* small host-side handle */
+
+const char *maze_strerror(int code);
+
+/* ------------------------------------------------------------------ student
+ * Static parameters (paper Section 2.2: fixed at initialisation): number of
+ * envs N, interior size H x W, odd view size k, episode cap max_steps (250 in
+ * the paper's experiments, Section 4).  Limits: W + 2(k-1) <= 64 and
+ * H + 2(k-1) <= 64 (the walls are kept as one machine word per padded row),
+ * 1 <= max_steps < 2^24.
+ *
+ * maze_workspace_bytes: device bytes maze_create needs for these parameters.
+ * maze_create: builds the host handle; d_workspace must be 256-byte aligned.
+ * The state is undefined until the first maze_reset_to_levels.               */
+int maze_workspace_bytes(int N, int H, int W, int view, size_t *out);
+int maze_create(maze_ctx **out, int N, int H, int W, int view, int max_steps,
+                void *d_workspace, size_t workspace_bytes);
+int maze_destroy(maze_ctx *ctx);
+
+/* Set every env's free parameters (its level) and put the agent on the start
+ * pose with t = 0 -- the state setter of Section 2.2, and the hand-off target
+ * of the teacher's final design.
+ *   d_walls     int8  [N,H,W]  non-zero = wall
+ *   d_agent_xy  int32 [N,2]    start (x,y)
+ *   d_agent_dir int8  [N]      start heading
+ *   d_goal_xy   int32 [N,2]
+ * Preconditions (caller's): agent and goal inside the interior, on free,
+ * distinct cells.  For memory safety coordinates are clamped into the interior
+ * and the heading is taken modulo 4.                                          */
+int maze_reset_to_levels(maze_ctx *ctx, const int8_t *d_walls, const int32_t *d_agent_xy,
+                         const int8_t *d_agent_dir, const int32_t *d_goal_xy, void *stream);
+
+/* n_steps >= 1 environment steps for all N envs (Section 3: goal-reaching maze
+ * with MiniGrid semantics).  Per env and step:
+ *   t += 1; action 0 = turn left, 1 = turn right, 2 = forward unless the cell
+ *   ahead is a wall; any other value changes nothing but still counts a step;
+ *   reached = agent on goal; reward = 1 - 0.9*t/max_steps if reached else 0;
+ *   done = reached or t >= max_steps; if done the agent returns to the level's
+ *   start pose and t = 0 (same level).
+ *   d_actions int8  [n_steps,N]
+ *   d_reward  float [n_steps,N]
+ *   d_done    uint8 [n_steps,N]
+ *   d_obs     int8  [n_steps,N,k,k,3] or NULL: observation AFTER each step (of
+ *             the reset state when done), same encoding as maze_render_obs.
+ * n_steps > 1 runs the whole open-loop rollout in one launch with the state
+ * held on chip; n_steps = 1 is the plain step a policy loop calls.            */
+int maze_step(maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
+              uint8_t *d_done, int8_t *d_obs, void *stream);
+
+/* Egocentric k x k observation of the current state (Section 3: partially
+ * observable).  d_obs int8 [N,k,k,3]; view row 0 is farthest ahead, the agent
+ * is at row k-1, column k/2, facing row 0; column 0 is on its left.  Channels
+ * are one-hot (wall, goal, empty); the agent's own cell reads empty; cells
+ * outside the interior are wall; no occlusion.                                */
+int maze_render_obs(maze_ctx *ctx, int8_t *d_obs, void *stream);
+
+/* State / level getters (Section 2.2).  d_xy int32 [N,2], d_dir int8 [N],
+ * d_t int32 [N]; level arrays as in maze_reset_to_levels.  Any pointer may be
+ * NULL to skip that output.                                                   */
+int maze_get_state(maze_ctx *ctx, int32_t *d_xy, int8_t *d_dir, int32_t *d_t, void *stream);
+int maze_get_levels(maze_ctx *ctx, int8_t *d_walls, int32_t *d_agent_xy, int8_t *d_agent_dir,
+                    int32_t *d_goal_xy, void *stream);
+
+/* Choose the kernel family used by maze_step / maze_render_obs: 0 = automatic
+ * (the tiled store-layout kernels when the shape allows, else the per-cell
+ * kernel), 1 = always the per-cell kernel.  Results are identical; meant for
+ * tests and measurements.                                                     */
+int maze_set_kernel_variant(maze_ctx *ctx, int variant);
+
+/* ------------------------------------------------------------------- teacher
+ * The teacher's design MDP (Section 2.2): an empty H x W grid on which the
+ * teacher places n_walls walls, then the agent, then the goal, one cell index
+ * (row-major, y*W + x) per step.  Limits: H*W <= 4096, n_walls >= 0.
+ *
+ * Per env and step, with t the number of placements made so far:
+ *   the action is clamped into [0, H*W);
+ *   t <  n_walls   : the cell becomes a wall (again, if it already is one);
+ *   t == n_walls   : the agent is put there with heading agent_dir_init, a wall
+ *                    on that cell is removed;
+ *   t == n_walls+1 : the goal is put there; if that is the agent's cell the goal
+ *                    moves on to the next cell in row-major order (cyclically);
+ *                    a wall on the goal's cell is removed;
+ *   t <- t+1 while t < n_walls+2; later steps change nothing.
+ *   done = (t == n_walls+2).                                                  */
+int editor_workspace_bytes(int N, int H, int W, size_t *out);
+int editor_create(editor_ctx **out, int N, int H, int W, int n_walls,
+                  void *d_workspace, size_t workspace_bytes);
+int editor_destroy(editor_ctx *ctx);
+
+/* Empty grid, nothing placed, t = 0; latches the heading each env's agent will
+ * get (d_agent_dir_init int8 [N], taken modulo 4).                            */
+int editor_reset(editor_ctx *ctx, const int8_t *d_agent_dir_init, void *stream);
+
+/*   d_actions int32 [n_steps,N]
+ *   d_obs     int8  [n_steps,N,H,W,3] or NULL: full grid after each step,
+ *             channels (wall, goal, agent)
+ *   d_t       int32 [n_steps,N] or NULL: t after each step
+ *   d_done    uint8 [n_steps,N] or NULL                                        */
+int editor_step(editor_ctx *ctx, const int32_t *d_actions, int n_steps, int8_t *d_obs,
+                int32_t *d_t, uint8_t *d_done, void *stream);
+
+/* The designed levels in exactly the layout maze_reset_to_levels takes (the
+ * reset_student hand-off of Section 2.2).  Before the agent / goal is placed
+ * its coordinates read (-1,-1) and the heading 0.                             */
+int editor_get_levels(editor_ctx *ctx, int8_t *d_walls, int32_t *d_agent_xy,
+                      int8_t *d_agent_dir, int32_t *d_goal_xy, void *stream);
+
+/* ----------------------------------------------------------------------- GAE
+ * Generalised advantage estimation (PPO with GAE, appendix on hyperparameters;
+ * gamma, lambda as in the hyperparameter table).  Per env, backwards in time:
+ *   delta_t = r_t + gamma * V_{t+1} * (1 - d_t) - V_t
+ *   A_t     = delta_t + gamma * lambda * (1 - d_t) * A_{t+1},   A_T = 0
+ *   ret_t   = A_t + V_t
+ *   d_rewards float [T,N], d_values float [T+1,N], d_dones uint8 [T,N],
+ *   d_adv float [T,N], d_returns float [T,N] or NULL.
+ * The recurrence is carried in double and rounded to float on output.         */
+int compute_gae(const float *d_rewards, const float *d_values, const uint8_t *d_dones,
+                int T, int N, double gamma, double lambda, float *d_adv, float *d_returns,
+                void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MAZE_CDNA4_H */

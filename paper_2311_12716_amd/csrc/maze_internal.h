@@ -1,0 +1,75 @@
+// Internal definitions shared by the translation units of libmaze_cdna4.
+// Not part of the public boundary (see include/maze_cdna4.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "maze_cdna4.h"
+
+#define MAZE_HIP_CHECK(expr)                      \
+    do {                                          \
+        hipError_t e__ = (expr);                  \
+        if (e__ != hipSuccess) return MAZE_EHIP;  \
+    } while (0)
+
+static inline size_t maze_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---------------------------------------------------------------------------
+// Student env: device-side layout.
+//
+// The wall grid is padded with P = k-1 rings of wall cells so that a k x k view
+// never leaves the array, and kept as one bit per cell, one machine word per
+// padded row.  Four copies are stored, one per heading d, each rotated so that
+// heading d points towards smaller row indices ("up") and the agent's right
+// hand towards larger bit indices.  In frame d an agent at padded (X,Y) sits at
+//     d = 3 (-y): (Xd,Yd) = (X,        Y       )   rows HP, bits WP
+//     d = 0 (+x): (Xd,Yd) = (Y,        WP-1-X  )   rows WP, bits HP
+//     d = 1 (+y): (Xd,Yd) = (WP-1-X,   HP-1-Y  )   rows HP, bits WP
+//     d = 2 (-x): (Xd,Yd) = (HP-1-Y,   X       )   rows WP, bits HP
+// and its view is rows Yd-(k-1)..Yd, bits Xd-k/2..Xd+k/2 of grid d, whatever d.
+// The dynamic state is kept in the frame of the current heading:
+//     pose = Xd | Yd << 8 | d << 16.
+// ---------------------------------------------------------------------------
+struct StudentDev {
+    int N, H, W, k, max_steps;
+    int P, HP, WP, SP;      // pad, padded height/width, rows stored per rotated grid
+    uint32_t *pose;         // [N] current pose (frame of current heading)
+    uint32_t *tcount;       // [N] steps since the episode began
+    uint32_t *start;        // [N] start pose (frame of the start heading)
+    uint32_t *goalrot;      // [N][4] goal position Xd | Yd << 8 in each frame
+    void *grids;            // [N][4][SP] words (uint32_t or uint64_t)
+    double reward_slope;    // 0.9 / max_steps
+};
+
+struct maze_ctx {
+    StudentDev dev;
+    int word64;             // rows need 64-bit words
+    int variant;            // 0 auto, 1 per-cell kernels only
+    int device;
+    size_t workspace_bytes;
+};
+
+// ---------------------------------------------------------------------------
+// Teacher editor env: device-side layout.
+//
+// Per env the grid is kept as the bit stream its observation expands from:
+// bit 3*c + ch of the stream is channel ch (0 wall, 1 goal, 2 agent) of cell c.
+// ---------------------------------------------------------------------------
+struct EditorDev {
+    int N, H, W, n_walls;
+    int cells;              // H*W
+    int SW;                 // stream dwords per env = ceil(3*cells/32)
+    uint32_t *stream;       // [N][SW]
+    int32_t *agent_cell;    // [N], -1 until placed
+    int32_t *goal_cell;     // [N], -1 until placed
+    int32_t *t;             // [N]
+    int8_t *dir_init;       // [N]
+};
+
+struct editor_ctx {
+    EditorDev dev;
+    int device;
+    size_t workspace_bytes;
+};

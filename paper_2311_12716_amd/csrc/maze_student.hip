@@ -1,0 +1,367 @@
+// Student maze env: host entry points, level packing, per-cell kernels and the
+// getters.  The tiled store-layout rollout kernels live in maze_student_tiled.hip.
+#include "maze_internal.h"
+#include "maze_student_device.h"
+
+#include <new>
+
+// ------------------------------------------------------------------ host side
+static int student_dims(int N, int H, int W, int view, StudentDev *d, int *word64)
+{
+    if (N <= 0 || H <= 0 || W <= 0 || view <= 0 || (view & 1) == 0) return MAZE_EINVAL;
+    int P = view - 1;
+    int HP = H + 2 * P, WP = W + 2 * P;
+    if (HP > 64 || WP > 64) return MAZE_ESIZE;
+    d->N = N; d->H = H; d->W = W; d->k = view;
+    d->P = P; d->HP = HP; d->WP = WP; d->SP = HP > WP ? HP : WP;
+    *word64 = (d->SP > 32);
+    return MAZE_OK;
+}
+
+struct StudentLayout { size_t pose, tcount, start, goalrot, grids, total; };
+
+static StudentLayout student_layout(const StudentDev &d, int word64)
+{
+    StudentLayout L;
+    size_t off = 0;
+    size_t n = (size_t)d.N;
+    L.pose = off;    off = maze_align_up(off + n * 4, 256);
+    L.tcount = off;  off = maze_align_up(off + n * 4, 256);
+    L.start = off;   off = maze_align_up(off + n * 4, 256);
+    L.goalrot = off; off = maze_align_up(off + n * 16, 256);
+    L.grids = off;   off = maze_align_up(off + n * 4 * d.SP * (word64 ? 8 : 4), 256);
+    L.total = off;
+    return L;
+}
+
+extern "C" int maze_workspace_bytes(int N, int H, int W, int view, size_t *out)
+{
+    if (!out) return MAZE_ENULL;
+    StudentDev d;
+    int w64;
+    int rc = student_dims(N, H, W, view, &d, &w64);
+    if (rc != MAZE_OK) return rc;
+    *out = student_layout(d, w64).total;
+    return MAZE_OK;
+}
+
+extern "C" int maze_create(maze_ctx **out, int N, int H, int W, int view, int max_steps,
+                           void *d_workspace, size_t workspace_bytes)
+{
+    if (!out) return MAZE_ENULL;
+    *out = nullptr;
+    if (!d_workspace) return MAZE_ENULL;
+    StudentDev d;
+    int w64;
+    int rc = student_dims(N, H, W, view, &d, &w64);
+    if (rc != MAZE_OK) return rc;
+    if (max_steps < 1 || max_steps >= (1 << 24)) return MAZE_EINVAL;
+    if (((uintptr_t)d_workspace & 255) != 0) return MAZE_EINVAL;
+    StudentLayout L = student_layout(d, w64);
+    if (workspace_bytes < L.total) return MAZE_ESIZE;
+    maze_ctx *c = new (std::nothrow) maze_ctx;
+    if (!c) return MAZE_EINVAL;
+    char *ws = (char *)d_workspace;
+    d.max_steps = max_steps;
+    d.pose = (uint32_t *)(ws + L.pose);
+    d.tcount = (uint32_t *)(ws + L.tcount);
+    d.start = (uint32_t *)(ws + L.start);
+    d.goalrot = (uint32_t *)(ws + L.goalrot);
+    d.grids = ws + L.grids;
+    d.reward_slope = 0.9 / (double)max_steps;
+    c->dev = d;
+    c->word64 = w64;
+    c->variant = 0;
+    c->workspace_bytes = workspace_bytes;
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return MAZE_EHIP; }
+    *out = c;
+    return MAZE_OK;
+}
+
+extern "C" int maze_destroy(maze_ctx *ctx)
+{
+    if (!ctx) return MAZE_ENULL;
+    delete ctx;
+    return MAZE_OK;
+}
+
+extern "C" int maze_set_kernel_variant(maze_ctx *ctx, int variant)
+{
+    if (!ctx) return MAZE_ENULL;
+    if (variant < 0 || variant > 1) return MAZE_EINVAL;
+    ctx->variant = variant;
+    return MAZE_OK;
+}
+
+// ------------------------------------------------------------- level packing
+// One thread per (env, heading, row of the rotated grid): builds that row's word.
+template <typename Word>
+__global__ void k_pack_grids(StudentDev p, const int8_t *__restrict__ walls)
+{
+    long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    long long total = (long long)p.N * 4 * p.SP;
+    if (gid >= total) return;
+    int row = (int)(gid % p.SP);
+    int d = (int)((gid / p.SP) & 3);
+    int n = (int)(gid / ((long long)p.SP * 4));
+    int rows = (d & 1) ? p.HP : p.WP;
+    int bits = (d & 1) ? p.WP : p.HP;
+    Word w = ~(Word)0;                       // rows beyond the frame are solid
+    if (row < rows) {
+        w = 0;
+        const int8_t *g = walls + (size_t)n * p.H * p.W;
+        for (int b = 0; b < bits; ++b) {
+            int X, Y;
+            frame_to_padded(p, d, b, row, X, Y);
+            int x = X - p.P, y = Y - p.P;
+            bool wall = (x < 0 || x >= p.W || y < 0 || y >= p.H) ? true : (g[y * p.W + x] != 0);
+            if (wall) w |= (Word)1 << b;
+        }
+        for (int b = bits; b < (int)(sizeof(Word) * 8); ++b) w |= (Word)1 << b;
+    }
+    ((Word *)p.grids)[gid] = w;
+}
+
+// One thread per env: start pose, goal in the four frames, state = start, t = 0.
+__global__ void k_pack_poses(StudentDev p, const int32_t *__restrict__ agent_xy,
+                             const int8_t *__restrict__ agent_dir,
+                             const int32_t *__restrict__ goal_xy)
+{
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= p.N) return;
+    int ax = min(max(agent_xy[2 * n], 0), p.W - 1) + p.P;
+    int ay = min(max(agent_xy[2 * n + 1], 0), p.H - 1) + p.P;
+    int gx = min(max(goal_xy[2 * n], 0), p.W - 1) + p.P;
+    int gy = min(max(goal_xy[2 * n + 1], 0), p.H - 1) + p.P;
+    int d = agent_dir[n] & 3;
+    int xd, yd;
+    padded_to_frame(p, d, ax, ay, xd, yd);
+    uint32_t s = (uint32_t)xd | ((uint32_t)yd << 8) | ((uint32_t)d << 16);
+    p.start[n] = s;
+    p.pose[n] = s;
+    p.tcount[n] = 0;
+    for (int f = 0; f < 4; ++f) {
+        padded_to_frame(p, f, gx, gy, xd, yd);
+        p.goalrot[4 * n + f] = (uint32_t)xd | ((uint32_t)yd << 8);
+    }
+}
+
+extern "C" int maze_reset_to_levels(maze_ctx *ctx, const int8_t *d_walls,
+                                    const int32_t *d_agent_xy, const int8_t *d_agent_dir,
+                                    const int32_t *d_goal_xy, void *stream)
+{
+    if (!ctx || !d_walls || !d_agent_xy || !d_agent_dir || !d_goal_xy) return MAZE_ENULL;
+    hipStream_t st = (hipStream_t)stream;
+    const StudentDev &p = ctx->dev;
+    long long total = (long long)p.N * 4 * p.SP;
+    unsigned blocks = (unsigned)((total + 255) / 256);
+    if (ctx->word64)
+        hipLaunchKernelGGL(k_pack_grids<uint64_t>, dim3(blocks), dim3(256), 0, st, p, d_walls);
+    else
+        hipLaunchKernelGGL(k_pack_grids<uint32_t>, dim3(blocks), dim3(256), 0, st, p, d_walls);
+    hipLaunchKernelGGL(k_pack_poses, dim3((p.N + 255) / 256), dim3(256), 0, st, p, d_agent_xy,
+                       d_agent_dir, d_goal_xy);
+    MAZE_HIP_CHECK(hipGetLastError());
+    return MAZE_OK;
+}
+
+// ---------------------------------------------------------- per-cell kernels
+// One lane per env, state in registers across the n_steps loop, walls read from
+// the packed grids in global memory (they stay in L2), observation written one
+// byte at a time.  Correct for every supported shape; the tiled kernels are
+// the fast path.
+template <typename Word>
+__device__ __forceinline__ void render_cells(const StudentDev &p, const Word *__restrict__ grid_n,
+                                             uint32_t pose, uint32_t goal, int8_t *__restrict__ o)
+{
+    const int k = p.k, h = k >> 1;
+    int xd = pose & 255, yd = (pose >> 8) & 255, d = (pose >> 16) & 3;
+    int gxd = goal & 255, gyd = (goal >> 8) & 255;
+    const Word *g = grid_n + d * p.SP;
+    for (int r = 0; r < k; ++r) {
+        int row = yd - (k - 1) + r;
+        Word w = g[row] >> (xd - h);
+        for (int c = 0; c < k; ++c) {
+            int wall = (int)((w >> c) & 1);
+            int isgoal = (!wall) && (row == gyd) && (xd - h + c == gxd);
+            o[0] = (int8_t)wall;
+            o[1] = (int8_t)isgoal;
+            o[2] = (int8_t)(!wall && !isgoal);
+            o += 3;
+        }
+    }
+}
+
+template <typename Word>
+__global__ void k_student_percell(StudentDev p, const int8_t *__restrict__ actions, int n_steps,
+                                  float *__restrict__ reward, uint8_t *__restrict__ done,
+                                  int8_t *__restrict__ obs)
+{
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= p.N) return;
+    const Word *grid_n = (const Word *)p.grids + (size_t)n * 4 * p.SP;
+    uint32_t pose = p.pose[n];
+    uint32_t t = p.tcount[n];
+    const uint32_t start = p.start[n];
+    uint32_t gr[4];
+    for (int f = 0; f < 4; ++f) gr[f] = p.goalrot[4 * n + f];
+    const size_t obs_env = (size_t)p.k * p.k * 3;
+    for (int s = 0; s < n_steps; ++s) {
+        int a = actions[(size_t)s * p.N + n];
+        int xd = pose & 255, yd = (pose >> 8) & 255, d = (pose >> 16) & 3;
+        bool blocked = (grid_n[d * p.SP + yd - 1] >> xd) & 1;
+        pose = student_move(p, pose, a, blocked);
+        t += 1;
+        d = (pose >> 16) & 3;
+        bool reached = (pose & 0xFFFF) == gr[d];
+        float r = reached ? (float)(1.0 - (double)t * p.reward_slope) : 0.0f;
+        bool dn = reached || t >= (uint32_t)p.max_steps;
+        if (dn) { pose = start; t = 0; }
+        reward[(size_t)s * p.N + n] = r;
+        done[(size_t)s * p.N + n] = dn ? 1 : 0;
+        if (obs)
+            render_cells<Word>(p, grid_n, pose, gr[(pose >> 16) & 3],
+                               obs + ((size_t)s * p.N + n) * obs_env);
+    }
+    p.pose[n] = pose;
+    p.tcount[n] = t;
+}
+
+template <typename Word>
+__global__ void k_render_percell(StudentDev p, int8_t *__restrict__ obs)
+{
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= p.N) return;
+    const Word *grid_n = (const Word *)p.grids + (size_t)n * 4 * p.SP;
+    uint32_t pose = p.pose[n];
+    uint32_t goal = p.goalrot[4 * n + ((pose >> 16) & 3)];
+    render_cells<Word>(p, grid_n, pose, goal, obs + (size_t)n * p.k * p.k * 3);
+}
+
+// Implemented in maze_student_tiled.hip: returns 1 if it launched, 0 if the shape
+// is not covered by a tiled kernel.
+int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_steps,
+                         float *d_reward, uint8_t *d_done, int8_t *d_obs, hipStream_t st);
+
+extern "C" int maze_step(maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
+                         uint8_t *d_done, int8_t *d_obs, void *stream)
+{
+    if (!ctx || !d_actions || !d_reward || !d_done) return MAZE_ENULL;
+    if (n_steps < 1) return MAZE_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const StudentDev &p = ctx->dev;
+    int launched = 0;
+    if (ctx->variant == 0)
+        launched = student_tiled_launch(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
+    if (!launched) {
+        dim3 grid((p.N + 63) / 64), block(64);
+        if (ctx->word64)
+            hipLaunchKernelGGL(k_student_percell<uint64_t>, grid, block, 0, st, p, d_actions,
+                               n_steps, d_reward, d_done, d_obs);
+        else
+            hipLaunchKernelGGL(k_student_percell<uint32_t>, grid, block, 0, st, p, d_actions,
+                               n_steps, d_reward, d_done, d_obs);
+    }
+    MAZE_HIP_CHECK(hipGetLastError());
+    return MAZE_OK;
+}
+
+extern "C" int maze_render_obs(maze_ctx *ctx, int8_t *d_obs, void *stream)
+{
+    if (!ctx || !d_obs) return MAZE_ENULL;
+    hipStream_t st = (hipStream_t)stream;
+    const StudentDev &p = ctx->dev;
+    dim3 grid((p.N + 63) / 64), block(64);
+    if (ctx->word64)
+        hipLaunchKernelGGL(k_render_percell<uint64_t>, grid, block, 0, st, p, d_obs);
+    else
+        hipLaunchKernelGGL(k_render_percell<uint32_t>, grid, block, 0, st, p, d_obs);
+    MAZE_HIP_CHECK(hipGetLastError());
+    return MAZE_OK;
+}
+
+// -------------------------------------------------------------------- getters
+__global__ void k_get_state(StudentDev p, int32_t *xy, int8_t *dir, int32_t *t)
+{
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= p.N) return;
+    uint32_t pose = p.pose[n];
+    int d = (pose >> 16) & 3, X, Y;
+    frame_to_padded(p, d, pose & 255, (pose >> 8) & 255, X, Y);
+    if (xy) { xy[2 * n] = X - p.P; xy[2 * n + 1] = Y - p.P; }
+    if (dir) dir[n] = (int8_t)d;
+    if (t) t[n] = (int32_t)p.tcount[n];
+}
+
+template <typename Word>
+__global__ void k_get_walls(StudentDev p, int8_t *walls)
+{
+    long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    long long total = (long long)p.N * p.H * p.W;
+    if (gid >= total) return;
+    int x = (int)(gid % p.W);
+    int y = (int)((gid / p.W) % p.H);
+    int n = (int)(gid / ((long long)p.W * p.H));
+    const Word *g3 = (const Word *)p.grids + ((size_t)n * 4 + 3) * p.SP;   // frame 3 = unrotated
+    walls[gid] = (int8_t)((g3[y + p.P] >> (x + p.P)) & 1);
+}
+
+__global__ void k_get_level_poses(StudentDev p, int32_t *agent_xy, int8_t *agent_dir,
+                                  int32_t *goal_xy)
+{
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= p.N) return;
+    uint32_t s = p.start[n];
+    int d = (s >> 16) & 3, X, Y;
+    frame_to_padded(p, d, s & 255, (s >> 8) & 255, X, Y);
+    if (agent_xy) { agent_xy[2 * n] = X - p.P; agent_xy[2 * n + 1] = Y - p.P; }
+    if (agent_dir) agent_dir[n] = (int8_t)d;
+    if (goal_xy) {
+        uint32_t g = p.goalrot[4 * n + 3];
+        goal_xy[2 * n] = (int)(g & 255) - p.P;
+        goal_xy[2 * n + 1] = (int)((g >> 8) & 255) - p.P;
+    }
+}
+
+extern "C" int maze_get_state(maze_ctx *ctx, int32_t *d_xy, int8_t *d_dir, int32_t *d_t,
+                              void *stream)
+{
+    if (!ctx) return MAZE_ENULL;
+    const StudentDev &p = ctx->dev;
+    hipLaunchKernelGGL(k_get_state, dim3((p.N + 255) / 256), dim3(256), 0, (hipStream_t)stream, p,
+                       d_xy, d_dir, d_t);
+    MAZE_HIP_CHECK(hipGetLastError());
+    return MAZE_OK;
+}
+
+extern "C" int maze_get_levels(maze_ctx *ctx, int8_t *d_walls, int32_t *d_agent_xy,
+                               int8_t *d_agent_dir, int32_t *d_goal_xy, void *stream)
+{
+    if (!ctx) return MAZE_ENULL;
+    const StudentDev &p = ctx->dev;
+    hipStream_t st = (hipStream_t)stream;
+    if (d_walls) {
+        long long total = (long long)p.N * p.H * p.W;
+        unsigned blocks = (unsigned)((total + 255) / 256);
+        if (ctx->word64)
+            hipLaunchKernelGGL(k_get_walls<uint64_t>, dim3(blocks), dim3(256), 0, st, p, d_walls);
+        else
+            hipLaunchKernelGGL(k_get_walls<uint32_t>, dim3(blocks), dim3(256), 0, st, p, d_walls);
+    }
+    hipLaunchKernelGGL(k_get_level_poses, dim3((p.N + 255) / 256), dim3(256), 0, st, p, d_agent_xy,
+                       d_agent_dir, d_goal_xy);
+    MAZE_HIP_CHECK(hipGetLastError());
+    return MAZE_OK;
+}
+
+extern "C" const char *maze_strerror(int code)
+{
+    switch (code) {
+    case MAZE_OK: return "ok";
+    case MAZE_EINVAL: return "argument out of range";
+    case MAZE_ENULL: return "required pointer is NULL";
+    case MAZE_ESIZE: return "grid or view too large for the packed layout, or workspace too small";
+    case MAZE_EHIP: return "HIP runtime call failed";
+    default: return "unknown error code";
+    }
+}

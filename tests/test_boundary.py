@@ -1,0 +1,85 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol
+the header declares, the binding covers them, and host-side validation returns
+error codes without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "maze_cdna4.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(?:int|const char \*)\s*\*?\s*([a-z_0-9]+)\s*\(", text)
+    return sorted(set(names))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2311_12716_amd import binding
+    return binding.load_library()
+
+
+def test_header_declares_the_five_named_calls():
+    names = declared_functions()
+    for n in ("maze_reset_to_levels", "maze_step", "maze_render_obs", "editor_step", "compute_gae"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    from paper_2311_12716_amd import binding
+    names = declared_functions()
+    assert len(names) >= 17
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+    assert sorted(binding.SIGNATURES) == names
+
+
+def test_workspace_size_validation(lib):
+    n = ctypes.c_size_t(0)
+    assert lib.maze_workspace_bytes(32768, 13, 13, 5, ctypes.byref(n)) == 0 and n.value > 0
+    assert n.value % 256 == 0
+    assert lib.maze_workspace_bytes(8, 13, 13, 4, ctypes.byref(n)) == -1      # even view
+    assert lib.maze_workspace_bytes(0, 13, 13, 5, ctypes.byref(n)) == -1
+    assert lib.maze_workspace_bytes(8, 13, 0, 5, ctypes.byref(n)) == -1
+    assert lib.maze_workspace_bytes(8, 60, 60, 7, ctypes.byref(n)) == -3     # padded rows > 64 bits
+    assert lib.maze_workspace_bytes(8, 13, 13, 5, None) == -2
+    assert lib.editor_workspace_bytes(8, 13, 13, ctypes.byref(n)) == 0 and n.value > 0
+    assert lib.editor_workspace_bytes(8, 1, 1, ctypes.byref(n)) == -1
+    assert lib.editor_workspace_bytes(8, 100, 100, ctypes.byref(n)) == -3
+    assert lib.editor_workspace_bytes(-1, 13, 13, ctypes.byref(n)) == -1
+
+
+def test_create_rejects_bad_arguments_before_touching_the_gpu(lib):
+    h = ctypes.c_void_p()
+    assert lib.maze_create(ctypes.byref(h), 8, 13, 13, 5, 250, None, 1 << 20) == -2
+    assert lib.maze_create(None, 8, 13, 13, 5, 250, 256, 1 << 20) == -2
+    assert lib.maze_create(ctypes.byref(h), 8, 13, 13, 5, 0, 256, 1 << 20) == -1     # max_steps
+    assert lib.maze_create(ctypes.byref(h), 8, 13, 13, 5, 250, 257, 1 << 20) == -1   # alignment
+    assert lib.maze_create(ctypes.byref(h), 8, 13, 13, 5, 250, 256, 16) == -3        # too small
+    assert h.value is None
+    assert lib.editor_create(ctypes.byref(h), 8, 13, 13, 50, None, 1 << 20) == -2
+    assert lib.editor_create(ctypes.byref(h), 8, 13, 13, -1, 256, 1 << 20) == -1
+    assert lib.editor_create(ctypes.byref(h), 8, 13, 13, 50, 256, 16) == -3
+    assert lib.maze_destroy(None) == -2 and lib.editor_destroy(None) == -2
+    assert lib.maze_step(None, None, 1, None, None, None, None) == -2
+    assert lib.compute_gae(None, None, None, 1, 1, 0.9, 0.9, None, None, None) == -2
+    assert lib.compute_gae(256, 256, 256, 0, 1, 0.9, 0.9, 256, None, None) == -1
+
+
+def test_strerror_names_every_code(lib):
+    seen = {lib.maze_strerror(c) for c in (0, -1, -2, -3, -4)}
+    assert len(seen) == 5 and all(s for s in seen)
+    assert b"unknown" in lib.maze_strerror(-99)
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    from paper_2311_12716_amd import binding
+    with pytest.raises(binding.MazeError):
+        binding.compute_gae(torch.zeros(4, 2), torch.zeros(5, 2), torch.zeros(4, 2, dtype=torch.uint8),
+                            0.99, 0.95)

@@ -1,0 +1,235 @@
+"""GPU parity: the HIP library against the CPU oracle on the same seeded inputs.
+
+Bit-exact for positions, headings, step counters, observations, done flags and
+levels; rewards and GAE outputs within 1e-6 absolute (the oracle evaluates them
+in double, the library rounds to float).  All calls go through the C ABI.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_12716_amd import binding, workloads as wl
+from parity_util import (DEV, assert_rollout_equal, assert_state_equal, cpu_student, gpu_student,
+                         note, run_fused, to_gpu)
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-6
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_c1_step_by_step_and_fused(variant):
+    """Config 1: 32 envs, 13x13, 25 walls, 1000 steps: the per-step calls a policy loop
+    makes (maze_step n=1 + maze_render_obs) and the one-launch rollout agree with the oracle
+    and with each other."""
+    w = wl.config(1)
+    note(f"C1 variant {variant}")
+    env, o = gpu_student(w, variant), cpu_student(w)
+    acts = to_gpu(w.actions)
+    for s in range(w.T):
+        r, d, _ = env.step(acts[s:s + 1], want_obs=False)
+        obs = env.render_obs()
+        orr, od, oobs = o.step(w.actions[s:s + 1], 1)
+        assert (d.cpu().numpy() == od).all(), f"done differs at step {s}"
+        assert np.abs(r.cpu().numpy().astype(np.float64) - orr).max() <= TOL
+        assert (obs.cpu().numpy() == oobs[0]).all(), f"obs differs at step {s}"
+        if s % 100 == 0:
+            assert_state_equal(env, o)
+    assert_state_equal(env, o)
+    run_fused(w, variant)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_c2_rollout_and_gae(variant):
+    """Config 2: 4096 envs, 0..60 walls, 256 steps, then GAE on the rollout's own rewards
+    and dones with uniform value estimates."""
+    w = wl.config(2)
+    note(f"C2 variant {variant}")
+    env, o, (r, d, obs), (orr, od, oobs) = run_fused(w, variant)
+    assert obs.shape == (256, 4096, 5, 5, 3) and obs.dtype == torch.int8
+    adv, ret = binding.compute_gae(r, to_gpu(w.values), d, w.gamma, w.lam)
+    oadv, oret = oracle.compute_gae(orr, w.values, od, w.gamma, w.lam)
+    assert np.abs(adv.cpu().numpy() - oadv).max() <= TOL
+    assert np.abs(ret.cpu().numpy() - oret).max() <= TOL
+
+
+def test_c3_full_size():
+    """Config 3 at full size (32768 envs x 256 steps), the shape the benchmark times."""
+    w = wl.config(3)
+    note("C3 full size")
+    env, o, (r, d, obs), (orr, od, oobs) = run_fused(w)
+    assert int(d.sum()) == int(od.sum()) > 0
+
+
+def test_c4_editor_full_size_and_handoff():
+    """Config 4: 32768 editor envs x 52 placements, full-grid observation and timestep each
+    step, then the designed levels go into maze_reset_to_levels and come back unchanged."""
+    w = wl.config(4)
+    note("C4 full size")
+    ed = binding.EditorEnv(w.N, w.H, w.W, w.n_walls, device=DEV)
+    ed.reset(to_gpu(w.agent_dir_init))
+    obs, t, done = ed.step(to_gpu(w.actions))
+    oe = oracle.EditorOracle(w.N, w.H, w.W, w.n_walls)
+    oe.reset(w.agent_dir_init)
+    oobs, ot, odone = oe.step(w.actions, w.T)
+    assert (t.cpu().numpy() == ot).all() and (done.cpu().numpy() == odone).all()
+    for s in range(w.T):                       # step by step keeps host memory bounded
+        assert (obs[s].cpu().numpy() == oobs[s]).all(), f"editor obs differs at step {s}"
+    walls, axy, ad, gxy = ed.get_levels()
+    lv = oe.get_levels()
+    assert (walls.cpu().numpy() == lv.walls).all() and (axy.cpu().numpy() == lv.agent_xy).all()
+    assert (ad.cpu().numpy() == lv.agent_dir).all() and (gxy.cpu().numpy() == lv.goal_xy).all()
+    # hand-off: the same device arrays become the student's levels
+    env = binding.MazeEnv(w.N, w.H, w.W, 5, 250, device=DEV)
+    env.reset_to_levels(walls, axy, ad, gxy)
+    w2, a2, d2, g2 = env.get_levels()
+    assert (w2.cpu().numpy() == lv.walls).all() and (a2.cpu().numpy() == lv.agent_xy).all()
+    assert (d2.cpu().numpy() == lv.agent_dir).all() and (g2.cpu().numpy() == lv.goal_xy).all()
+    # and the student's first observation on them matches the oracle's
+    om = oracle.MazeOracle(w.N, w.H, w.W, 5, 250)
+    om.reset_to_levels(lv.walls, lv.agent_xy, lv.agent_dir, lv.goal_xy)
+    assert (env.render_obs().cpu().numpy() == om.render_obs()).all()
+
+
+def test_c5_perfect_mazes_full_size():
+    """Config 5: 8192 envs on 51x51 perfect mazes, view 7, 512 steps, then GAE."""
+    w = wl.config(5)
+    note("C5 full size")
+    env, o, (r, d, obs), (orr, od, oobs) = run_fused(w)
+    assert obs.shape == (512, 8192, 7, 7, 3)
+    adv, ret = binding.compute_gae(r, to_gpu(w.values), d, w.gamma, w.lam)
+    oadv, oret = oracle.compute_gae(orr, w.values, od, w.gamma, w.lam)
+    assert np.abs(adv.cpu().numpy() - oadv).max() <= TOL
+    assert np.abs(ret.cpu().numpy() - oret).max() <= TOL
+
+
+@pytest.mark.parametrize("N", [1, 63, 65, 200, 1000])
+@pytest.mark.parametrize("variant", [0, 1])
+def test_ragged_batch_sizes(N, variant):
+    w = wl.student_random(f"ragged{N}", 900 + N, N=N, T=300, n_walls=40, max_steps=60)
+    note(w.name)
+    run_fused(w, variant)
+
+
+@pytest.mark.parametrize("H,W,k,nw", [(13, 13, 3, 30), (7, 19, 5, 40), (20, 9, 7, 50),
+                                      (5, 5, 9, 6), (51, 51, 7, 900), (40, 52, 7, 500),
+                                      (24, 24, 5, 200), (2, 2, 3, 1)])
+@pytest.mark.parametrize("variant", [0, 1])
+def test_other_shapes(H, W, k, nw, variant):
+    """Non-square grids, all supported view sizes, grids at the word-size limits."""
+    w = wl.student_random(f"shape{H}x{W}k{k}", 31 * H + W + k, N=300, H=H, W=W, view=k, T=200,
+                          n_walls=nw, max_steps=80)
+    note(w.name)
+    run_fused(w, variant)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_degenerate_cases(variant):
+    # every action value a byte can hold: only 0, 1, 2 do anything
+    w = wl.student_random("allbytes", 77, N=256, T=256, n_walls=20, max_steps=250)
+    w.actions = (np.arange(256, dtype=np.int64)[:, None] + np.arange(256)[None, :]).astype(np.uint8) \
+        .view(np.int8).copy()
+    run_fused(w, variant)
+    # max_steps = 1: every step ends the episode
+    w = wl.student_random("cap1", 78, N=128, T=20, n_walls=10, max_steps=1)
+    env, o, (r, d, _), _ = run_fused(w, variant)
+    assert bool((d == 1).all())
+    # walls everywhere except agent and goal: nobody ever moves
+    w = wl.student_random("full", 79, N=128, T=64, n_walls=167, max_steps=30)
+    run_fused(w, variant)
+    # no walls at all
+    w = wl.student_random("empty", 80, N=128, T=300, n_walls=0, max_steps=250)
+    run_fused(w, variant)
+
+
+def test_chunked_rollout_equals_one_launch():
+    """State carried across calls: 256 steps as 1+7+64+184 equals one 256-step launch."""
+    w = wl.student_random("chunks", 5, N=777, T=256, n_walls=50)
+    env, o = gpu_student(w), cpu_student(w)
+    acts = to_gpu(w.actions)
+    parts, s = [], 0
+    for n in (1, 7, 64, 184):
+        parts.append(env.step(acts[s:s + n]))
+        s += n
+    r = torch.cat([p[0] for p in parts]); d = torch.cat([p[1] for p in parts])
+    obs = torch.cat([p[2] for p in parts])
+    assert_rollout_equal((r, d, obs), o.step(w.actions, w.T), "chunked")
+    assert_state_equal(env, o)
+
+
+def test_reset_to_new_levels_replaces_everything():
+    w1 = wl.student_random("first", 1, N=500, T=50, n_walls=50)
+    w2 = wl.student_random("second", 2, N=500, T=50, n_walls=10)
+    env = gpu_student(w1)
+    env.step(to_gpu(w1.actions))
+    env.reset_to_levels(to_gpu(w2.walls), to_gpu(w2.agent_xy), to_gpu(w2.agent_dir), to_gpu(w2.goal_xy))
+    o = cpu_student(w2)
+    assert_state_equal(env, o)
+    walls, axy, ad, gxy = env.get_levels()
+    assert (walls.cpu().numpy() == w2.walls).all() and (axy.cpu().numpy() == w2.agent_xy).all()
+    assert (ad.cpu().numpy() == w2.agent_dir).all() and (gxy.cpu().numpy() == w2.goal_xy).all()
+    assert_rollout_equal(env.step(to_gpu(w2.actions)), o.step(w2.actions, w2.T), "after reset")
+
+
+@pytest.mark.parametrize("N,H,W,nw,T", [(1, 13, 13, 50, 52), (65, 5, 8, 12, 20), (300, 13, 13, 0, 5),
+                                        (100, 2, 1, 3, 7), (130, 64, 64, 40, 44), (64, 9, 4, 20, 30)])
+def test_editor_shapes_and_overrun(N, H, W, nw, T):
+    rng = np.random.default_rng(N + H)
+    # out-of-range actions included: they are clamped
+    actions = rng.integers(-3, H * W + 3, size=(T, N), dtype=np.int32)
+    dirs = rng.integers(0, 4, size=N, dtype=np.int8)
+    note(f"editor N={N} {H}x{W} walls={nw} T={T}")
+    ed = binding.EditorEnv(N, H, W, nw, device=DEV)
+    ed.reset(to_gpu(dirs))
+    oe = oracle.EditorOracle(N, H, W, nw)
+    oe.reset(dirs)
+    # two calls: state carried across them
+    k = T // 2
+    acts = to_gpu(actions)
+    o1, t1, d1 = ed.step(acts[:k])
+    walls_mid = [x.cpu().numpy() for x in ed.get_levels()]
+    oo1, ot1, od1 = oe.step(actions[:k], k)
+    lv = oe.get_levels()
+    for a, b in zip(walls_mid, (lv.walls, lv.agent_xy, lv.agent_dir, lv.goal_xy)):
+        assert (a == b).all()
+    o2, t2, d2 = ed.step(acts[k:])
+    oo2, ot2, od2 = oe.step(actions[k:], T - k)
+    assert (torch.cat([o1, o2]).cpu().numpy() == np.concatenate([oo1, oo2])).all()
+    assert (torch.cat([t1, t2]).cpu().numpy() == np.concatenate([ot1, ot2])).all()
+    assert (torch.cat([d1, d2]).cpu().numpy() == np.concatenate([od1, od2])).all()
+    lv = oe.get_levels()
+    for a, b in zip(ed.get_levels(), (lv.walls, lv.agent_xy, lv.agent_dir, lv.goal_xy)):
+        assert (a.cpu().numpy() == b).all()
+    # reset clears everything
+    ed.reset(to_gpu(dirs))
+    walls, axy, ad, gxy = ed.get_levels()
+    assert int(walls.sum()) == 0 and bool((axy == -1).all()) and bool((gxy == -1).all())
+
+
+@pytest.mark.parametrize("T,N", [(1, 1), (256, 4096), (512, 8192), (33, 65), (1000, 32)])
+@pytest.mark.parametrize("g,l", [(0.995, 0.98), (0.999, 0.95)])
+def test_gae_shapes(T, N, g, l):
+    rng = np.random.default_rng(T * 7 + N)
+    r = (rng.random((T, N), dtype=np.float32) * (rng.random((T, N)) < 0.05)).astype(np.float32)
+    V = rng.random((T + 1, N), dtype=np.float32)
+    d = (rng.random((T, N)) < 0.02).astype(np.uint8)
+    adv, ret = binding.compute_gae(to_gpu(r), to_gpu(V), to_gpu(d), g, l)
+    oadv, oret = oracle.compute_gae(r, V, d, g, l)
+    assert np.abs(adv.cpu().numpy() - oadv).max() <= TOL
+    assert np.abs(ret.cpu().numpy() - oret).max() <= TOL
+    adv2, none = binding.compute_gae(to_gpu(r), to_gpu(V), to_gpu(d), g, l, want_returns=False)
+    assert none is None and bool((adv2 == adv).all())
+
+
+def test_error_paths_on_the_gpu_box():
+    env = binding.MazeEnv(64, 13, 13, 5, 250, device=DEV)
+    with pytest.raises(binding.MazeError):
+        env.step(torch.zeros((4, 63), dtype=torch.int8, device=DEV))       # wrong N
+    with pytest.raises(binding.MazeError):
+        env.step(torch.zeros((4, 64), dtype=torch.int32, device=DEV))      # wrong dtype
+    with pytest.raises(binding.MazeError):
+        env.step(torch.zeros((4, 64), dtype=torch.int8))                    # CPU tensor
+    with pytest.raises(binding.MazeError):
+        binding.MazeEnv(64, 60, 60, 7, 250, device=DEV)                     # rows > 64 bits
+    with pytest.raises(binding.MazeError):
+        env.set_kernel_variant(9)
