@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the maze hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--no-rows]
+
+One "step" is one pass of the throughput workload (config 3: 32768 envs, 13x13
+interior, 50 random walls, view 5, episode cap 250, 256 open-loop random actions):
+maze_reset_to_levels + maze_render_obs (observation of the start state) + one
+256-step maze_step launch that writes observation, reward and done for every
+env-step.  Inputs are resident in HBM before the timed region.  `value` is
+env-steps per second over the K timed steps.
+
+The JSON line also carries
+  roofline      achieved algorithmic HBM GB/s of the rollout kernel (81 bytes per
+                env-step: 1 action in, 75 obs + 4 reward + 1 done out), timed with
+                HIP events on the launch stream inside the timed region;
+  cpu_baseline  the CPU oracle on the same workload on this host's cores;
+  rows          the other calls of the path (teacher editor at config 4, GAE,
+                the 51x51 config 5 rollout, the per-step call pattern), each timed
+                on its own after the main measurement.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+BYTES_PER_ENV_STEP = {5: 81, 7: 153}   # 1 action + 3k^2 obs + 4 reward + 1 done
+
+
+def load_traffic():
+    """HBM bytes per rollout launch measured with rocprofv3 --pmc (see profiles/)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f)
+    except OSError:
+        return {}
+
+
+def event_ms(pairs):
+    return [a.elapsed_time(b) for a, b in pairs]
+
+
+def time_calls(torch, fn, iters, warmup=2):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    pairs = []
+    for _ in range(iters):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    ms = event_ms(pairs)
+    return float(np.mean(ms)), float(np.min(ms))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-rows", action="store_true", help="skip the per-row measurements")
+    ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 per-cell kernels")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (envs are independent; sharding the batch "
+              "over GPUs needs no communication and is not part of this build). Use --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2311_12716_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    binding.load_library()        # fails loudly if the HIP library is not built
+    dev = "cuda:0"
+    g = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    # ---------------------------------------------------------------- main: config 3
+    w = wl.config(3)
+    N, T, k = w.N, w.T, w.view
+    env = binding.MazeEnv(N, w.H, w.W, k, w.max_steps, device=dev)
+    env.set_kernel_variant(args.variant)
+    walls, axy, adir, gxy, actions = g(w.walls), g(w.agent_xy), g(w.agent_dir), g(w.goal_xy), \
+        g(w.actions)
+    obs0 = torch.empty((N, k, k, 3), dtype=torch.int8, device=dev)
+    reward = torch.empty((T, N), dtype=torch.float32, device=dev)
+    done = torch.empty((T, N), dtype=torch.uint8, device=dev)
+    obs = torch.empty((T, N, k, k, 3), dtype=torch.int8, device=dev)
+
+    kernel_events = []
+
+    def one_step(record):
+        env.reset_to_levels(walls, axy, adir, gxy)
+        env.render_obs(obs0)
+        if record:
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+        env.step(actions, reward, done, obs)
+        if record:
+            b.record()
+            kernel_events.append((a, b))
+
+    for _ in range(args.warmup):
+        one_step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    env_steps = float(args.steps) * N * T
+    value = env_steps / elapsed
+    kms = event_ms(kernel_events)
+    k_avg_s = float(np.mean(kms)) * 1e-3
+    alg_bytes = BYTES_PER_ENV_STEP[k] * N * T
+    achieved = alg_bytes / k_avg_s / 1e9
+    traffic = load_traffic().get("student_rollout_c3")
+    n_resets = int(done.sum().item())
+
+    out = {
+        "metric": "env-steps/sec (student maze step + obs render)",
+        "value": value,
+        "unit": "env-steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32 bit-packed grids / int8 obs / f32 reward",
+        "data": "synthetic",
+        "config": {"workload": w.name, "envs": N, "grid": "13x13", "walls": 50, "view": k,
+                   "max_steps": w.max_steps, "rollout_steps": T, "resets_per_rollout": n_resets,
+                   "kernel_variant": args.variant},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "student rollout (maze_step, 256 steps fused)",
+                     "kernel_ms_avg": k_avg_s * 1e3, "kernel_ms_min": float(np.min(kms)),
+                     "algorithmic_bytes_per_launch": alg_bytes},
+    }
+
+    # ---------------------------------------------------------------- other rows
+    if not args.no_rows:
+        rows = {}
+        ms, mn = time_calls(torch, lambda: env.reset_to_levels(walls, axy, adir, gxy), 20)
+        rows["maze_reset_to_levels_c3"] = {"ms": ms, "GB/s": N * (169 + 17) / ms / 1e6}
+        ms, mn = time_calls(torch, lambda: env.render_obs(obs0), 20)
+        rows["maze_render_obs_c3"] = {"ms": ms, "GB/s": N * 75 / ms / 1e6}
+        a1 = actions[:1].contiguous()
+        r1, d1 = reward[:1], done[:1]
+
+        def per_step():
+            env.step(a1, r1, d1, None, want_obs=False)
+            env.render_obs(obs0)
+        ms, mn = time_calls(torch, per_step, 200, warmup=20)
+        rows["per_step_call_pattern_c3"] = {"ms": ms, "env-steps/s": N / ms * 1e3,
+                                            "note": "maze_step(n=1) + maze_render_obs, launch-bound"}
+        # GAE on this rollout's outputs
+        values = torch.rand((T + 1, N), dtype=torch.float32, device=dev)
+        adv = torch.empty((T, N), dtype=torch.float32, device=dev)
+        ret = torch.empty((T, N), dtype=torch.float32, device=dev)
+        ms, mn = time_calls(torch, lambda: binding.compute_gae(reward, values, done, 0.995, 0.98,
+                                                               adv, ret), 20)
+        rows["compute_gae_T256_N32768"] = {"ms": ms, "GB/s": 17.0 * N * T / ms / 1e6}
+        del values, adv, ret
+        # config 2 sized GAE
+        N2, T2 = 4096, 256
+        r2 = torch.rand((T2, N2), device=dev)
+        v2 = torch.rand((T2 + 1, N2), device=dev)
+        d2 = (torch.rand((T2, N2), device=dev) < 0.01).to(torch.uint8)
+        a2, rt2 = torch.empty_like(r2), torch.empty_like(r2)
+        ms, mn = time_calls(torch, lambda: binding.compute_gae(r2, v2, d2, 0.995, 0.98, a2, rt2), 50)
+        rows["compute_gae_c2_T256_N4096"] = {"ms": ms, "GB/s": 17.0 * N2 * T2 / ms / 1e6}
+        # teacher editor, config 4
+        ew = wl.config(4)
+        ed = binding.EditorEnv(ew.N, ew.H, ew.W, ew.n_walls, device=dev)
+        eact, edir = g(ew.actions), g(ew.agent_dir_init)
+        eobs = torch.empty((ew.T, ew.N, ew.H, ew.W, 3), dtype=torch.int8, device=dev)
+        et = torch.empty((ew.T, ew.N), dtype=torch.int32, device=dev)
+        edn = torch.empty((ew.T, ew.N), dtype=torch.uint8, device=dev)
+
+        def editor_pass():
+            ed.reset(edir)
+            ed.step(eact, eobs, et, edn)
+        ms, mn = time_calls(torch, editor_pass, 10)
+        ebytes = 515.0 * ew.N * ew.T
+        rows["editor_c4"] = {"ms": ms, "editor-steps/s": ew.N * ew.T / ms * 1e3,
+                             "GB/s": ebytes / ms / 1e6, "frac_of_hbm_peak": ebytes / ms / 1e6 / HBM_PEAK_GBS}
+        del eobs, et, edn, ed
+        # config 5: 51x51 perfect mazes, view 7
+        w5 = wl.config(5)
+        env5 = binding.MazeEnv(w5.N, w5.H, w5.W, w5.view, w5.max_steps, device=dev)
+        env5.set_kernel_variant(args.variant)
+        env5.reset_to_levels(g(w5.walls), g(w5.agent_xy), g(w5.agent_dir), g(w5.goal_xy))
+        a5 = g(w5.actions)
+        r5 = torch.empty((w5.T, w5.N), dtype=torch.float32, device=dev)
+        d5 = torch.empty((w5.T, w5.N), dtype=torch.uint8, device=dev)
+        o5 = torch.empty((w5.T, w5.N, 7, 7, 3), dtype=torch.int8, device=dev)
+        ms, mn = time_calls(torch, lambda: env5.step(a5, r5, d5, o5), 10)
+        b5 = 153.0 * w5.N * w5.T
+        rows["student_rollout_c5"] = {"ms": ms, "env-steps/s": w5.N * w5.T / ms * 1e3,
+                                      "GB/s": b5 / ms / 1e6, "frac_of_hbm_peak": b5 / ms / 1e6 / HBM_PEAK_GBS}
+        del o5, env5
+        # plain streaming-write ceiling of this GPU (torch fill of the obs buffer)
+        ms, mn = time_calls(torch, lambda: obs.fill_(1), 10)
+        rows["fill_ceiling"] = {"ms": ms, "GB/s": obs.numel() / ms / 1e6,
+                                "note": "torch fill_ of the 629 MB obs tensor"}
+        out["rows"] = rows
+
+    # ---------------------------------------------------------------- CPU oracle
+    if not args.no_cpu:
+        import oracle
+        o = oracle.MazeOracle(N, w.H, w.W, k, w.max_steps)
+        cpu_steps, t_cpu = 0, 0.0
+        reps = 0
+        while t_cpu < 10.0 and reps < 64:
+            o.reset_to_levels(w.walls, w.agent_xy, w.agent_dir, w.goal_xy)
+            c0 = time.perf_counter()
+            o.render_obs()
+            o.step(w.actions, T)
+            t_cpu += time.perf_counter() - c0
+            cpu_steps += N * T
+            reps += 1
+        out["cpu_baseline"] = {"value": cpu_steps / t_cpu, "unit": "env-steps/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"{reps} x the full config-3 rollout "
+                                         f"({N} envs x {T} steps, step + render), {t_cpu:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

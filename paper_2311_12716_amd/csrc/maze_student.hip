@@ -193,11 +193,11 @@ __device__ __forceinline__ void render_cells(const StudentDev &p, const Word *__
 }
 
 template <typename Word>
-__global__ void k_student_percell(StudentDev p, const int8_t *__restrict__ actions, int n_steps,
-                                  float *__restrict__ reward, uint8_t *__restrict__ done,
-                                  int8_t *__restrict__ obs)
+__global__ void k_student_percell(StudentDev p, int n_begin, const int8_t *__restrict__ actions,
+                                  int n_steps, float *__restrict__ reward,
+                                  uint8_t *__restrict__ done, int8_t *__restrict__ obs)
 {
-    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    int n = n_begin + blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= p.N) return;
     const Word *grid_n = (const Word *)p.grids + (size_t)n * 4 * p.SP;
     uint32_t pose = p.pose[n];
@@ -228,9 +228,9 @@ __global__ void k_student_percell(StudentDev p, const int8_t *__restrict__ actio
 }
 
 template <typename Word>
-__global__ void k_render_percell(StudentDev p, int8_t *__restrict__ obs)
+__global__ void k_render_percell(StudentDev p, int n_begin, int8_t *__restrict__ obs)
 {
-    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    int n = n_begin + blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= p.N) return;
     const Word *grid_n = (const Word *)p.grids + (size_t)n * 4 * p.SP;
     uint32_t pose = p.pose[n];
@@ -238,10 +238,12 @@ __global__ void k_render_percell(StudentDev p, int8_t *__restrict__ obs)
     render_cells<Word>(p, grid_n, pose, goal, obs + (size_t)n * p.k * p.k * 3);
 }
 
-// Implemented in maze_student_tiled.hip: returns 1 if it launched, 0 if the shape
-// is not covered by a tiled kernel.
+// Implemented in maze_student_tiled.hip: launches the tiled kernel on the first
+// *covered envs (a multiple of 64; 0 if the shape is not covered) and returns 1 if
+// it launched.  n_steps == 0 renders the current state.
 int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_steps,
-                         float *d_reward, uint8_t *d_done, int8_t *d_obs, hipStream_t st);
+                         float *d_reward, uint8_t *d_done, int8_t *d_obs, int *covered,
+                         hipStream_t st);
 
 extern "C" int maze_step(maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
                          uint8_t *d_done, int8_t *d_obs, void *stream)
@@ -250,17 +252,17 @@ extern "C" int maze_step(maze_ctx *ctx, const int8_t *d_actions, int n_steps, fl
     if (n_steps < 1) return MAZE_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     const StudentDev &p = ctx->dev;
-    int launched = 0;
+    int covered = 0;
     if (ctx->variant == 0)
-        launched = student_tiled_launch(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
-    if (!launched) {
-        dim3 grid((p.N + 63) / 64), block(64);
+        student_tiled_launch(ctx, d_actions, n_steps, d_reward, d_done, d_obs, &covered, st);
+    if (covered < p.N) {
+        dim3 grid((p.N - covered + 63) / 64), block(64);
         if (ctx->word64)
-            hipLaunchKernelGGL(k_student_percell<uint64_t>, grid, block, 0, st, p, d_actions,
-                               n_steps, d_reward, d_done, d_obs);
+            hipLaunchKernelGGL(k_student_percell<uint64_t>, grid, block, 0, st, p, covered,
+                               d_actions, n_steps, d_reward, d_done, d_obs);
         else
-            hipLaunchKernelGGL(k_student_percell<uint32_t>, grid, block, 0, st, p, d_actions,
-                               n_steps, d_reward, d_done, d_obs);
+            hipLaunchKernelGGL(k_student_percell<uint32_t>, grid, block, 0, st, p, covered,
+                               d_actions, n_steps, d_reward, d_done, d_obs);
     }
     MAZE_HIP_CHECK(hipGetLastError());
     return MAZE_OK;
@@ -271,11 +273,16 @@ extern "C" int maze_render_obs(maze_ctx *ctx, int8_t *d_obs, void *stream)
     if (!ctx || !d_obs) return MAZE_ENULL;
     hipStream_t st = (hipStream_t)stream;
     const StudentDev &p = ctx->dev;
-    dim3 grid((p.N + 63) / 64), block(64);
-    if (ctx->word64)
-        hipLaunchKernelGGL(k_render_percell<uint64_t>, grid, block, 0, st, p, d_obs);
-    else
-        hipLaunchKernelGGL(k_render_percell<uint32_t>, grid, block, 0, st, p, d_obs);
+    int covered = 0;
+    if (ctx->variant == 0)
+        student_tiled_launch(ctx, nullptr, 0, nullptr, nullptr, d_obs, &covered, st);
+    if (covered < p.N) {
+        dim3 grid((p.N - covered + 63) / 64), block(64);
+        if (ctx->word64)
+            hipLaunchKernelGGL(k_render_percell<uint64_t>, grid, block, 0, st, p, covered, d_obs);
+        else
+            hipLaunchKernelGGL(k_render_percell<uint32_t>, grid, block, 0, st, p, covered, d_obs);
+    }
     MAZE_HIP_CHECK(hipGetLastError());
     return MAZE_OK;
 }
