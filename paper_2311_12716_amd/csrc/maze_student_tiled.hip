@@ -5,10 +5,10 @@
 // its observation as a BIT STREAM -- bit i of the stream is byte i of the env's
 // k*k*3 observation, which is 0 or 1 -- and leaves it in LDS.  The 64 streams,
 // concatenated, are exactly the 64*3k^2 contiguous output bytes of this time
-// step, so other lanes then take 32 consecutive stream bits each (they may
-// straddle two envs), expand each bit to a byte and write 32 contiguous bytes
-// with two 16-byte stores.  Every obs byte leaves the CU in an aligned, fully
-// used 16-byte store.
+// step, so other lanes then take 16 consecutive stream bits each (they may
+// straddle two envs), expand each bit to a byte and write 16 contiguous bytes;
+// consecutive lanes take consecutive pieces, so one store instruction of a wave
+// writes 1 KB of contiguous, aligned output.
 #include "maze_internal.h"
 #include "maze_student_device.h"
 
@@ -20,8 +20,8 @@ struct View {
     static constexpr int SB = 3 * CELLS;           // stream bits (= obs bytes) per env
     static constexpr int ND = (SB + 31) / 32;      // data dwords per env record
     static constexpr int REC = ND + 1;             // record = data dwords + one zero dword
-    static constexpr int NSD = 2 * SB;             // stream dwords per 64-env wave-step
-    static constexpr int ROUNDS = (NSD + 63) / 64;
+    static constexpr int NWIN = 4 * SB;            // 16-bit windows per 64-env step
+    static constexpr int ROUNDS = (NWIN + 63) / 64;
     static constexpr int LUTN = 1 << K;            // row pattern -> 3K stream bits
     static constexpr int ROWBITS = 3 * K;
 };
@@ -118,15 +118,17 @@ __device__ __forceinline__ void produce_record(const uint32_t *lut, uint32_t *re
     }
 }
 
-// Lane-constant description of the 32 stream bits a lane expands in one round.
+// Lane-constant description of the 16 stream bits a lane expands in one round.
+// In round j lane l takes window 64*j + l, so one store instruction of the wave
+// writes 64 consecutive 16-byte pieces = 1 KB of contiguous output.
 // Dword indices are relative to the first record of the buffer.
 struct Window {
     int addr0;      // first dword holding the window (in env e0's record)
     int addr1;      // env e0+1's first dword, or e0's zero dword when the window ends in e0
     int sh;         // bit offset of the window inside addr0's dword
-    int rem;        // bits taken from env e0 when fewer than 32, else 0 (then addr1 reads zero)
+    int rem;        // bits taken from env e0 when fewer than 16, else 0 (then addr1 reads zero)
     int active;     // window exists (the last round is partial)
-    uint32_t out;   // byte offset of the window's 32 output bytes in the workgroup's block
+    uint32_t out;   // byte offset of the window's 16 output bytes in the workgroup's block
 };
 
 template <int K>
@@ -135,36 +137,32 @@ __device__ __forceinline__ Window make_window(int lane, int round)
     using V = View<K>;
     Window w;
     int m = round * 64 + lane;
-    w.active = m < V::NSD;
+    w.active = m < V::NWIN;
     int mm = w.active ? m : 0;
-    int bitpos = 32 * mm;
+    int bitpos = 16 * mm;
     int e0 = bitpos / V::SB;
     int s = bitpos - e0 * V::SB;
     int rec0 = e0 * V::REC;
     w.addr0 = rec0 + (s >> 5);
     w.sh = s & 31;
     int rem = V::SB - s;
-    w.rem = rem < 32 ? rem : 0;
-    w.addr1 = rem < 32 ? rec0 + V::REC : rec0 + V::ND;
-    w.out = 32u * mm;
+    w.rem = rem < 16 ? rem : 0;
+    w.addr1 = rem < 16 ? rec0 + V::REC : rec0 + V::ND;
+    w.out = 16u * mm;
     return w;
 }
 
-// Expand one 32-bit window of the concatenated streams into 32 output bytes.
+// Expand one 16-bit window of the concatenated streams into 16 output bytes.
 __device__ __forceinline__ void consume_window(const uint32_t *recs, const Window &w, int8_t *block)
 {
     uint32_t lo = recs[w.addr0], hi = recs[w.addr0 + 1], nx = recs[w.addr1];
-    // bits [s, s+32) of env e0 (zero beyond its end), then env e0+1 from bit 0; when the
+    // bits [s, s+16) of env e0 (zero beyond its end), then env e0+1 from bit 0; when the
     // window ends inside e0, nx is e0's zero dword and the shift amount is irrelevant
     uint32_t bits = __builtin_amdgcn_alignbit(hi, lo, w.sh) | (nx << w.rem);
-    uint4 a, b;
+    uint4 a;
     a.x = expand_nibble(bits & 15);          a.y = expand_nibble((bits >> 4) & 15);
     a.z = expand_nibble((bits >> 8) & 15);   a.w = expand_nibble((bits >> 12) & 15);
-    b.x = expand_nibble((bits >> 16) & 15);  b.y = expand_nibble((bits >> 20) & 15);
-    b.z = expand_nibble((bits >> 24) & 15);  b.w = expand_nibble(bits >> 28);
-    uint4 *dst = (uint4 *)(block + w.out);
-    dst[0] = a;
-    dst[1] = b;
+    *(uint4 *)(block + w.out) = a;
 }
 
 template <int K, typename Word>
@@ -206,8 +204,8 @@ constexpr int ACT_RING = 8;   // action prefetch distance of the producer wave, 
 //              traffic is the action byte, prefetched ACT_RING steps ahead, so it never
 //              waits for a store to be acknowledged.
 //   consumer : after the step's barrier, expands buffer s&1 into the step's
-//              64*3k^2 contiguous obs bytes with 16-byte stores (round j of the
-//              windows goes to consumer j % NC); the last consumer also writes the
+//              64*3k^2 contiguous obs bytes, 1 KB per store instruction (round j
+//              of the windows goes to consumer j % NC); the last consumer also writes the
 //              reward and done rows.  Consumers never load from global memory.
 // One barrier per step: the producer arrives after building step s, the consumers
 // after draining step s-1, so buffer s&1 is rewritten (step s+2) only after its
