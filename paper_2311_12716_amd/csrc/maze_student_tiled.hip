@@ -1,14 +1,26 @@
 // Tiled store-layout kernels of the student env.
 //
 // A workgroup owns 64 consecutive envs for the whole rollout.  Per step one lane
-// per env advances the env (state in registers, wall rows from LDS) and builds
-// its observation as a BIT STREAM -- bit i of the stream is byte i of the env's
-// k*k*3 observation, which is 0 or 1 -- and leaves it in LDS.  The 64 streams,
+// per env advances the env (state in registers, wall rows from LDS) and its
+// observation is built as a BIT STREAM -- bit i of the stream is byte i of the
+// env's k*k*3 observation, which is 0 or 1 -- and left in LDS.  The 64 streams,
 // concatenated, are exactly the 64*3k^2 contiguous output bytes of this time
 // step, so other lanes then take 16 consecutive stream bits each (they may
 // straddle two envs), expand each bit to a byte and write 16 contiguous bytes;
 // consecutive lanes take consecutive pieces, so one store instruction of a wave
 // writes 1 KB of contiguous, aligned output.
+//
+// The per-step work is a three-stage pipeline over the waves of the workgroup,
+// advanced by one barrier per step:
+//   wave 0 ("dynamics")  step s  : action, move, goal/done/reset, reads the K
+//                                  wall rows of the new view and publishes the
+//                                  K x K view bits, the goal offset, reward, done
+//   wave 1 ("records")   step s-1: view bits -> stream record (row lookup table),
+//                                  goal cell patched in
+//   waves 2.. ("stores") step s-2: expand records to bytes, store obs/reward/done
+// Only the dynamics wave carries a dependency from step to step, so the time per
+// step is that wave's short chain; the store waves never load from global memory
+// and the dynamics wave touches it once every 16 steps (actions, staged in LDS).
 #include "maze_internal.h"
 #include "maze_student_device.h"
 
@@ -24,7 +36,13 @@ struct View {
     static constexpr int ROUNDS = (NWIN + 63) / 64;
     static constexpr int LUTN = 1 << K;            // row pattern -> 3K stream bits
     static constexpr int ROWBITS = 3 * K;
+    static constexpr int RPD = 32 / K;             // view rows packed per dword
+    static constexpr int WV = (K + RPD - 1) / RPD; // dwords of packed view bits
+    static constexpr int NC = ROUNDS < 5 ? ROUNDS : 5;   // store waves per workgroup
+    static constexpr int WAVES = 2 + NC;
 };
+
+constexpr int ACT_BLOCK = 16;   // steps of actions staged per global load of the dynamics wave
 
 // 4 stream bits -> 4 bytes (bit j -> byte j).  The four shifted copies do not
 // overlap, so the multiply carries nothing.
@@ -37,30 +55,30 @@ template <typename Word> struct WordOps;
 template <> struct WordOps<uint32_t> { static constexpr int DW = 1; };
 template <> struct WordOps<uint64_t> { static constexpr int DW = 2; };
 
-// Per-workgroup LDS carve-up (dword offsets).  Two record buffers so that the
-// producer wave can build step s+1 while the consumer waves drain step s; each
-// buffer also carries the step's reward (float bits) and done flag per env.
+// Per-workgroup LDS carve-up (dword offsets).
 template <int K, typename Word>
 struct Lds {
-    static constexpr int LUT = 0;
-    static constexpr int BUF_REC = 0;                             // inside a buffer
-    static constexpr int BUF_REW = 64 * View<K>::REC;
-    static constexpr int BUF_DONE = BUF_REW + 64;
-    static constexpr int BUF_SIZE = BUF_DONE + 64;
-    static constexpr int BUF0 = View<K>::LUTN;
-    static constexpr int GRID0 = BUF0 + 2 * BUF_SIZE;
-    __host__ __device__ static int grid_stride(int SP)       // dwords per env, odd
+    using V = View<K>;
+    static constexpr int LUT = 0;                                  // [LUTN]
+    static constexpr int ACT = LUT + V::LUTN;                      // [2][ACT_BLOCK][16] action bytes
+    static constexpr int ST = ACT + 2 * ACT_BLOCK * 16;            // [2][WV+1][64] view bits, goal offset
+    static constexpr int ST_SIZE = (V::WV + 1) * 64;
+    static constexpr int OUT = ST + 2 * ST_SIZE;                   // [4][2][64] reward bits, done
+    static constexpr int REC = OUT + 4 * 128;                      // [2][64*REC] stream records
+    static constexpr int REC_SIZE = 64 * V::REC;
+    static constexpr int GRID0 = REC + 2 * REC_SIZE;               // [64][grid_stride]
+    __host__ __device__ static int grid_stride(int SP)             // dwords per env, odd
     {
-        return (4 * SP * WordOps<Word>::DW + 4) | 1;
+        return (4 * SP * WordOps<Word>::DW) | 1;
     }
     __host__ static size_t bytes(int SP, bool grid_in_lds)
     {
-        return 4 * (size_t)(GRID0 + (grid_in_lds ? 64 * grid_stride(SP) : 64 * 5));
+        return 4 * (size_t)(GRID0 + (grid_in_lds ? 64 * grid_stride(SP) : 0));
     }
 };
 
-// Row r of the view of an env (r = 0 farthest).  The words come from LDS or, for
-// grids too large to stage, from the packed grids in global memory.
+// The K wall words of an env's view (row 0 farthest).  From LDS or, for grids too
+// large to stage, from the packed grids in global memory.
 template <int K, typename Word, bool GRID_LDS>
 __device__ __forceinline__ void load_view_rows(const uint32_t *lds_env, const Word *glob_env, int SP,
                                                int d, int yd, Word (&rows)[K])
@@ -83,20 +101,34 @@ __device__ __forceinline__ void load_view_rows(const uint32_t *lds_env, const Wo
     }
 }
 
-// Build the env's stream record from its view rows and leave it in LDS.
+// K x K view bits (row r, column c -> bit K*(r % RPD) + c of dword r / RPD).
 template <int K, typename Word>
-__device__ __forceinline__ void produce_record(const uint32_t *lut, uint32_t *rec,
-                                               const Word (&rows)[K], int xd, int gf, int gc)
+__device__ __forceinline__ void pack_view(const Word (&rows)[K], int xd, uint32_t (&vw)[View<K>::WV])
 {
     using V = View<K>;
-    constexpr int h = K / 2;
+    const int sh = xd - K / 2;
+#pragma unroll
+    for (int q = 0; q < V::WV; ++q) vw[q] = 0;
+#pragma unroll
+    for (int r = 0; r < K; ++r) {
+        uint32_t bits = (uint32_t)(rows[r] >> sh) & (V::LUTN - 1);
+        vw[r / V::RPD] |= bits << (K * (r % V::RPD));
+    }
+}
+
+// Stream record of one env from its view bits; goal at (gf cells ahead, gc cells to
+// the right) of the agent.  An empty cell is 100b, a wall 001b, the goal 010b.
+template <int K>
+__device__ __forceinline__ void produce_record(const uint32_t *lut, uint32_t *rec,
+                                               const uint32_t (&vw)[View<K>::WV], int gf, int gc)
+{
+    using V = View<K>;
     uint32_t D[V::REC];
 #pragma unroll
     for (int q = 0; q < V::REC; ++q) D[q] = 0;
-    const int sh = xd - h;
 #pragma unroll
     for (int r = 0; r < K; ++r) {
-        uint32_t idx = (uint32_t)(rows[r] >> sh) & (V::LUTN - 1);
+        uint32_t idx = (vw[r / V::RPD] >> (K * (r % V::RPD))) & (V::LUTN - 1);
         uint32_t piece = lut[idx];
         const int off = V::ROWBITS * r, q = off >> 5, b = off & 31;
         D[q] |= piece << b;
@@ -104,12 +136,10 @@ __device__ __forceinline__ void produce_record(const uint32_t *lut, uint32_t *re
     }
 #pragma unroll
     for (int q = 0; q < V::REC; ++q) rec[q] = D[q];
-    // goal: an empty cell (100b) becomes a goal cell (010b): flip stream bits 3c+1, 3c+2
-    // (gf, gc) = goal position relative to the agent: cells ahead, cells to the right
-    int f = gf;
-    int c = gc + h;                                // view column
-    bool inview = ((unsigned)f < (unsigned)K) & ((unsigned)c < (unsigned)K);
-    int cell = (K - 1 - f) * K + c;
+    // goal: the empty cell (100b) becomes a goal cell (010b): flip stream bits 3c+1, 3c+2
+    int c = gc + K / 2;                            // view column
+    bool inview = ((unsigned)gf < (unsigned)K) & ((unsigned)c < (unsigned)K);
+    int cell = (K - 1 - gf) * K + c;
     int bit = 3 * cell + 1;
     if (inview) {
         int q = bit >> 5, b = bit & 31;
@@ -137,7 +167,7 @@ __device__ __forceinline__ Window make_window(int lane, int round)
     using V = View<K>;
     Window w;
     int m = round * 64 + lane;
-    w.active = m < V::NWIN;
+    w.active = (round < V::ROUNDS) && (m < V::NWIN);
     int mm = w.active ? m : 0;
     int bitpos = 16 * mm;
     int e0 = bitpos / V::SB;
@@ -195,151 +225,161 @@ __device__ __forceinline__ void stage_grids(const StudentDev &p, uint32_t *lds, 
     }
 }
 
-constexpr int ACT_RING = 8;   // action prefetch distance of the producer wave, in steps
-
 // ------------------------------------------------------------------ rollout
-// Workgroup = 64 envs = one PRODUCER wave + NC CONSUMER waves.
-//   producer : lane = env.  Per step: action -> move -> goal/done/reset -> view rows
-//              -> stream record, reward, done into LDS buffer s&1.  Its only global
-//              traffic is the action byte, prefetched ACT_RING steps ahead, so it never
-//              waits for a store to be acknowledged.
-//   consumer : after the step's barrier, expands buffer s&1 into the step's
-//              64*3k^2 contiguous obs bytes, 1 KB per store instruction (round j
-//              of the windows goes to consumer j % NC); the last consumer also writes the
-//              reward and done rows.  Consumers never load from global memory.
-// One barrier per step: the producer arrives after building step s, the consumers
-// after draining step s-1, so buffer s&1 is rewritten (step s+2) only after its
-// readers have passed the next barrier.
-template <int K, typename Word, bool GRID_LDS, int NC>
-__global__ __launch_bounds__(64 * (1 + NC)) void k_student_rollout(
+template <int K, typename Word, bool GRID_LDS>
+__global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
     StudentDev p, const int8_t *__restrict__ actions, int n_steps, float *__restrict__ reward,
     uint8_t *__restrict__ done, int8_t *__restrict__ obs)
 {
     using V = View<K>;
     using L = Lds<K, Word>;
+    constexpr int NT = 64 * V::WAVES;
     extern __shared__ uint32_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int env0 = blockIdx.x * 64;
+    const int n = env0 + lane;
+    const int last = n_steps - 1;
 
-    fill_lut<K, Word>(lds, tid, 64 * (1 + NC));
-    if (GRID_LDS) stage_grids<K, Word>(p, lds, tid, 64 * (1 + NC), env0);
-    __syncthreads();
+    fill_lut<K, Word>(lds, tid, NT);
+    if (GRID_LDS) stage_grids<K, Word>(p, lds, tid, NT, env0);
 
+    // ---- dynamics wave: state, constants, first block of actions
+    int xd = 0, yd = 0, d = 0, gf = 0, gc = 0, sxd = 0, syd = 0, sd = 0, sgf = 0, sgc = 0;
+    uint32_t t = 0, a_next = 3;
+    Word ahead = 0;
+    uint4 act_regs = make_uint4(0, 0, 0, 0);
+    const uint32_t *lds_env = lds + L::GRID0 + lane * (GRID_LDS ? L::grid_stride(p.SP) : 0);
+    const Word *glob_env = (const Word *)p.grids + (size_t)n * 4 * p.SP;
+    // lane l stages the action bytes of step (block*16 + l/4), envs 16*(l%4) .. +15
+    const int8_t *act_lane = actions + env0 + 16 * (lane & 3);
+    auto load_actions = [&](int block) {
+        int s = min(block * ACT_BLOCK + (lane >> 2), last);
+        return *(const uint4 *)(act_lane + (size_t)s * p.N);
+    };
     if (wave == 0) {
-        // ------------------------------------------------------------ producer
-        const int n = env0 + lane;
-        const int gs = GRID_LDS ? L::grid_stride(p.SP) : 0;
-        const uint32_t *lds_env = lds + L::GRID0 + lane * gs;
-        const Word *glob_env = (const Word *)p.grids + (size_t)n * 4 * p.SP;
-        const uint32_t *lut = lds + L::LUT;
         uint32_t pose = p.pose[n];
-        int xd = pose & 255, yd = (pose >> 8) & 255, d = (pose >> 16) & 3;
-        uint32_t t = p.tcount[n];
+        xd = pose & 255; yd = (pose >> 8) & 255; d = (pose >> 16) & 3;
+        t = p.tcount[n];
         const uint32_t start = p.start[n];
-        const int sxd = start & 255, syd = (start >> 8) & 255, sd = (start >> 16) & 3;
+        sxd = start & 255; syd = (start >> 8) & 255; sd = (start >> 16) & 3;
         // goal relative to the agent in the agent's own frame: gf cells ahead, gc cells to
-        // the right.  Turning rotates this vector, moving forward shortens gf; no goal
-        // coordinates are needed inside the loop.
+        // the right.  Turning rotates this vector, moving forward shortens gf.
         const uint32_t g_now = p.goalrot[4 * (size_t)n + d], g_start = p.goalrot[4 * (size_t)n + sd];
-        int gf = yd - (int)(g_now >> 8), gc = (int)(g_now & 255) - xd;
-        const int sgf = syd - (int)(g_start >> 8), sgc = (int)(g_start & 255) - sxd;
-        const uint32_t tmax = (uint32_t)p.max_steps;
-        const double slope = p.reward_slope;
-        const int HPm1 = p.HP - 1, WPm1 = p.WP - 1;
-
+        gf = yd - (int)(g_now >> 8); gc = (int)(g_now & 255) - xd;
+        sgf = syd - (int)(g_start >> 8); sgc = (int)(g_start & 255) - sxd;
+        ((uint4 *)(lds + L::ACT))[lane] = load_actions(0);
+        act_regs = load_actions(1);
+    }
+    __syncthreads();
+    if (wave == 0) {
         Word rows[K];
         load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, p.SP, d, yd, rows);
-        Word ahead = rows[K - 2];           // wall word of the row just ahead of the agent
+        ahead = rows[K - 2];           // wall word of the row just ahead of the agent
+        a_next = ((const uint8_t *)(lds + L::ACT))[lane];
+    }
 
-        // one env step + observation record into LDS buffer s&1, then the step's barrier
-        auto step = [&](int s, uint32_t a) __attribute__((always_inline)) {
-            // ---- dynamics (branch-free)
-            t += 1;
-            const int blocked = (int)((ahead >> xd) & 1);
-            const int odd = d & 1;
-            const int rows_m1 = odd ? HPm1 : WPm1;
-            const int bits_m1 = odd ? WPm1 : HPm1;
-            const int tl = (a == 0), tr = (a == 1), fw = (a == 2) & (blocked ^ 1);
-            const int x_l = rows_m1 - yd, y_r = bits_m1 - xd, y_f = yd - fw;
-            const int nx = tl ? x_l : (tr ? yd : xd);
-            const int ny = tl ? xd : (tr ? y_r : y_f);
-            const int nf = tl ? -gc : (tr ? gc : gf - fw);
-            const int nc = tl ? gf : (tr ? -gf : gc);
-            d = (d + 3 * tl + tr) & 3;
-            const int reached = ((nf | nc) == 0);
-            const int fin = reached | (t >= tmax);
-            const float r = reached ? (float)(1.0 - (double)t * slope) : 0.0f;
-            xd = fin ? sxd : nx;
-            yd = fin ? syd : ny;
-            d = fin ? sd : d;
-            t = fin ? 0u : t;
-            gf = fin ? sgf : nf;
-            gc = fin ? sgc : nc;
-            // ---- observation of the new state -> LDS buffer s&1
-            uint32_t *buf = lds + L::BUF0 + (s & 1) * L::BUF_SIZE;
-            load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, p.SP, d, yd, rows);
-            ahead = rows[K - 2];
-            buf[L::BUF_REW + lane] = __float_as_uint(r);
-            buf[L::BUF_DONE + lane] = (uint32_t)fin;
-            produce_record<K, Word>(lut, buf + L::BUF_REC + lane * V::REC, rows, xd, gf, gc);
-            __syncthreads();
-        };
+    // ---- store waves: windows and output cursors
+    const int c = wave - 2;
+    constexpr int MYR = (V::ROUNDS + V::NC - 1) / V::NC;     // rounds per store wave, at most
+    Window win[MYR];
+#pragma unroll
+    for (int j = 0; j < MYR; ++j) win[j] = make_window<K>(lane, (c < 0 ? 0 : c) + j * V::NC);
+    const size_t step_obs = (size_t)p.N * V::SB;
+    int8_t *block = obs + (size_t)env0 * V::SB;
+    float *rw = reward + n;
+    uint8_t *dn = done + n;
 
-        // actions are prefetched ACT_RING steps ahead (indices clamped to the last step, so
-        // every load is unconditional and stays in flight across the steps in between)
-        // (read as unsigned bytes: values other than 0, 1, 2 are no-ops either way)
-        const uint8_t *act = (const uint8_t *)actions + n;
-        const int last = n_steps - 1;
-        uint32_t ring[ACT_RING];
+    const uint32_t tmax = (uint32_t)p.max_steps;
+    const double slope = p.reward_slope;
+    const int HPm1 = p.HP - 1, WPm1 = p.WP - 1;
+
+    for (int i = 0; i < n_steps + 2; ++i) {
+        if (wave == 0) {
+            // ------------------------------------------------ dynamics, step i
+            if (i < n_steps) {
+                const uint32_t a = a_next;
+                // action of the next step (its block was staged at least 8 steps ago)
+                {
+                    const int s1 = min(i + 1, last);
+                    a_next = ((const uint8_t *)(lds + L::ACT))[((s1 / ACT_BLOCK) & 1) * (ACT_BLOCK * 64) +
+                                                              (s1 % ACT_BLOCK) * 64 + lane];
+                }
+                t += 1;
+                const int blocked = (int)((ahead >> xd) & 1);
+                const int odd = d & 1;
+                const int rows_m1 = odd ? HPm1 : WPm1;
+                const int bits_m1 = odd ? WPm1 : HPm1;
+                const int tl = (a == 0), tr = (a == 1), fw = (a == 2) & (blocked ^ 1);
+                const int x_l = rows_m1 - yd, y_r = bits_m1 - xd, y_f = yd - fw;
+                const int nx = tl ? x_l : (tr ? yd : xd);
+                const int ny = tl ? xd : (tr ? y_r : y_f);
+                const int nf = tl ? -gc : (tr ? gc : gf - fw);
+                const int nc = tl ? gf : (tr ? -gf : gc);
+                d = (d + 3 * tl + tr) & 3;
+                const int reached = ((nf | nc) == 0);
+                const int fin = reached | (t >= tmax);
+                const float r = reached ? (float)(1.0 - (double)t * slope) : 0.0f;
+                xd = fin ? sxd : nx;
+                yd = fin ? syd : ny;
+                d = fin ? sd : d;
+                t = fin ? 0u : t;
+                gf = fin ? sgf : nf;
+                gc = fin ? sgc : nc;
+                Word rows[K];
+                load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, p.SP, d, yd, rows);
+                ahead = rows[K - 2];
+                uint32_t vw[V::WV];
+                pack_view<K, Word>(rows, xd, vw);
+                uint32_t *st = lds + L::ST + (i & 1) * L::ST_SIZE;
 #pragma unroll
-        for (int i = 0; i < ACT_RING; ++i) ring[i] = act[(size_t)min(i, last) * p.N];
-        int s = 0;
-        for (; s + ACT_RING <= n_steps; s += ACT_RING) {
+                for (int q = 0; q < V::WV; ++q) st[q * 64 + lane] = vw[q];
+                st[V::WV * 64 + lane] = (uint32_t)(gf & 0xFFFF) | ((uint32_t)gc << 16);
+                uint32_t *out = lds + L::OUT + (i & 3) * 128;
+                out[lane] = __float_as_uint(r);
+                out[64 + lane] = (uint32_t)fin;
+                // stage the next block of actions half way through the current one
+                if ((i % ACT_BLOCK) == ACT_BLOCK / 2) {
+                    const int nb = i / ACT_BLOCK + 1;
+                    ((uint4 *)(lds + L::ACT))[(nb & 1) * 64 + lane] = act_regs;
+                    act_regs = load_actions(nb + 1);
+                }
+            }
+        } else if (wave == 1) {
+            // ------------------------------------------------ records, step i-1
+            const int s = i - 1;
+            if (s >= 0 && s < n_steps) {
+                const uint32_t *st = lds + L::ST + (s & 1) * L::ST_SIZE;
+                uint32_t vw[V::WV];
 #pragma unroll
-            for (int i = 0; i < ACT_RING; ++i) {
-                const uint32_t a = ring[i];
-                ring[i] = act[(size_t)min(s + i + ACT_RING, last) * p.N];
-                step(s + i, a);
+                for (int q = 0; q < V::WV; ++q) vw[q] = st[q * 64 + lane];
+                const uint32_t g = st[V::WV * 64 + lane];
+                produce_record<K>(lds + L::LUT, lds + L::REC + (s & 1) * L::REC_SIZE + lane * V::REC, vw,
+                                  (int)(int16_t)(g & 0xFFFF), (int)g >> 16);
+            }
+        } else {
+            // ------------------------------------------------ stores, step i-2
+            const int s = i - 2;
+            if (s >= 0) {
+                const uint32_t *recs = lds + L::REC + (s & 1) * L::REC_SIZE;
+#pragma unroll
+                for (int j = 0; j < MYR; ++j)
+                    if (win[j].active) consume_window(recs, win[j], block);
+                if (c == V::NC - 1) {
+                    const uint32_t *out = lds + L::OUT + (s & 3) * 128;
+                    *rw = __uint_as_float(out[lane]);
+                    *dn = (uint8_t)out[64 + lane];
+                }
+                block += step_obs;
+                rw += p.N;
+                dn += p.N;
             }
         }
-        // fewer than ACT_RING steps left: their actions are ring[0..]
-#pragma unroll
-        for (int i = 0; i < ACT_RING - 1; ++i)
-            if (s + i < n_steps) step(s + i, ring[i]);
+        __syncthreads();
+    }
+    if (wave == 0) {
         p.pose[n] = (uint32_t)xd | ((uint32_t)yd << 8) | ((uint32_t)d << 16);
         p.tcount[n] = t;
-        __syncthreads();
-    } else {
-        // ------------------------------------------------------------ consumer
-        const int c = wave - 1;
-        constexpr int MYR = (V::ROUNDS + NC - 1) / NC;     // rounds per consumer, at most
-        Window win[MYR];
-#pragma unroll
-        for (int j = 0; j < MYR; ++j) {
-            int round = c + j * NC;
-            win[j] = make_window<K>(lane, round < V::ROUNDS ? round : 0);
-            if (round >= V::ROUNDS) win[j].active = 0;
-        }
-        const size_t step_obs = (size_t)p.N * V::SB;
-        int8_t *block = obs + (size_t)env0 * V::SB;
-        float *rw = reward + env0 + lane;
-        uint8_t *dn = done + env0 + lane;
-        for (int s = 0; s < n_steps; ++s) {
-            __syncthreads();
-            const uint32_t *buf = lds + L::BUF0 + (s & 1) * L::BUF_SIZE;
-#pragma unroll
-            for (int j = 0; j < MYR; ++j)
-                if (win[j].active) consume_window(buf + L::BUF_REC, win[j], block);
-            if (c == NC - 1) {
-                *rw = __uint_as_float(buf[L::BUF_REW + lane]);
-                *dn = (uint8_t)buf[L::BUF_DONE + lane];
-            }
-            block += step_obs;
-            rw += p.N;
-            dn += p.N;
-        }
-        __syncthreads();
     }
 }
 
@@ -361,16 +401,17 @@ __global__ __launch_bounds__(64) void k_render_tiled(StudentDev p, int8_t *__res
     int xd = pose & 255, yd = (pose >> 8) & 255, d = (pose >> 16) & 3;
     Word rows[K];
     load_view_rows<K, Word, false>(nullptr, glob_env, p.SP, d, yd, rows);
-    uint32_t *buf = lds + L::BUF0;
+    uint32_t vw[V::WV];
+    pack_view<K, Word>(rows, xd, vw);
     const uint32_t g = p.goalrot[4 * (size_t)n + d];
-    produce_record<K, Word>(lds + L::LUT, buf + L::BUF_REC + lane * V::REC, rows, xd,
-                            yd - (int)(g >> 8), (int)(g & 255) - xd);
+    produce_record<K>(lds + L::LUT, lds + L::REC + lane * V::REC, vw, yd - (int)(g >> 8),
+                      (int)(g & 255) - xd);
     __syncthreads();
     int8_t *block = obs + (size_t)env0 * V::SB;
 #pragma unroll
     for (int j = 0; j < V::ROUNDS; ++j) {
         Window w = make_window<K>(lane, j);
-        if (w.active) consume_window(buf + L::BUF_REC, w, block);
+        if (w.active) consume_window(lds + L::REC, w, block);
     }
 }
 
@@ -379,21 +420,20 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
              uint8_t *d_done, int8_t *d_obs, int groups, hipStream_t st)
 {
     using V = View<K>;
-    constexpr int NC = V::ROUNDS < 3 ? V::ROUNDS : 3;      // consumer waves per workgroup
     const StudentDev &p = ctx->dev;
     // stage the grids in LDS when the workgroup's 64 envs fit in 64 KB, else read rows from L2
     bool grid_lds = Lds<K, Word>::bytes(p.SP, true) <= 64 * 1024;
     size_t shmem = Lds<K, Word>::bytes(p.SP, grid_lds);
     size_t shmem_render = Lds<K, Word>::bytes(p.SP, false);
-    dim3 grid(groups), block(64 * (1 + NC));
+    dim3 grid(groups), block(64 * V::WAVES);
     if (n_steps == 0) {
         hipLaunchKernelGGL((k_render_tiled<K, Word>), grid, dim3(64), shmem_render, st, p, d_obs);
     } else if (grid_lds) {
-        hipLaunchKernelGGL((k_student_rollout<K, Word, true, NC>), grid, block, shmem, st, p,
-                           d_actions, n_steps, d_reward, d_done, d_obs);
+        hipLaunchKernelGGL((k_student_rollout<K, Word, true>), grid, block, shmem, st, p, d_actions,
+                           n_steps, d_reward, d_done, d_obs);
     } else {
-        hipLaunchKernelGGL((k_student_rollout<K, Word, false, NC>), grid, block, shmem, st, p,
-                           d_actions, n_steps, d_reward, d_done, d_obs);
+        hipLaunchKernelGGL((k_student_rollout<K, Word, false>), grid, block, shmem, st, p, d_actions,
+                           n_steps, d_reward, d_done, d_obs);
     }
     return 1;
 }
@@ -411,8 +451,10 @@ int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_ste
     if (!d_obs) return 0;
     const int K = p.k;
     if (K != 3 && K != 5 && K != 7) return 0;
-    // 16-byte stores: every time step's block and the buffer itself must be 16-byte aligned
+    // 16-byte accesses: every time step's obs block, the obs buffer and each step's row of
+    // actions must be 16-byte aligned
     if ((((size_t)p.N * 3 * K * K) & 15) != 0 || ((uintptr_t)d_obs & 15) != 0) return 0;
+    if (n_steps > 0 && ((p.N & 15) != 0 || ((uintptr_t)d_actions & 15) != 0)) return 0;
     int full = p.N / 64;
     if (full == 0) return 0;
     int rc;
