@@ -24,6 +24,8 @@
 #include "maze_internal.h"
 #include "maze_student_device.h"
 
+#include <type_traits>
+
 namespace {
 
 template <int K>
@@ -43,6 +45,7 @@ struct View {
 };
 
 constexpr int ACT_BLOCK = 16;   // steps of actions staged per global load of the dynamics wave
+constexpr int SPB = 4;          // steps per barrier: every stage handles SPB steps between barriers
 
 // 4 stream bits -> 4 bytes (bit j -> byte j).  The four shifted copies do not
 // overlap, so the multiply carries nothing.
@@ -55,18 +58,19 @@ template <typename Word> struct WordOps;
 template <> struct WordOps<uint32_t> { static constexpr int DW = 1; };
 template <> struct WordOps<uint64_t> { static constexpr int DW = 2; };
 
-// Per-workgroup LDS carve-up (dword offsets).
+// Per-workgroup LDS carve-up (dword offsets).  ST and REC hold SPB steps each and
+// are double buffered by block parity (a block = the SPB steps between two barriers).
 template <int K, typename Word>
 struct Lds {
     using V = View<K>;
     static constexpr int LUT = 0;                                  // [LUTN]
     static constexpr int ACT = LUT + V::LUTN;                      // [2][ACT_BLOCK][16] action bytes
-    static constexpr int ST = ACT + 2 * ACT_BLOCK * 16;            // [2][WV+1][64] view bits, goal offset
-    static constexpr int ST_SIZE = (V::WV + 1) * 64;
-    static constexpr int OUT = ST + 2 * ST_SIZE;                   // [4][2][64] reward bits, done
-    static constexpr int REC = OUT + 4 * 128;                      // [2][64*REC] stream records
-    static constexpr int REC_SIZE = 64 * V::REC;
-    static constexpr int GRID0 = REC + 2 * REC_SIZE;               // [64][grid_stride]
+    static constexpr int ST = ACT + 2 * ACT_BLOCK * 16;            // [2][SPB][WV+2][64] view bits, goal, out
+    static constexpr int ST_SIZE = (V::WV + 2) * 64;
+    static constexpr int REC = ST + 2 * SPB * ST_SIZE;             // [2][SPB]{[64*REC] records, [64] out}
+    static constexpr int REC_OUT = 64 * V::REC;
+    static constexpr int REC_SIZE = 64 * V::REC + 64;
+    static constexpr int GRID0 = REC + 2 * SPB * REC_SIZE;         // [64][grid_stride]
     __host__ __device__ static int grid_stride(int SP)             // dwords per env, odd
     {
         return (4 * SP * WordOps<Word>::DW) | 1;
@@ -111,7 +115,8 @@ __device__ __forceinline__ void pack_view(const Word (&rows)[K], int xd, uint32_
     for (int q = 0; q < V::WV; ++q) vw[q] = 0;
 #pragma unroll
     for (int r = 0; r < K; ++r) {
-        uint32_t bits = (uint32_t)(rows[r] >> sh) & (V::LUTN - 1);
+        uint32_t bits = sizeof(Word) == 4 ? __builtin_amdgcn_ubfe((uint32_t)rows[r], sh, K)
+                                          : (uint32_t)(rows[r] >> sh) & (V::LUTN - 1);
         vw[r / V::RPD] |= bits << (K * (r % V::RPD));
     }
 }
@@ -226,7 +231,14 @@ __device__ __forceinline__ void stage_grids(const StudentDev &p, uint32_t *lds, 
 }
 
 // ------------------------------------------------------------------ rollout
-template <int K, typename Word, bool GRID_LDS>
+// Each role runs its own loop over blocks of SPB steps; every wave passes exactly
+// ceil(n_steps / SPB) + 3 barriers.
+//   between barriers b and b+1:  dynamics builds block b   -> ST[b&1]
+//                                records  builds block b-1 -> REC[(b-1)&1]  (reads ST[(b-1)&1])
+//                                stores   drain  block b-2                  (read REC[(b-2)&1])
+// so no buffer is written while it is read.  The block loops are unrolled by two so
+// every LDS address is a lane constant plus an immediate.
+template <int K, typename Word, bool GRID_LDS, bool SQUARE>
 __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
     StudentDev p, const int8_t *__restrict__ actions, int n_steps, float *__restrict__ reward,
     uint8_t *__restrict__ done, int8_t *__restrict__ obs)
@@ -239,147 +251,177 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int env0 = blockIdx.x * 64;
     const int n = env0 + lane;
-    const int last = n_steps - 1;
 
     fill_lut<K, Word>(lds, tid, NT);
     if (GRID_LDS) stage_grids<K, Word>(p, lds, tid, NT, env0);
 
-    // ---- dynamics wave: state, constants, first block of actions
-    int xd = 0, yd = 0, d = 0, gf = 0, gc = 0, sxd = 0, syd = 0, sd = 0, sgf = 0, sgc = 0;
-    uint32_t t = 0, a_next = 3;
-    Word ahead = 0;
-    uint4 act_regs = make_uint4(0, 0, 0, 0);
-    const uint32_t *lds_env = lds + L::GRID0 + lane * (GRID_LDS ? L::grid_stride(p.SP) : 0);
-    const Word *glob_env = (const Word *)p.grids + (size_t)n * 4 * p.SP;
-    // lane l stages the action bytes of step (block*16 + l/4), envs 16*(l%4) .. +15
-    const int8_t *act_lane = actions + env0 + 16 * (lane & 3);
-    auto load_actions = [&](int block) {
-        int s = min(block * ACT_BLOCK + (lane >> 2), last);
-        return *(const uint4 *)(act_lane + (size_t)s * p.N);
-    };
     if (wave == 0) {
+        // ================================================================ dynamics
+        const int last = n_steps - 1;
         uint32_t pose = p.pose[n];
-        xd = pose & 255; yd = (pose >> 8) & 255; d = (pose >> 16) & 3;
-        t = p.tcount[n];
+        int xd = pose & 255, yd = (pose >> 8) & 255, d = (pose >> 16) & 3;
+        uint32_t t = p.tcount[n];
         const uint32_t start = p.start[n];
-        sxd = start & 255; syd = (start >> 8) & 255; sd = (start >> 16) & 3;
+        const int sxd = start & 255, syd = (start >> 8) & 255, sd = (start >> 16) & 3;
         // goal relative to the agent in the agent's own frame: gf cells ahead, gc cells to
         // the right.  Turning rotates this vector, moving forward shortens gf.
         const uint32_t g_now = p.goalrot[4 * (size_t)n + d], g_start = p.goalrot[4 * (size_t)n + sd];
-        gf = yd - (int)(g_now >> 8); gc = (int)(g_now & 255) - xd;
-        sgf = syd - (int)(g_start >> 8); sgc = (int)(g_start & 255) - sxd;
+        int gf = yd - (int)(g_now >> 8), gc = (int)(g_now & 255) - xd;
+        const int sgf = syd - (int)(g_start >> 8), sgc = (int)(g_start & 255) - sxd;
+        const uint32_t tmax = (uint32_t)p.max_steps;
+        const int HPm1 = p.HP - 1, WPm1 = p.WP - 1;
+        const uint32_t *lds_env = lds + L::GRID0 + lane * (GRID_LDS ? L::grid_stride(p.SP) : 0);
+        const Word *glob_env = (const Word *)p.grids + (size_t)n * 4 * p.SP;
+        // actions: lane l stages the bytes of step (block*16 + l/4), envs 16*(l%4) .. +15
+        const int8_t *act_lane = actions + env0 + 16 * (lane & 3);
+        auto load_actions = [&](int block) {
+            int s = min(block * ACT_BLOCK + (lane >> 2), last);
+            return *(const uint4 *)(act_lane + (size_t)s * p.N);
+        };
         ((uint4 *)(lds + L::ACT))[lane] = load_actions(0);
-        act_regs = load_actions(1);
-    }
-    __syncthreads();
-    if (wave == 0) {
+        uint4 act_regs = load_actions(1);
+        __syncthreads();                                             // barrier 0 (set-up)
         Word rows[K];
         load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, p.SP, d, yd, rows);
-        ahead = rows[K - 2];           // wall word of the row just ahead of the agent
-        a_next = ((const uint8_t *)(lds + L::ACT))[lane];
-    }
+        Word ahead = rows[K - 2];          // wall word of the row just ahead of the agent
+        const uint8_t *act_lds = (const uint8_t *)(lds + L::ACT) + lane;
+        uint32_t act_off = 0;              // byte offset of the current step's row in the ring
+        uint32_t a_next = act_lds[0];
 
-    // ---- store waves: windows and output cursors
-    const int c = wave - 2;
-    constexpr int MYR = (V::ROUNDS + V::NC - 1) / V::NC;     // rounds per store wave, at most
-    Window win[MYR];
-#pragma unroll
-    for (int j = 0; j < MYR; ++j) win[j] = make_window<K>(lane, (c < 0 ? 0 : c) + j * V::NC);
-    const size_t step_obs = (size_t)p.N * V::SB;
-    int8_t *block = obs + (size_t)env0 * V::SB;
-    float *rw = reward + n;
-    uint8_t *dn = done + n;
-
-    const uint32_t tmax = (uint32_t)p.max_steps;
-    const double slope = p.reward_slope;
-    const int HPm1 = p.HP - 1, WPm1 = p.WP - 1;
-
-    for (int i = 0; i < n_steps + 2; ++i) {
-        if (wave == 0) {
-            // ------------------------------------------------ dynamics, step i
-            if (i < n_steps) {
-                const uint32_t a = a_next;
-                // action of the next step (its block was staged at least 8 steps ago)
-                {
-                    const int s1 = min(i + 1, last);
-                    a_next = ((const uint8_t *)(lds + L::ACT))[((s1 / ACT_BLOCK) & 1) * (ACT_BLOCK * 64) +
-                                                              (s1 % ACT_BLOCK) * 64 + lane];
-                }
-                t += 1;
-                const int blocked = (int)((ahead >> xd) & 1);
-                const int odd = d & 1;
-                const int rows_m1 = odd ? HPm1 : WPm1;
-                const int bits_m1 = odd ? WPm1 : HPm1;
-                const int tl = (a == 0), tr = (a == 1), fw = (a == 2) & (blocked ^ 1);
-                const int x_l = rows_m1 - yd, y_r = bits_m1 - xd, y_f = yd - fw;
-                const int nx = tl ? x_l : (tr ? yd : xd);
-                const int ny = tl ? xd : (tr ? y_r : y_f);
-                const int nf = tl ? -gc : (tr ? gc : gf - fw);
-                const int nc = tl ? gf : (tr ? -gf : gc);
-                d = (d + 3 * tl + tr) & 3;
-                const int reached = ((nf | nc) == 0);
-                const int fin = reached | (t >= tmax);
-                const float r = reached ? (float)(1.0 - (double)t * slope) : 0.0f;
-                xd = fin ? sxd : nx;
-                yd = fin ? syd : ny;
-                d = fin ? sd : d;
-                t = fin ? 0u : t;
-                gf = fin ? sgf : nf;
-                gc = fin ? sgc : nc;
-                Word rows[K];
-                load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, p.SP, d, yd, rows);
-                ahead = rows[K - 2];
-                uint32_t vw[V::WV];
-                pack_view<K, Word>(rows, xd, vw);
-                uint32_t *st = lds + L::ST + (i & 1) * L::ST_SIZE;
-#pragma unroll
-                for (int q = 0; q < V::WV; ++q) st[q * 64 + lane] = vw[q];
-                st[V::WV * 64 + lane] = (uint32_t)(gf & 0xFFFF) | ((uint32_t)gc << 16);
-                uint32_t *out = lds + L::OUT + (i & 3) * 128;
-                out[lane] = __float_as_uint(r);
-                out[64 + lane] = (uint32_t)fin;
-                // stage the next block of actions half way through the current one
-                if ((i % ACT_BLOCK) == ACT_BLOCK / 2) {
-                    const int nb = i / ACT_BLOCK + 1;
-                    ((uint4 *)(lds + L::ACT))[(nb & 1) * 64 + lane] = act_regs;
-                    act_regs = load_actions(nb + 1);
-                }
+        auto step = [&](int i, int slot) {
+            const uint32_t a = a_next;
+            act_off = (act_off + 64) & (2 * ACT_BLOCK * 64 - 1);
+            a_next = act_lds[act_off];     // next step's action (staged >= 8 steps ago)
+            t += 1;
+            const int blocked = sizeof(Word) == 4 ? (int)__builtin_amdgcn_ubfe((uint32_t)ahead, xd, 1)
+                                                  : (int)((ahead >> xd) & 1);
+            const bool tl = (a == 0), tr = (a == 1);
+            const int fw = (a == 2) ? (blocked ^ 1) : 0;
+            int rows_m1 = WPm1, bits_m1 = WPm1;
+            if (!SQUARE) {
+                const bool odd = d & 1;
+                rows_m1 = odd ? HPm1 : WPm1;
+                bits_m1 = odd ? WPm1 : HPm1;
             }
-        } else if (wave == 1) {
-            // ------------------------------------------------ records, step i-1
-            const int s = i - 1;
-            if (s >= 0 && s < n_steps) {
-                const uint32_t *st = lds + L::ST + (s & 1) * L::ST_SIZE;
-                uint32_t vw[V::WV];
+            const int nx = tl ? rows_m1 - yd : (tr ? yd : xd);
+            const int ny = tl ? xd : (tr ? bits_m1 - xd : yd - fw);
+            const int nf = tl ? -gc : (tr ? gc : gf - fw);
+            const int nc = tl ? gf : (tr ? -gf : gc);
+            d = (d + (tl ? 3 : 0) + (tr ? 1 : 0)) & 3;
+            const bool reached = ((nf | nc) == 0);
+            const bool fin = reached | (t >= tmax);
+            // out word for the store wave: step count if the goal was reached, done in bit 31
+            const uint32_t out = (reached ? t : 0u) | (fin ? 0x80000000u : 0u);
+            xd = fin ? sxd : nx;
+            yd = fin ? syd : ny;
+            d = fin ? sd : d;
+            t = fin ? 0u : t;
+            gf = fin ? sgf : nf;
+            gc = fin ? sgc : nc;
+            load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, p.SP, d, yd, rows);
+            ahead = rows[K - 2];
+            uint32_t vw[V::WV];
+            pack_view<K, Word>(rows, xd, vw);
+            uint32_t *st = lds + L::ST + slot * L::ST_SIZE + lane;
 #pragma unroll
-                for (int q = 0; q < V::WV; ++q) vw[q] = st[q * 64 + lane];
-                const uint32_t g = st[V::WV * 64 + lane];
-                produce_record<K>(lds + L::LUT, lds + L::REC + (s & 1) * L::REC_SIZE + lane * V::REC, vw,
-                                  (int)(int16_t)(g & 0xFFFF), (int)g >> 16);
+            for (int q = 0; q < V::WV; ++q) st[q * 64] = vw[q];
+            st[V::WV * 64] = (uint32_t)(gf & 0xFFFF) | ((uint32_t)gc << 16);
+            st[(V::WV + 1) * 64] = out;
+            // stage the next block of actions half way through the current one
+            if ((i & (ACT_BLOCK - 1)) == ACT_BLOCK / 2) {
+                const int nb = i / ACT_BLOCK + 1;
+                ((uint4 *)(lds + L::ACT))[(nb & 1) * 64 + lane] = act_regs;
+                act_regs = load_actions(nb + 1);
             }
-        } else {
-            // ------------------------------------------------ stores, step i-2
-            const int s = i - 2;
-            if (s >= 0) {
-                const uint32_t *recs = lds + L::REC + (s & 1) * L::REC_SIZE;
+        };
+        auto block = [&](int i0, auto PAR) {
 #pragma unroll
-                for (int j = 0; j < MYR; ++j)
-                    if (win[j].active) consume_window(recs, win[j], block);
-                if (c == V::NC - 1) {
-                    const uint32_t *out = lds + L::OUT + (s & 3) * 128;
-                    *rw = __uint_as_float(out[lane]);
-                    *dn = (uint8_t)out[64 + lane];
-                }
-                block += step_obs;
+            for (int u = 0; u < SPB; ++u)
+                if (i0 + u < n_steps) step(i0 + u, decltype(PAR)::value * SPB + u);
+            __syncthreads();
+        };
+        int i = 0;
+        for (; i + SPB < n_steps; i += 2 * SPB) {
+            block(i, std::integral_constant<int, 0>());
+            block(i + SPB, std::integral_constant<int, 1>());
+        }
+        if (i < n_steps) block(i, std::integral_constant<int, 0>());
+        p.pose[n] = (uint32_t)xd | ((uint32_t)yd << 8) | ((uint32_t)d << 16);
+        p.tcount[n] = t;
+        __syncthreads();
+        __syncthreads();
+    } else if (wave == 1) {
+        // ================================================================= records
+        __syncthreads();                                             // barrier 0 (set-up)
+        __syncthreads();                                             // block 0 published
+        auto step = [&](int slot) {
+            const uint32_t *st = lds + L::ST + slot * L::ST_SIZE + lane;
+            uint32_t vw[V::WV];
+#pragma unroll
+            for (int q = 0; q < V::WV; ++q) vw[q] = st[q * 64];
+            const uint32_t g = st[V::WV * 64];
+            const uint32_t out = st[(V::WV + 1) * 64];
+            uint32_t *rec = lds + L::REC + slot * L::REC_SIZE;
+            rec[L::REC_OUT + lane] = out;
+            produce_record<K>(lds + L::LUT, rec + lane * V::REC, vw, (int)(int16_t)(g & 0xFFFF),
+                              (int)g >> 16);
+        };
+        auto block = [&](int s0, auto PAR) {
+#pragma unroll
+            for (int u = 0; u < SPB; ++u)
+                if (s0 + u < n_steps) step(decltype(PAR)::value * SPB + u);
+            __syncthreads();
+        };
+        int s = 0;
+        for (; s + SPB < n_steps; s += 2 * SPB) {
+            block(s, std::integral_constant<int, 0>());
+            block(s + SPB, std::integral_constant<int, 1>());
+        }
+        if (s < n_steps) block(s, std::integral_constant<int, 0>());
+        __syncthreads();
+    } else {
+        // ================================================================== stores
+        const int c = wave - 2;
+        constexpr int MYR = (V::ROUNDS + V::NC - 1) / V::NC;     // rounds per store wave, at most
+        Window win[MYR];
+#pragma unroll
+        for (int j = 0; j < MYR; ++j) win[j] = make_window<K>(lane, c + j * V::NC);
+        const size_t step_obs = (size_t)p.N * V::SB;
+        int8_t *out_block = obs + (size_t)env0 * V::SB;
+        float *rw = reward + n;
+        uint8_t *dn = done + n;
+        const double slope = p.reward_slope;
+        const bool aux = (c == V::NC - 1);                       // this wave also writes reward/done
+        __syncthreads();                                             // barrier 0 (set-up)
+        __syncthreads();                                             // block 0 published
+        __syncthreads();                                             // block 0 recorded
+        auto step = [&](int slot) {
+            const uint32_t *rec = lds + L::REC + slot * L::REC_SIZE;
+#pragma unroll
+            for (int j = 0; j < MYR; ++j)
+                if (win[j].active) consume_window(rec, win[j], out_block);
+            out_block += step_obs;
+            if (aux) {
+                const uint32_t out = rec[L::REC_OUT + lane];
+                const uint32_t tr = out & 0x7FFFFFFFu;
+                *rw = tr ? (float)(1.0 - (double)tr * slope) : 0.0f;
+                *dn = (uint8_t)(out >> 31);
                 rw += p.N;
                 dn += p.N;
             }
+        };
+        auto block = [&](int s0, auto PAR) {
+#pragma unroll
+            for (int u = 0; u < SPB; ++u)
+                if (s0 + u < n_steps) step(decltype(PAR)::value * SPB + u);
+            __syncthreads();
+        };
+        int s = 0;
+        for (; s + SPB < n_steps; s += 2 * SPB) {
+            block(s, std::integral_constant<int, 0>());
+            block(s + SPB, std::integral_constant<int, 1>());
         }
-        __syncthreads();
-    }
-    if (wave == 0) {
-        p.pose[n] = (uint32_t)xd | ((uint32_t)yd << 8) | ((uint32_t)d << 16);
-        p.tcount[n] = t;
+        if (s < n_steps) block(s, std::integral_constant<int, 0>());
     }
 }
 
@@ -428,12 +470,15 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
     dim3 grid(groups), block(64 * V::WAVES);
     if (n_steps == 0) {
         hipLaunchKernelGGL((k_render_tiled<K, Word>), grid, dim3(64), shmem_render, st, p, d_obs);
+    } else if (grid_lds && p.HP == p.WP) {
+        hipLaunchKernelGGL((k_student_rollout<K, Word, true, true>), grid, block, shmem, st, p,
+                           d_actions, n_steps, d_reward, d_done, d_obs);
     } else if (grid_lds) {
-        hipLaunchKernelGGL((k_student_rollout<K, Word, true>), grid, block, shmem, st, p, d_actions,
-                           n_steps, d_reward, d_done, d_obs);
+        hipLaunchKernelGGL((k_student_rollout<K, Word, true, false>), grid, block, shmem, st, p,
+                           d_actions, n_steps, d_reward, d_done, d_obs);
     } else {
-        hipLaunchKernelGGL((k_student_rollout<K, Word, false>), grid, block, shmem, st, p, d_actions,
-                           n_steps, d_reward, d_done, d_obs);
+        hipLaunchKernelGGL((k_student_rollout<K, Word, false, false>), grid, block, shmem, st, p,
+                           d_actions, n_steps, d_reward, d_done, d_obs);
     }
     return 1;
 }
