@@ -239,7 +239,7 @@ __global__ void k_render_percell(StudentDev p, int n_begin, int8_t *__restrict__
 }
 
 // Implemented in maze_student_tiled.hip: launches the tiled kernel on the first
-// *covered envs (a multiple of 64; 0 if the shape is not covered) and returns 1 if
+// *covered envs (a multiple of the workgroup size; 0 if the shape is not covered) and returns 1 if
 // it launched.  n_steps == 0 renders the current state.
 int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_steps,
                          float *d_reward, uint8_t *d_done, int8_t *d_obs, int *covered,

@@ -1,23 +1,25 @@
 // Tiled store-layout kernels of the student env.
 //
-// A workgroup owns 64 consecutive envs for the whole rollout.  Per step one lane
-// per env advances the env (state in registers, wall rows from LDS) and its
-// observation is built as a BIT STREAM -- bit i of the stream is byte i of the
-// env's k*k*3 observation, which is 0 or 1 -- and left in LDS.  The 64 streams,
-// concatenated, are exactly the 64*3k^2 contiguous output bytes of this time
-// step, so other lanes then take 16 consecutive stream bits each (they may
+// A workgroup owns EPW = 128 consecutive envs for the whole rollout (128 * 3k^2
+// bytes per step is a whole number of 128-byte lines, so no line of the output is
+// shared between workgroups).  Per step one lane per env advances the env (state in
+// registers, wall rows from LDS) and its observation is built as a BIT STREAM --
+// bit i of the stream is byte i of the env's k*k*3 observation, which is 0 or 1 --
+// and left in LDS.  The 128 streams, concatenated, are exactly the 128*3k^2
+// contiguous output bytes of this time step, so other lanes then take 16 consecutive stream bits each (they may
 // straddle two envs), expand each bit to a byte and write 16 contiguous bytes;
 // consecutive lanes take consecutive pieces, so one store instruction of a wave
 // writes 1 KB of contiguous, aligned output.
 //
 // The per-step work is a three-stage pipeline over the waves of the workgroup,
-// advanced by one barrier per step:
-//   wave 0 ("dynamics")  step s  : action, move, goal/done/reset, reads the K
-//                                  wall rows of the new view and publishes the
-//                                  K x K view bits, the goal offset, reward, done
-//   wave 1 ("records")   step s-1: view bits -> stream record (row lookup table),
-//                                  goal cell patched in
-//   waves 2.. ("stores") step s-2: expand records to bytes, store obs/reward/done
+// advanced by one barrier per block of SPB steps:
+//   waves 0,1 ("dynamics") block b  : action, move, goal/done/reset, read the K
+//                                     wall rows of the new view and publish the
+//                                     K x K view bits, the goal offset, reward, done
+//   waves 2,3 ("records")  block b-1: view bits -> stream record (row lookup table),
+//                                     goal cell patched in; store reward and done
+//   waves 4.. ("stores")   block b-2: expand records to bytes, store obs
+// (one dynamics and one records wave per 64 envs)
 // Only the dynamics wave carries a dependency from step to step, so the time per
 // step is that wave's short chain; the store waves never load from global memory
 // and the dynamics wave touches it once every 16 steps (actions, staged in LDS).
@@ -28,24 +30,27 @@
 
 namespace {
 
+constexpr int EPW = 128;        // envs per workgroup
+constexpr int HALVES = EPW / 64;
+
 template <int K>
 struct View {
     static constexpr int CELLS = K * K;
     static constexpr int SB = 3 * CELLS;           // stream bits (= obs bytes) per env
     static constexpr int ND = (SB + 31) / 32;      // data dwords per env record
     static constexpr int REC = ND + 1;             // record = data dwords + one zero dword
-    static constexpr int NWIN = 4 * SB;            // 16-bit windows per 64-env step
+    static constexpr int NWIN = EPW * SB / 16;     // 16-bit windows per workgroup step
     static constexpr int ROUNDS = (NWIN + 63) / 64;
     static constexpr int LUTN = 1 << K;            // row pattern -> 3K stream bits
     static constexpr int ROWBITS = 3 * K;
     static constexpr int RPD = 32 / K;             // view rows packed per dword
     static constexpr int WV = (K + RPD - 1) / RPD; // dwords of packed view bits
-    static constexpr int NC = ROUNDS < 5 ? ROUNDS : 5;   // store waves per workgroup
-    static constexpr int WAVES = 2 + NC;
+    static constexpr int NC = ROUNDS < 10 ? ROUNDS : 10; // store waves per workgroup
+    static constexpr int WAVES = 2 * HALVES + NC;
 };
 
 constexpr int ACT_BLOCK = 16;   // steps of actions staged per global load of the dynamics wave
-constexpr int SPB = 4;          // steps per barrier: every stage handles SPB steps between barriers
+constexpr int SPB = 2;          // steps per barrier: every stage handles SPB steps between barriers
 
 // 4 stream bits -> 4 bytes (bit j -> byte j).  The four shifted copies do not
 // overlap, so the multiply carries nothing.
@@ -64,20 +69,20 @@ template <int K, typename Word>
 struct Lds {
     using V = View<K>;
     static constexpr int LUT = 0;                                  // [LUTN]
-    static constexpr int ACT = LUT + V::LUTN;                      // [2][ACT_BLOCK][16] action bytes
-    static constexpr int ST = ACT + 2 * ACT_BLOCK * 16;            // [2][SPB][WV+2][64] view bits, goal, out
-    static constexpr int ST_SIZE = (V::WV + 2) * 64;
-    static constexpr int REC = ST + 2 * SPB * ST_SIZE;             // [2][SPB]{[64*REC] records, [64] out}
-    static constexpr int REC_OUT = 64 * V::REC;
-    static constexpr int REC_SIZE = 64 * V::REC + 64;
-    static constexpr int GRID0 = REC + 2 * SPB * REC_SIZE;         // [64][grid_stride]
+    static constexpr int ACT = LUT + V::LUTN;                      // [2][ACT_BLOCK][EPW] action bytes
+    static constexpr int ACT_ROW = EPW;                            // bytes per step
+    static constexpr int ST = ACT + 2 * ACT_BLOCK * EPW / 4;       // [2][SPB][WV+2][EPW] view bits, goal, out
+    static constexpr int ST_SIZE = (V::WV + 2) * EPW;
+    static constexpr int REC = ST + 2 * SPB * ST_SIZE;             // [2][SPB][EPW*REC] stream records
+    static constexpr int REC_SIZE = EPW * V::REC;
+    static constexpr int GRID0 = REC + 2 * SPB * REC_SIZE;         // [EPW][grid_stride]
     __host__ __device__ static int grid_stride(int SP)             // dwords per env, odd
     {
         return (4 * SP * WordOps<Word>::DW) | 1;
     }
     __host__ static size_t bytes(int SP, bool grid_in_lds)
     {
-        return 4 * (size_t)(GRID0 + (grid_in_lds ? 64 * grid_stride(SP) : 0));
+        return 4 * (size_t)(GRID0 + (grid_in_lds ? EPW * grid_stride(SP) : 0));
     }
 };
 
@@ -212,7 +217,7 @@ __device__ __forceinline__ void fill_lut(uint32_t *lds, int tid, int nthreads)
     }
 }
 
-// Copy the workgroup's 64 envs' grids into LDS (all threads take part).
+// Copy the workgroup's envs' grids into LDS (all threads take part).
 template <int K, typename Word>
 __device__ __forceinline__ void stage_grids(const StudentDev &p, uint32_t *lds, int tid, int nthreads,
                                             int env0)
@@ -223,7 +228,7 @@ __device__ __forceinline__ void stage_grids(const StudentDev &p, uint32_t *lds, 
     const uint32_t *src = (const uint32_t *)p.grids + (size_t)env0 * per_env;
     int e = 0, o = tid;
     while (o >= per_env) { o -= per_env; ++e; }
-    while (e < 64) {
+    while (e < EPW) {
         base[e * gs + o] = src[(size_t)e * per_env + o];
         o += nthreads;
         while (o >= per_env) { o -= per_env; ++e; }
@@ -249,14 +254,15 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
     extern __shared__ uint32_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int env0 = blockIdx.x * 64;
-    const int n = env0 + lane;
+    const int env0 = blockIdx.x * EPW;
 
     fill_lut<K, Word>(lds, tid, NT);
     if (GRID_LDS) stage_grids<K, Word>(p, lds, tid, NT, env0);
 
-    if (wave == 0) {
+    if (wave < HALVES) {
         // ================================================================ dynamics
+        const int e = wave * 64 + lane;            // env within the workgroup
+        const int n = env0 + e;
         const int last = n_steps - 1;
         uint32_t pose = p.pose[n];
         int xd = pose & 255, yd = (pose >> 8) & 255, d = (pose >> 16) & 3;
@@ -270,27 +276,30 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
         const int sgf = syd - (int)(g_start >> 8), sgc = (int)(g_start & 255) - sxd;
         const uint32_t tmax = (uint32_t)p.max_steps;
         const int HPm1 = p.HP - 1, WPm1 = p.WP - 1;
-        const uint32_t *lds_env = lds + L::GRID0 + lane * (GRID_LDS ? L::grid_stride(p.SP) : 0);
+        const uint32_t *lds_env = lds + L::GRID0 + e * (GRID_LDS ? L::grid_stride(p.SP) : 0);
         const Word *glob_env = (const Word *)p.grids + (size_t)n * 4 * p.SP;
-        // actions: lane l stages the bytes of step (block*16 + l/4), envs 16*(l%4) .. +15
-        const int8_t *act_lane = actions + env0 + 16 * (lane & 3);
+        // actions: lane l of this wave stages the bytes of step (block*16 + l/4) for its
+        // 64 envs, 16 envs per lane
+        const int stage_col = wave * 64 + 16 * (lane & 3);
+        const int8_t *act_lane = actions + env0 + stage_col;
+        uint8_t *act_stage = (uint8_t *)(lds + L::ACT) + (lane >> 2) * L::ACT_ROW + stage_col;
         auto load_actions = [&](int block) {
             int s = min(block * ACT_BLOCK + (lane >> 2), last);
             return *(const uint4 *)(act_lane + (size_t)s * p.N);
         };
-        ((uint4 *)(lds + L::ACT))[lane] = load_actions(0);
+        *(uint4 *)act_stage = load_actions(0);
         uint4 act_regs = load_actions(1);
         __syncthreads();                                             // barrier 0 (set-up)
         Word rows[K];
         load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, p.SP, d, yd, rows);
         Word ahead = rows[K - 2];          // wall word of the row just ahead of the agent
-        const uint8_t *act_lds = (const uint8_t *)(lds + L::ACT) + lane;
+        const uint8_t *act_lds = (const uint8_t *)(lds + L::ACT) + e;
         uint32_t act_off = 0;              // byte offset of the current step's row in the ring
         uint32_t a_next = act_lds[0];
 
         auto step = [&](int i, int slot) {
             const uint32_t a = a_next;
-            act_off = (act_off + 64) & (2 * ACT_BLOCK * 64 - 1);
+            act_off = (act_off + L::ACT_ROW) & (2 * ACT_BLOCK * L::ACT_ROW - 1);
             a_next = act_lds[act_off];     // next step's action (staged >= 8 steps ago)
             t += 1;
             const int blocked = sizeof(Word) == 4 ? (int)__builtin_amdgcn_ubfe((uint32_t)ahead, xd, 1)
@@ -310,7 +319,7 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
             d = (d + (tl ? 3 : 0) + (tr ? 1 : 0)) & 3;
             const bool reached = ((nf | nc) == 0);
             const bool fin = reached | (t >= tmax);
-            // out word for the store wave: step count if the goal was reached, done in bit 31
+            // out word: step count if the goal was reached, done in bit 31
             const uint32_t out = (reached ? t : 0u) | (fin ? 0x80000000u : 0u);
             xd = fin ? sxd : nx;
             yd = fin ? syd : ny;
@@ -322,15 +331,15 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
             ahead = rows[K - 2];
             uint32_t vw[V::WV];
             pack_view<K, Word>(rows, xd, vw);
-            uint32_t *st = lds + L::ST + slot * L::ST_SIZE + lane;
+            uint32_t *st = lds + L::ST + slot * L::ST_SIZE + e;
 #pragma unroll
-            for (int q = 0; q < V::WV; ++q) st[q * 64] = vw[q];
-            st[V::WV * 64] = (uint32_t)(gf & 0xFFFF) | ((uint32_t)gc << 16);
-            st[(V::WV + 1) * 64] = out;
+            for (int q = 0; q < V::WV; ++q) st[q * EPW] = vw[q];
+            st[V::WV * EPW] = (uint32_t)(gf & 0xFFFF) | ((uint32_t)gc << 16);
+            st[(V::WV + 1) * EPW] = out;
             // stage the next block of actions half way through the current one
             if ((i & (ACT_BLOCK - 1)) == ACT_BLOCK / 2) {
                 const int nb = i / ACT_BLOCK + 1;
-                ((uint4 *)(lds + L::ACT))[(nb & 1) * 64 + lane] = act_regs;
+                *(uint4 *)(act_stage + (nb & 1) * (ACT_BLOCK * L::ACT_ROW)) = act_regs;
                 act_regs = load_actions(nb + 1);
             }
         };
@@ -350,21 +359,28 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
         p.tcount[n] = t;
         __syncthreads();
         __syncthreads();
-    } else if (wave == 1) {
+    } else if (wave < 2 * HALVES) {
         // ================================================================= records
+        const int e = (wave - HALVES) * 64 + lane;
+        float *rw = reward + env0 + e;
+        uint8_t *dn = done + env0 + e;
+        const double slope = p.reward_slope;
         __syncthreads();                                             // barrier 0 (set-up)
         __syncthreads();                                             // block 0 published
         auto step = [&](int slot) {
-            const uint32_t *st = lds + L::ST + slot * L::ST_SIZE + lane;
+            const uint32_t *st = lds + L::ST + slot * L::ST_SIZE + e;
             uint32_t vw[V::WV];
 #pragma unroll
-            for (int q = 0; q < V::WV; ++q) vw[q] = st[q * 64];
-            const uint32_t g = st[V::WV * 64];
-            const uint32_t out = st[(V::WV + 1) * 64];
-            uint32_t *rec = lds + L::REC + slot * L::REC_SIZE;
-            rec[L::REC_OUT + lane] = out;
-            produce_record<K>(lds + L::LUT, rec + lane * V::REC, vw, (int)(int16_t)(g & 0xFFFF),
-                              (int)g >> 16);
+            for (int q = 0; q < V::WV; ++q) vw[q] = st[q * EPW];
+            const uint32_t g = st[V::WV * EPW];
+            const uint32_t out = st[(V::WV + 1) * EPW];
+            produce_record<K>(lds + L::LUT, lds + L::REC + slot * L::REC_SIZE + e * V::REC, vw,
+                              (int)(int16_t)(g & 0xFFFF), (int)g >> 16);
+            const uint32_t tr = out & 0x7FFFFFFFu;
+            *rw = tr ? (float)(1.0 - (double)tr * slope) : 0.0f;
+            *dn = (uint8_t)(out >> 31);
+            rw += p.N;
+            dn += p.N;
         };
         auto block = [&](int s0, auto PAR) {
 #pragma unroll
@@ -381,17 +397,13 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
         __syncthreads();
     } else {
         // ================================================================== stores
-        const int c = wave - 2;
+        const int c = wave - 2 * HALVES;
         constexpr int MYR = (V::ROUNDS + V::NC - 1) / V::NC;     // rounds per store wave, at most
         Window win[MYR];
 #pragma unroll
         for (int j = 0; j < MYR; ++j) win[j] = make_window<K>(lane, c + j * V::NC);
         const size_t step_obs = (size_t)p.N * V::SB;
         int8_t *out_block = obs + (size_t)env0 * V::SB;
-        float *rw = reward + n;
-        uint8_t *dn = done + n;
-        const double slope = p.reward_slope;
-        const bool aux = (c == V::NC - 1);                       // this wave also writes reward/done
         __syncthreads();                                             // barrier 0 (set-up)
         __syncthreads();                                             // block 0 published
         __syncthreads();                                             // block 0 recorded
@@ -401,14 +413,6 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
             for (int j = 0; j < MYR; ++j)
                 if (win[j].active) consume_window(rec, win[j], out_block);
             out_block += step_obs;
-            if (aux) {
-                const uint32_t out = rec[L::REC_OUT + lane];
-                const uint32_t tr = out & 0x7FFFFFFFu;
-                *rw = tr ? (float)(1.0 - (double)tr * slope) : 0.0f;
-                *dn = (uint8_t)(out >> 31);
-                rw += p.N;
-                dn += p.N;
-            }
         };
         auto block = [&](int s0, auto PAR) {
 #pragma unroll
@@ -426,17 +430,18 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
 }
 
 // ---------------------------------------------------- observation of the state
-// One wave per 64 envs: produce the records, then expand them (no time loop).
+// One workgroup of EPW threads per EPW envs: produce the records, then expand them
+// (no time loop).
 template <int K, typename Word>
-__global__ __launch_bounds__(64) void k_render_tiled(StudentDev p, int8_t *__restrict__ obs)
+__global__ __launch_bounds__(EPW) void k_render_tiled(StudentDev p, int8_t *__restrict__ obs)
 {
     using V = View<K>;
     using L = Lds<K, Word>;
     extern __shared__ uint32_t lds[];
-    const int lane = threadIdx.x;
-    const int env0 = blockIdx.x * 64;
-    const int n = env0 + lane;
-    fill_lut<K, Word>(lds, lane, 64);
+    const int e = threadIdx.x, lane = e & 63, wave = e >> 6;
+    const int env0 = blockIdx.x * EPW;
+    const int n = env0 + e;
+    fill_lut<K, Word>(lds, e, EPW);
     __syncthreads();
     const Word *glob_env = (const Word *)p.grids + (size_t)n * 4 * p.SP;
     uint32_t pose = p.pose[n];
@@ -446,12 +451,11 @@ __global__ __launch_bounds__(64) void k_render_tiled(StudentDev p, int8_t *__res
     uint32_t vw[V::WV];
     pack_view<K, Word>(rows, xd, vw);
     const uint32_t g = p.goalrot[4 * (size_t)n + d];
-    produce_record<K>(lds + L::LUT, lds + L::REC + lane * V::REC, vw, yd - (int)(g >> 8),
+    produce_record<K>(lds + L::LUT, lds + L::REC + e * V::REC, vw, yd - (int)(g >> 8),
                       (int)(g & 255) - xd);
     __syncthreads();
     int8_t *block = obs + (size_t)env0 * V::SB;
-#pragma unroll
-    for (int j = 0; j < V::ROUNDS; ++j) {
+    for (int j = wave; j < V::ROUNDS; j += HALVES) {
         Window w = make_window<K>(lane, j);
         if (w.active) consume_window(lds + L::REC, w, block);
     }
@@ -463,13 +467,13 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
 {
     using V = View<K>;
     const StudentDev &p = ctx->dev;
-    // stage the grids in LDS when the workgroup's 64 envs fit in 64 KB, else read rows from L2
+    // stage the grids in LDS when the workgroup's envs fit in 64 KB, else read rows from L2
     bool grid_lds = Lds<K, Word>::bytes(p.SP, true) <= 64 * 1024;
     size_t shmem = Lds<K, Word>::bytes(p.SP, grid_lds);
     size_t shmem_render = Lds<K, Word>::bytes(p.SP, false);
     dim3 grid(groups), block(64 * V::WAVES);
     if (n_steps == 0) {
-        hipLaunchKernelGGL((k_render_tiled<K, Word>), grid, dim3(64), shmem_render, st, p, d_obs);
+        hipLaunchKernelGGL((k_render_tiled<K, Word>), grid, dim3(EPW), shmem_render, st, p, d_obs);
     } else if (grid_lds && p.HP == p.WP) {
         hipLaunchKernelGGL((k_student_rollout<K, Word, true, true>), grid, block, shmem, st, p,
                            d_actions, n_steps, d_reward, d_done, d_obs);
@@ -485,7 +489,7 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
 
 }  // namespace
 
-// Launch the tiled kernel on the first `*covered` envs (a multiple of 64) and
+// Launch the tiled kernel on the first `*covered` envs (a multiple of EPW) and
 // report how many it took; the caller runs the per-cell kernel on the rest.
 // n_steps == 0 renders the current state.  Returns 0 if no tiled kernel applies.
 int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
@@ -500,7 +504,7 @@ int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_ste
     // actions must be 16-byte aligned
     if ((((size_t)p.N * 3 * K * K) & 15) != 0 || ((uintptr_t)d_obs & 15) != 0) return 0;
     if (n_steps > 0 && ((p.N & 15) != 0 || ((uintptr_t)d_actions & 15) != 0)) return 0;
-    int full = p.N / 64;
+    int full = p.N / EPW;
     if (full == 0) return 0;
     int rc;
     if (ctx->word64) {
@@ -512,6 +516,6 @@ int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_ste
         else if (K == 5) rc = launch_k<5, uint32_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, full, st);
         else rc = launch_k<7, uint32_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, full, st);
     }
-    if (rc) *covered = full * 64;
+    if (rc) *covered = full * EPW;
     return rc;
 }
