@@ -121,11 +121,11 @@ __device__ __forceinline__ void editor_apply(const EditorDev &p, uint32_t *__res
 
 // One lane per env; the stream stays in global memory (L2) and the observation is
 // written byte by byte.  Correct for every supported shape.
-__global__ void k_editor_percell(EditorDev p, const int32_t *__restrict__ actions, int n_steps,
-                                 int8_t *__restrict__ obs, int32_t *__restrict__ t_out,
-                                 uint8_t *__restrict__ done)
+__global__ void k_editor_percell(EditorDev p, int n_begin, const int32_t *__restrict__ actions,
+                                 int n_steps, int8_t *__restrict__ obs,
+                                 int32_t *__restrict__ t_out, uint8_t *__restrict__ done)
 {
-    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    int n = n_begin + blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= p.N) return;
     uint32_t *s = p.stream + (size_t)n * p.SW;
     int32_t t = p.t[n], ac = p.agent_cell[n], gc = p.goal_cell[n];
@@ -145,8 +145,9 @@ __global__ void k_editor_percell(EditorDev p, const int32_t *__restrict__ action
     p.goal_cell[n] = gc;
 }
 
+// Implemented in maze_editor_tiled.hip: runs the tiled kernel on the first *covered envs.
 int editor_tiled_launch(const editor_ctx *ctx, const int32_t *d_actions, int n_steps,
-                        int8_t *d_obs, int32_t *d_t, uint8_t *d_done, hipStream_t st);
+                        int8_t *d_obs, int32_t *d_t, uint8_t *d_done, int *covered, hipStream_t st);
 
 extern "C" int editor_step(editor_ctx *ctx, const int32_t *d_actions, int n_steps, int8_t *d_obs,
                            int32_t *d_t, uint8_t *d_done, void *stream)
@@ -155,9 +156,11 @@ extern "C" int editor_step(editor_ctx *ctx, const int32_t *d_actions, int n_step
     if (n_steps < 1) return MAZE_EINVAL;
     const EditorDev &p = ctx->dev;
     hipStream_t st = (hipStream_t)stream;
-    if (!editor_tiled_launch(ctx, d_actions, n_steps, d_obs, d_t, d_done, st))
-        hipLaunchKernelGGL(k_editor_percell, dim3((p.N + 63) / 64), dim3(64), 0, st, p, d_actions,
-                           n_steps, d_obs, d_t, d_done);
+    int covered = 0;
+    editor_tiled_launch(ctx, d_actions, n_steps, d_obs, d_t, d_done, &covered, st);
+    if (covered < p.N)
+        hipLaunchKernelGGL(k_editor_percell, dim3((p.N - covered + 63) / 64), dim3(64), 0, st, p,
+                           covered, d_actions, n_steps, d_obs, d_t, d_done);
     MAZE_HIP_CHECK(hipGetLastError());
     return MAZE_OK;
 }

@@ -1,9 +1,148 @@
-// Tiled store-layout kernel of the teacher editor env (placeholder: no shape is
-// covered yet, the per-cell kernel runs).
+// Tiled store-layout kernel of the teacher editor env.
+//
+// The editor's state per env IS the bit stream its observation expands from: bit
+// 3*c + ch of the stream is channel ch (wall, goal, agent) of cell c, i.e. byte
+// 3*c + ch of the env's H*W*3 observation.  A workgroup keeps the streams of
+// EPW = 128 consecutive envs in LDS for the whole call (128 * 3*H*W bytes per step
+// is a whole number of 128-byte lines).  Per step
+//   2 "edit" waves (one lane per env) apply the placement to their env's stream
+//     with LDS bit atomics and write the step's t and done,
+//   NS "store" waves then expand the 128 concatenated streams to bytes: lane l of
+//     round j takes stream bits [16*(64*j+l), +16) -- they may straddle two envs --
+//     and writes 16 bytes, so one store instruction of a wave writes 1 KB of
+//     contiguous output.
+// Two barriers per step separate editing from reading; the edit phase is a few
+// dozen instructions, the store phase moves 3*H*W*128 bytes.
 #include "maze_internal.h"
 
-int editor_tiled_launch(const editor_ctx *, const int32_t *, int, int8_t *, int32_t *, uint8_t *,
-                        hipStream_t)
+namespace {
+
+constexpr int EPW = 128;        // envs per workgroup
+constexpr int NE = EPW / 64;    // edit waves
+constexpr int NS = 12;          // store waves
+constexpr int NWAVES = NE + NS;
+
+__device__ __forceinline__ uint32_t expand_nibble(uint32_t nib)
 {
-    return 0;
+    return (nib * 0x00204081u) & 0x01010101u;
+}
+
+__device__ __forceinline__ void lds_set_bit(uint32_t *rec, int bit)
+{
+    atomicOr(&rec[bit >> 5], 1u << (bit & 31));
+}
+
+__device__ __forceinline__ void lds_clear_bit(uint32_t *rec, int bit)
+{
+    atomicAnd(&rec[bit >> 5], ~(1u << (bit & 31)));
+}
+
+__global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
+    EditorDev p, const int32_t *__restrict__ actions, int n_steps, int8_t *__restrict__ obs,
+    int32_t *__restrict__ t_out, uint8_t *__restrict__ done)
+{
+    extern __shared__ uint32_t lds[];            // [EPW][REC], REC = SW + 1 (last dword stays 0)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int env0 = blockIdx.x * EPW;
+    const int SW = p.SW, REC = SW + 1;
+    const int SB = 3 * p.cells;                  // stream bits = obs bytes per env
+
+    // stage the streams (and zero the pad dwords)
+    for (int i = tid; i < EPW * REC; i += 64 * NWAVES) {
+        int e = i / REC, o = i - e * REC;
+        lds[i] = (o < SW) ? p.stream[(size_t)(env0 + e) * SW + o] : 0u;
+    }
+    __syncthreads();
+
+    if (wave < NE) {
+        // ==================================================================== edit
+        const int e = wave * 64 + lane, n = env0 + e;
+        uint32_t *rec = lds + e * REC;
+        int32_t t = p.t[n], ac = p.agent_cell[n], gc = p.goal_cell[n];
+        const int32_t *act = actions + n;
+        int32_t a_next = act[0];
+        for (int s = 0; s < n_steps; ++s) {
+            const int32_t action = a_next;
+            if (s + 1 < n_steps) a_next = act[(size_t)(s + 1) * p.N];
+            const int a = min(max(action, 0), p.cells - 1);
+            if (t < p.n_walls) {
+                lds_set_bit(rec, 3 * a);
+            } else if (t == p.n_walls) {
+                ac = a;
+                lds_clear_bit(rec, 3 * a);
+                lds_set_bit(rec, 3 * a + 2);
+            } else if (t == p.n_walls + 1) {
+                const int j = (a == ac) ? ((a + 1 == p.cells) ? 0 : a + 1) : a;
+                gc = j;
+                lds_clear_bit(rec, 3 * j);
+                lds_set_bit(rec, 3 * j + 1);
+            }
+            if (t < p.n_walls + 2) t += 1;
+            if (t_out) t_out[(size_t)s * p.N + n] = t;
+            if (done) done[(size_t)s * p.N + n] = (t == p.n_walls + 2) ? 1 : 0;
+            __syncthreads();                     // edits of step s visible
+            __syncthreads();                     // stores of step s have read the streams
+        }
+        // write the state back
+        p.t[n] = t;
+        p.agent_cell[n] = ac;
+        p.goal_cell[n] = gc;
+        for (int o = 0; o < SW; ++o) p.stream[(size_t)n * SW + o] = rec[o];
+    } else {
+        // =================================================================== store
+        const int c = wave - NE;
+        const int nwin = EPW * SB / 16;          // 16-bit windows per step (EPW*SB is a multiple of 16)
+        // window m = c*64 + lane, then every NS*64 windows; its position is kept as
+        // (env e0, bit s inside the env) and advanced without divisions
+        const int adv_bits = 16 * NS * 64;
+        const int adv_q = adv_bits / SB, adv_r = adv_bits - adv_q * SB;
+        const int m0 = c * 64 + lane;
+        const int e_first = (16 * m0) / SB, s_first = 16 * m0 - e_first * SB;
+        const size_t step_obs = (size_t)p.N * SB;
+        int8_t *out_block = obs + (size_t)env0 * SB;
+        for (int s = 0; s < n_steps; ++s) {
+            __syncthreads();                     // edits of step s visible
+            int e0 = e_first, bs = s_first;
+            for (int m = m0; m < nwin; m += NS * 64) {
+                const uint32_t *r0 = lds + e0 * REC;
+                const int rem = SB - bs;
+                const bool spill = rem < 16;     // window runs into the next env
+                uint32_t lo = r0[bs >> 5], hi = r0[(bs >> 5) + 1];
+                uint32_t nx = spill ? r0[REC] : 0u;
+                uint32_t bits = __builtin_amdgcn_alignbit(hi, lo, bs & 31) | (nx << (spill ? rem : 0));
+                uint4 v;
+                v.x = expand_nibble(bits & 15);          v.y = expand_nibble((bits >> 4) & 15);
+                v.z = expand_nibble((bits >> 8) & 15);   v.w = expand_nibble((bits >> 12) & 15);
+                *(uint4 *)(out_block + 16 * (size_t)m) = v;
+                bs += adv_r;
+                e0 += adv_q;
+                if (bs >= SB) { bs -= SB; e0 += 1; }
+            }
+            out_block += step_obs;
+            __syncthreads();                     // reads done before the next edit
+        }
+    }
+}
+
+}  // namespace
+
+// Returns 1 if the tiled kernel was launched on the first *covered envs (a multiple of
+// EPW; the caller runs the per-cell kernel on the rest), 0 if the shape is not covered.
+int editor_tiled_launch(const editor_ctx *ctx, const int32_t *d_actions, int n_steps,
+                        int8_t *d_obs, int32_t *d_t, uint8_t *d_done, int *covered, hipStream_t st)
+{
+    const EditorDev &p = ctx->dev;
+    *covered = 0;
+    if (!d_obs) return 0;
+    size_t shmem = 4 * (size_t)EPW * (p.SW + 1);
+    if (shmem > 60 * 1024) return 0;
+    // 16-byte stores: each step's obs block and the buffer must be 16-byte aligned
+    if ((((size_t)p.N * 3 * p.cells) & 15) != 0 || ((uintptr_t)d_obs & 15) != 0) return 0;
+    int groups = p.N / EPW;
+    if (groups == 0) return 0;
+    hipLaunchKernelGGL(k_editor_tiled, dim3(groups), dim3(64 * NWAVES), shmem, st, p, d_actions,
+                       n_steps, d_obs, d_t, d_done);
+    *covered = groups * EPW;
+    return 1;
 }
