@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row measurements")
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 per-cell kernels")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (envs are independent; sharding the batch "
@@ -157,6 +159,15 @@ def main():
                      "kernel_ms_avg": k_avg_s * 1e3, "kernel_ms_min": float(np.min(kms)),
                      "algorithmic_bytes_per_launch": alg_bytes},
     }
+
+    if args.calib_copy:
+        # a plain copy of known size: 256 MiB read + 256 MiB written per launch
+        src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------------------------------------------------------- other rows
     if not args.no_rows:

@@ -94,55 +94,87 @@ extern "C" int maze_set_kernel_variant(maze_ctx *ctx, int variant)
 }
 
 // ------------------------------------------------------------- level packing
-// One thread per (env, heading, row of the rotated grid): builds that row's word.
-template <typename Word>
-__global__ void k_pack_grids(StudentDev p, const int8_t *__restrict__ walls)
+// One wavefront per env.  The H*W wall bytes are turned into two bitmaps with wave
+// ballots -- row-major (bit y*W + x) and column-major (bit x*H + y) -- 64 cells per
+// ballot, kept in the wave's slice of LDS.  Every row of the four heading frames is
+// then one field of one of the bitmaps (reversed for the two frames that look
+// against the axis), shifted into the ring of border walls.  Lane 0 also packs the
+// start pose and the goal's position in the four frames.
+constexpr int PACK_WAVES = 4;                 // waves (= envs) per workgroup
+constexpr int PACK_BM_DWORDS = 4096 / 32 + 4;  // bitmap of up to 64x64 cells + zero tail
+
+__device__ __forceinline__ uint64_t bitmap_field(const uint32_t *bm, int offset, int len)
 {
-    long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    long long total = (long long)p.N * 4 * p.SP;
-    if (gid >= total) return;
-    int row = (int)(gid % p.SP);
-    int d = (int)((gid / p.SP) & 3);
-    int n = (int)(gid / ((long long)p.SP * 4));
-    int rows = (d & 1) ? p.HP : p.WP;
-    int bits = (d & 1) ? p.WP : p.HP;
-    Word w = ~(Word)0;                       // rows beyond the frame are solid
-    if (row < rows) {
-        w = 0;
-        const int8_t *g = walls + (size_t)n * p.H * p.W;
-        for (int b = 0; b < bits; ++b) {
-            int X, Y;
-            frame_to_padded(p, d, b, row, X, Y);
-            int x = X - p.P, y = Y - p.P;
-            bool wall = (x < 0 || x >= p.W || y < 0 || y >= p.H) ? true : (g[y * p.W + x] != 0);
-            if (wall) w |= (Word)1 << b;
-        }
-        for (int b = bits; b < (int)(sizeof(Word) * 8); ++b) w |= (Word)1 << b;
-    }
-    ((Word *)p.grids)[gid] = w;
+    const int w = offset >> 5, sh = offset & 31;
+    const uint64_t lo = ((uint64_t)bm[w + 1] << 32) | bm[w];
+    const uint64_t hi = bm[w + 2];
+    uint64_t v = lo >> sh;
+    if (sh) v |= hi << (64 - sh);
+    return len >= 64 ? v : (v & (((uint64_t)1 << len) - 1));
 }
 
-// One thread per env: start pose, goal in the four frames, state = start, t = 0.
-__global__ void k_pack_poses(StudentDev p, const int32_t *__restrict__ agent_xy,
-                             const int8_t *__restrict__ agent_dir,
-                             const int32_t *__restrict__ goal_xy)
+template <typename Word>
+__global__ __launch_bounds__(64 * PACK_WAVES) void k_pack_levels(
+    StudentDev p, const int8_t *__restrict__ walls, const int32_t *__restrict__ agent_xy,
+    const int8_t *__restrict__ agent_dir, const int32_t *__restrict__ goal_xy)
 {
-    int n = blockIdx.x * blockDim.x + threadIdx.x;
-    if (n >= p.N) return;
-    int ax = min(max(agent_xy[2 * n], 0), p.W - 1) + p.P;
-    int ay = min(max(agent_xy[2 * n + 1], 0), p.H - 1) + p.P;
-    int gx = min(max(goal_xy[2 * n], 0), p.W - 1) + p.P;
-    int gy = min(max(goal_xy[2 * n + 1], 0), p.H - 1) + p.P;
-    int d = agent_dir[n] & 3;
-    int xd, yd;
-    padded_to_frame(p, d, ax, ay, xd, yd);
-    uint32_t s = (uint32_t)xd | ((uint32_t)yd << 8) | ((uint32_t)d << 16);
-    p.start[n] = s;
-    p.pose[n] = s;
-    p.tcount[n] = 0;
-    for (int f = 0; f < 4; ++f) {
-        padded_to_frame(p, f, gx, gy, xd, yd);
-        p.goalrot[4 * n + f] = (uint32_t)xd | ((uint32_t)yd << 8);
+    __shared__ uint32_t lds[PACK_WAVES][2][PACK_BM_DWORDS];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = blockIdx.x * PACK_WAVES + wave;
+    if (n >= p.N) return;                        // whole wave leaves together
+    uint32_t *bm_rm = lds[wave][0], *bm_cm = lds[wave][1];
+    const int cells = p.H * p.W;
+    const int8_t *g = walls + (size_t)n * cells;
+    const int chunks = (cells + 63) >> 6;
+    for (int c = 0; c <= chunks; ++c) {          // one extra chunk of zeros as the tail
+        const int idx = c * 64 + lane;
+        const bool valid = idx < cells;
+        const int x = valid ? idx / p.H : 0, y = valid ? idx - x * p.H : 0;
+        const bool rm = valid && g[idx] != 0;
+        const bool cm = valid && g[y * p.W + x] != 0;
+        const uint64_t m_rm = __ballot(rm), m_cm = __ballot(cm);
+        if (lane == 0) {
+            bm_rm[2 * c] = (uint32_t)m_rm; bm_rm[2 * c + 1] = (uint32_t)(m_rm >> 32);
+            bm_cm[2 * c] = (uint32_t)m_cm; bm_cm[2 * c + 1] = (uint32_t)(m_cm >> 32);
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    Word *out = (Word *)p.grids + (size_t)n * 4 * p.SP;
+    for (int task = lane; task < 4 * p.SP; task += 64) {
+        const int d = task / p.SP, row = task - d * p.SP;
+        const int rows = (d & 1) ? p.HP : p.WP;  // shape of frame d
+        const int len = (d & 1) ? p.W : p.H;     // interior cells per row of frame d
+        uint64_t word = ~(uint64_t)0;            // border rows and rows beyond the frame: solid
+        const int r = row - p.P;                 // interior line of the frame
+        if (row < rows && r >= 0 && r < rows - 2 * p.P) {
+            uint64_t f;
+            if (d == 3) f = bitmap_field(bm_rm, r * p.W, p.W);
+            else if (d == 1) f = __brevll(bitmap_field(bm_rm, (p.H - 1 - r) * p.W, p.W)) >> (64 - p.W);
+            else if (d == 0) f = bitmap_field(bm_cm, (p.W - 1 - r) * p.H, p.H);
+            else f = __brevll(bitmap_field(bm_cm, r * p.H, p.H)) >> (64 - p.H);
+            const uint64_t field_mask = (((uint64_t)1 << len) - 1) << p.P;
+            word = (f << p.P) | ~field_mask;
+        }
+        out[task] = (Word)word;
+    }
+    if (lane == 0) {
+        int ax = min(max(agent_xy[2 * n], 0), p.W - 1) + p.P;
+        int ay = min(max(agent_xy[2 * n + 1], 0), p.H - 1) + p.P;
+        int gx = min(max(goal_xy[2 * n], 0), p.W - 1) + p.P;
+        int gy = min(max(goal_xy[2 * n + 1], 0), p.H - 1) + p.P;
+        int d = agent_dir[n] & 3;
+        int xd, yd;
+        padded_to_frame(p, d, ax, ay, xd, yd);
+        uint32_t s = (uint32_t)xd | ((uint32_t)yd << 8) | ((uint32_t)d << 16);
+        p.start[n] = s;
+        p.pose[n] = s;
+        p.tcount[n] = 0;
+        for (int f = 0; f < 4; ++f) {
+            padded_to_frame(p, f, gx, gy, xd, yd);
+            p.goalrot[4 * n + f] = (uint32_t)xd | ((uint32_t)yd << 8);
+        }
     }
 }
 
@@ -153,14 +185,13 @@ extern "C" int maze_reset_to_levels(maze_ctx *ctx, const int8_t *d_walls,
     if (!ctx || !d_walls || !d_agent_xy || !d_agent_dir || !d_goal_xy) return MAZE_ENULL;
     hipStream_t st = (hipStream_t)stream;
     const StudentDev &p = ctx->dev;
-    long long total = (long long)p.N * 4 * p.SP;
-    unsigned blocks = (unsigned)((total + 255) / 256);
+    dim3 grid((p.N + PACK_WAVES - 1) / PACK_WAVES), block(64 * PACK_WAVES);
     if (ctx->word64)
-        hipLaunchKernelGGL(k_pack_grids<uint64_t>, dim3(blocks), dim3(256), 0, st, p, d_walls);
+        hipLaunchKernelGGL(k_pack_levels<uint64_t>, grid, block, 0, st, p, d_walls, d_agent_xy,
+                           d_agent_dir, d_goal_xy);
     else
-        hipLaunchKernelGGL(k_pack_grids<uint32_t>, dim3(blocks), dim3(256), 0, st, p, d_walls);
-    hipLaunchKernelGGL(k_pack_poses, dim3((p.N + 255) / 256), dim3(256), 0, st, p, d_agent_xy,
-                       d_agent_dir, d_goal_xy);
+        hipLaunchKernelGGL(k_pack_levels<uint32_t>, grid, block, 0, st, p, d_walls, d_agent_xy,
+                           d_agent_dir, d_goal_xy);
     MAZE_HIP_CHECK(hipGetLastError());
     return MAZE_OK;
 }
