@@ -28,6 +28,14 @@
 
 #include <type_traits>
 
+// Compile-time knobs (overridable for measurements).
+#ifndef MAZE_SPB
+#define MAZE_SPB 2
+#endif
+#ifndef MAZE_STORE_WAVES
+#define MAZE_STORE_WAVES 10
+#endif
+
 namespace {
 
 constexpr int EPW = 128;        // envs per workgroup
@@ -45,12 +53,12 @@ struct View {
     static constexpr int ROWBITS = 3 * K;
     static constexpr int RPD = 32 / K;             // view rows packed per dword
     static constexpr int WV = (K + RPD - 1) / RPD; // dwords of packed view bits
-    static constexpr int NC = ROUNDS < 10 ? ROUNDS : 10; // store waves per workgroup
+    static constexpr int NC = ROUNDS < MAZE_STORE_WAVES ? ROUNDS : MAZE_STORE_WAVES;   // store waves
     static constexpr int WAVES = 2 * HALVES + NC;
 };
 
 constexpr int ACT_BLOCK = 16;   // steps of actions staged per global load of the dynamics wave
-constexpr int SPB = 2;          // steps per barrier: every stage handles SPB steps between barriers
+constexpr int SPB = MAZE_SPB;   // steps per barrier: every stage handles SPB steps between barriers
 
 // 4 stream bits -> 4 bytes (bit j -> byte j).  The four shifted copies do not
 // overlap, so the multiply carries nothing.
