@@ -1,11 +1,12 @@
 // Tiled store-layout kernels of the student env.
 //
-// A workgroup owns EPW = 128 consecutive envs for the whole rollout (128 * 3k^2
-// bytes per step is a whole number of 128-byte lines, so no line of the output is
-// shared between workgroups).  Per step one lane per env advances the env (state in
+// A workgroup owns EPW consecutive envs for the whole rollout: 128 when the batch is
+// large enough to fill the GPU that way (128 * 3k^2 bytes per step is a whole number
+// of 128-byte lines, so no line of the output is shared between workgroups), 64 or
+// 32 for smaller batches or grids whose LDS copy would not fit.  Per step one lane per env advances the env (state in
 // registers, wall rows from LDS) and its observation is built as a BIT STREAM --
 // bit i of the stream is byte i of the env's k*k*3 observation, which is 0 or 1 --
-// and left in LDS.  The 128 streams, concatenated, are exactly the 128*3k^2
+// and left in LDS.  The EPW streams, concatenated, are exactly the EPW*3k^2
 // contiguous output bytes of this time step, so other lanes then take 16 consecutive stream bits each (they may
 // straddle two envs), expand each bit to a byte and write 16 contiguous bytes;
 // consecutive lanes take consecutive pieces, so one store instruction of a wave
@@ -13,12 +14,12 @@
 //
 // The per-step work is a three-stage pipeline over the waves of the workgroup,
 // advanced by one barrier per block of SPB steps:
-//   waves 0,1 ("dynamics") block b  : action, move, goal/done/reset, read the K
+//   first  ("dynamics") block b  : action, move, goal/done/reset, read the K
 //                                     wall rows of the new view and publish the
 //                                     K x K view bits, the goal offset, reward, done
-//   waves 2,3 ("records")  block b-1: view bits -> stream record (row lookup table),
+//   next   ("records")  block b-1: view bits -> stream record (row lookup table),
 //                                     goal cell patched in; store reward and done
-//   waves 4.. ("stores")   block b-2: expand records to bytes, store obs
+//   rest   ("stores")   block b-2: expand records to bytes, store obs
 // (one dynamics and one records wave per 64 envs)
 // Only the dynamics wave carries a dependency from step to step, so the time per
 // step is that wave's short chain; the store waves never load from global memory
@@ -38,27 +39,31 @@
 
 namespace {
 
-constexpr int EPW = 128;        // envs per workgroup
-constexpr int HALVES = EPW / 64;
+constexpr int SPB = MAZE_SPB;   // steps per barrier: every stage handles SPB steps between barriers
 
-template <int K>
+// Compile-time shape of a workgroup: view size K, EPW envs.
+template <int K, int EPW>
 struct View {
     static constexpr int CELLS = K * K;
     static constexpr int SB = 3 * CELLS;           // stream bits (= obs bytes) per env
     static constexpr int ND = (SB + 31) / 32;      // data dwords per env record
     static constexpr int REC = ND + 1;             // record = data dwords + one zero dword
-    static constexpr int NWIN = EPW * SB / 16;     // 16-bit windows per workgroup step
-    static constexpr int ROUNDS = (NWIN + 63) / 64;
     static constexpr int LUTN = 1 << K;            // row pattern -> 3K stream bits
     static constexpr int ROWBITS = 3 * K;
     static constexpr int RPD = 32 / K;             // view rows packed per dword
     static constexpr int WV = (K + RPD - 1) / RPD; // dwords of packed view bits
+    static constexpr int LA = EPW < 64 ? EPW : 64; // envs (= active lanes) of a dynamics / records wave
+    static constexpr int NDYN = EPW / LA;          // dynamics waves (and records waves)
+    static constexpr int NWIN = EPW * SB / 16;     // 16-bit windows per workgroup step
+    static constexpr int ROUNDS = (NWIN + 63) / 64;
     static constexpr int NC = ROUNDS < MAZE_STORE_WAVES ? ROUNDS : MAZE_STORE_WAVES;   // store waves
-    static constexpr int WAVES = 2 * HALVES + NC;
+    static constexpr int WAVES = 2 * NDYN + NC;
+    // actions: one 16-byte load per lane covers 16 envs of one step, so a dynamics wave
+    // stages ACT_BLOCK steps of its LA envs per load
+    static constexpr int ACT_LPR = LA / 16;
+    static constexpr int ACT_BLOCK = 64 / ACT_LPR;
+    static_assert((EPW * SB) % 16 == 0, "a step's chunk must be a whole number of 16-byte pieces");
 };
-
-constexpr int ACT_BLOCK = 16;   // steps of actions staged per global load of the dynamics wave
-constexpr int SPB = MAZE_SPB;   // steps per barrier: every stage handles SPB steps between barriers
 
 // 4 stream bits -> 4 bytes (bit j -> byte j).  The four shifted copies do not
 // overlap, so the multiply carries nothing.
@@ -73,13 +78,13 @@ template <> struct WordOps<uint64_t> { static constexpr int DW = 2; };
 
 // Per-workgroup LDS carve-up (dword offsets).  ST and REC hold SPB steps each and
 // are double buffered by block parity (a block = the SPB steps between two barriers).
-template <int K, typename Word>
+template <int K, typename Word, int EPW>
 struct Lds {
-    using V = View<K>;
+    using V = View<K, EPW>;
     static constexpr int LUT = 0;                                  // [LUTN]
     static constexpr int ACT = LUT + V::LUTN;                      // [2][ACT_BLOCK][EPW] action bytes
     static constexpr int ACT_ROW = EPW;                            // bytes per step
-    static constexpr int ST = ACT + 2 * ACT_BLOCK * EPW / 4;       // [2][SPB][WV+2][EPW] view bits, goal, out
+    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][WV+2][EPW] view bits, goal, out
     static constexpr int ST_SIZE = (V::WV + 2) * EPW;
     static constexpr int REC = ST + 2 * SPB * ST_SIZE;             // [2][SPB][EPW*REC] stream records
     static constexpr int REC_SIZE = EPW * V::REC;
@@ -120,9 +125,9 @@ __device__ __forceinline__ void load_view_rows(const uint32_t *lds_env, const Wo
 
 // K x K view bits (row r, column c -> bit K*(r % RPD) + c of dword r / RPD).
 template <int K, typename Word>
-__device__ __forceinline__ void pack_view(const Word (&rows)[K], int xd, uint32_t (&vw)[View<K>::WV])
+__device__ __forceinline__ void pack_view(const Word (&rows)[K], int xd, uint32_t (&vw)[View<K, 64>::WV])
 {
-    using V = View<K>;
+    using V = View<K, 64>;
     const int sh = xd - K / 2;
 #pragma unroll
     for (int q = 0; q < V::WV; ++q) vw[q] = 0;
@@ -138,9 +143,9 @@ __device__ __forceinline__ void pack_view(const Word (&rows)[K], int xd, uint32_
 // the right) of the agent.  An empty cell is 100b, a wall 001b, the goal 010b.
 template <int K>
 __device__ __forceinline__ void produce_record(const uint32_t *lut, uint32_t *rec,
-                                               const uint32_t (&vw)[View<K>::WV], int gf, int gc)
+                                               const uint32_t (&vw)[View<K, 64>::WV], int gf, int gc)
 {
-    using V = View<K>;
+    using V = View<K, 64>;
     uint32_t D[V::REC];
 #pragma unroll
     for (int q = 0; q < V::REC; ++q) D[q] = 0;
@@ -179,10 +184,10 @@ struct Window {
     uint32_t out;   // byte offset of the window's 16 output bytes in the workgroup's block
 };
 
-template <int K>
+template <int K, int EPW>
 __device__ __forceinline__ Window make_window(int lane, int round)
 {
-    using V = View<K>;
+    using V = View<K, EPW>;
     Window w;
     int m = round * 64 + lane;
     w.active = (round < V::ROUNDS) && (m < V::NWIN);
@@ -213,25 +218,25 @@ __device__ __forceinline__ void consume_window(const uint32_t *recs, const Windo
     *(uint4 *)(block + w.out) = a;
 }
 
-template <int K, typename Word>
-__device__ __forceinline__ void fill_lut(uint32_t *lds, int tid, int nthreads)
+template <int K>
+__device__ __forceinline__ void fill_lut(uint32_t *lut, int tid, int nthreads)
 {
-    using V = View<K>;
+    using V = View<K, 64>;
     for (int i = tid; i < V::LUTN; i += nthreads) {
         uint32_t v = 0;
 #pragma unroll
         for (int c = 0; c < K; ++c) v |= (((i >> c) & 1) ? 1u : 4u) << (3 * c);
-        lds[Lds<K, Word>::LUT + i] = v;
+        lut[i] = v;
     }
 }
 
 // Copy the workgroup's envs' grids into LDS (all threads take part).
-template <int K, typename Word>
+template <int K, typename Word, int EPW>
 __device__ __forceinline__ void stage_grids(const StudentDev &p, uint32_t *lds, int tid, int nthreads,
                                             int env0)
 {
-    const int gs = Lds<K, Word>::grid_stride(p.SP);
-    uint32_t *base = lds + Lds<K, Word>::GRID0;
+    const int gs = Lds<K, Word, EPW>::grid_stride(p.SP);
+    uint32_t *base = lds + Lds<K, Word, EPW>::GRID0;
     const int per_env = 4 * p.SP * WordOps<Word>::DW;
     const uint32_t *src = (const uint32_t *)p.grids + (size_t)env0 * per_env;
     int e = 0, o = tid;
@@ -251,25 +256,27 @@ __device__ __forceinline__ void stage_grids(const StudentDev &p, uint32_t *lds, 
 //                                stores   drain  block b-2                  (read REC[(b-2)&1])
 // so no buffer is written while it is read.  The block loops are unrolled by two so
 // every LDS address is a lane constant plus an immediate.
-template <int K, typename Word, bool GRID_LDS, bool SQUARE>
-__global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
+template <int K, typename Word, int EPW, bool GRID_LDS, bool SQUARE>
+__global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     StudentDev p, const int8_t *__restrict__ actions, int n_steps, float *__restrict__ reward,
     uint8_t *__restrict__ done, int8_t *__restrict__ obs)
 {
-    using V = View<K>;
-    using L = Lds<K, Word>;
+    using V = View<K, EPW>;
+    using L = Lds<K, Word, EPW>;
     constexpr int NT = 64 * V::WAVES;
+    constexpr int ACT_BLOCK = V::ACT_BLOCK;
     extern __shared__ uint32_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int env0 = blockIdx.x * EPW;
 
-    fill_lut<K, Word>(lds, tid, NT);
-    if (GRID_LDS) stage_grids<K, Word>(p, lds, tid, NT, env0);
+    fill_lut<K>(lds + L::LUT, tid, NT);
+    if (GRID_LDS) stage_grids<K, Word, EPW>(p, lds, tid, NT, env0);
 
-    if (wave < HALVES) {
+    if (wave < V::NDYN) {
         // ================================================================ dynamics
-        const int e = wave * 64 + lane;            // env within the workgroup
+        const bool active = lane < V::LA;          // a wave serves LA envs
+        const int e = wave * 64 + (active ? lane : 0);   // env within the workgroup
         const int n = env0 + e;
         const int last = n_steps - 1;
         uint32_t pose = p.pose[n];
@@ -286,13 +293,14 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
         const int HPm1 = p.HP - 1, WPm1 = p.WP - 1;
         const uint32_t *lds_env = lds + L::GRID0 + e * (GRID_LDS ? L::grid_stride(p.SP) : 0);
         const Word *glob_env = (const Word *)p.grids + (size_t)n * 4 * p.SP;
-        // actions: lane l of this wave stages the bytes of step (block*16 + l/4) for its
-        // 64 envs, 16 envs per lane
-        const int stage_col = wave * 64 + 16 * (lane & 3);
+        // actions: lane l of this wave stages the bytes of step block*ACT_BLOCK + l/ACT_LPR
+        // for 16 of the wave's envs (all 64 lanes stage, whatever LA is)
+        const int stage_row = lane / V::ACT_LPR;
+        const int stage_col = wave * 64 + 16 * (lane % V::ACT_LPR);
         const int8_t *act_lane = actions + env0 + stage_col;
-        uint8_t *act_stage = (uint8_t *)(lds + L::ACT) + (lane >> 2) * L::ACT_ROW + stage_col;
+        uint8_t *act_stage = (uint8_t *)(lds + L::ACT) + stage_row * L::ACT_ROW + stage_col;
         auto load_actions = [&](int block) {
-            int s = min(block * ACT_BLOCK + (lane >> 2), last);
+            int s = min(block * ACT_BLOCK + stage_row, last);
             return *(const uint4 *)(act_lane + (size_t)s * p.N);
         };
         *(uint4 *)act_stage = load_actions(0);
@@ -305,7 +313,7 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
         uint32_t act_off = 0;              // byte offset of the current step's row in the ring
         uint32_t a_next = act_lds[0];
 
-        auto step = [&](int i, int slot) {
+        auto env_step = [&](int slot) {
             const uint32_t a = a_next;
             act_off = (act_off + L::ACT_ROW) & (2 * ACT_BLOCK * L::ACT_ROW - 1);
             a_next = act_lds[act_off];     // next step's action (staged >= 8 steps ago)
@@ -344,6 +352,9 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
             for (int q = 0; q < V::WV; ++q) st[q * EPW] = vw[q];
             st[V::WV * EPW] = (uint32_t)(gf & 0xFFFF) | ((uint32_t)gc << 16);
             st[(V::WV + 1) * EPW] = out;
+        };
+        auto step = [&](int i, int slot) {
+            if (active) env_step(slot);
             // stage the next block of actions half way through the current one
             if ((i & (ACT_BLOCK - 1)) == ACT_BLOCK / 2) {
                 const int nb = i / ACT_BLOCK + 1;
@@ -363,13 +374,16 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
             block(i + SPB, std::integral_constant<int, 1>());
         }
         if (i < n_steps) block(i, std::integral_constant<int, 0>());
-        p.pose[n] = (uint32_t)xd | ((uint32_t)yd << 8) | ((uint32_t)d << 16);
-        p.tcount[n] = t;
+        if (active) {
+            p.pose[n] = (uint32_t)xd | ((uint32_t)yd << 8) | ((uint32_t)d << 16);
+            p.tcount[n] = t;
+        }
         __syncthreads();
         __syncthreads();
-    } else if (wave < 2 * HALVES) {
+    } else if (wave < 2 * V::NDYN) {
         // ================================================================= records
-        const int e = (wave - HALVES) * 64 + lane;
+        const bool active = lane < V::LA;
+        const int e = (wave - V::NDYN) * 64 + (active ? lane : 0);
         float *rw = reward + env0 + e;
         uint8_t *dn = done + env0 + e;
         const double slope = p.reward_slope;
@@ -393,7 +407,7 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
         auto block = [&](int s0, auto PAR) {
 #pragma unroll
             for (int u = 0; u < SPB; ++u)
-                if (s0 + u < n_steps) step(decltype(PAR)::value * SPB + u);
+                if (s0 + u < n_steps && active) step(decltype(PAR)::value * SPB + u);
             __syncthreads();
         };
         int s = 0;
@@ -405,11 +419,11 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
         __syncthreads();
     } else {
         // ================================================================== stores
-        const int c = wave - 2 * HALVES;
+        const int c = wave - 2 * V::NDYN;
         constexpr int MYR = (V::ROUNDS + V::NC - 1) / V::NC;     // rounds per store wave, at most
         Window win[MYR];
 #pragma unroll
-        for (int j = 0; j < MYR; ++j) win[j] = make_window<K>(lane, c + j * V::NC);
+        for (int j = 0; j < MYR; ++j) win[j] = make_window<K, EPW>(lane, c + j * V::NC);
         const size_t step_obs = (size_t)p.N * V::SB;
         int8_t *out_block = obs + (size_t)env0 * V::SB;
         __syncthreads();                                             // barrier 0 (set-up)
@@ -438,18 +452,20 @@ __global__ __launch_bounds__(64 * View<K>::WAVES) void k_student_rollout(
 }
 
 // ---------------------------------------------------- observation of the state
-// One workgroup of EPW threads per EPW envs: produce the records, then expand them
+// One workgroup of REPW threads per REPW envs: produce the records, then expand them
 // (no time loop).
+constexpr int REPW = 64;
+
 template <int K, typename Word>
-__global__ __launch_bounds__(EPW) void k_render_tiled(StudentDev p, int8_t *__restrict__ obs)
+__global__ __launch_bounds__(REPW) void k_render_tiled(StudentDev p, int8_t *__restrict__ obs)
 {
-    using V = View<K>;
-    using L = Lds<K, Word>;
+    using V = View<K, REPW>;
+    using L = Lds<K, Word, REPW>;
     extern __shared__ uint32_t lds[];
-    const int e = threadIdx.x, lane = e & 63, wave = e >> 6;
-    const int env0 = blockIdx.x * EPW;
-    const int n = env0 + e;
-    fill_lut<K, Word>(lds, e, EPW);
+    const int lane = threadIdx.x;
+    const int env0 = blockIdx.x * REPW;
+    const int n = env0 + lane;
+    fill_lut<K>(lds + L::LUT, lane, REPW);
     __syncthreads();
     const Word *glob_env = (const Word *)p.grids + (size_t)n * 4 * p.SP;
     uint32_t pose = p.pose[n];
@@ -459,46 +475,90 @@ __global__ __launch_bounds__(EPW) void k_render_tiled(StudentDev p, int8_t *__re
     uint32_t vw[V::WV];
     pack_view<K, Word>(rows, xd, vw);
     const uint32_t g = p.goalrot[4 * (size_t)n + d];
-    produce_record<K>(lds + L::LUT, lds + L::REC + e * V::REC, vw, yd - (int)(g >> 8),
+    produce_record<K>(lds + L::LUT, lds + L::REC + lane * V::REC, vw, yd - (int)(g >> 8),
                       (int)(g & 255) - xd);
     __syncthreads();
     int8_t *block = obs + (size_t)env0 * V::SB;
-    for (int j = wave; j < V::ROUNDS; j += HALVES) {
-        Window w = make_window<K>(lane, j);
+    for (int j = 0; j < V::ROUNDS; ++j) {
+        Window w = make_window<K, REPW>(lane, j);
         if (w.active) consume_window(lds + L::REC, w, block);
     }
 }
 
+constexpr size_t LDS_PER_CU = 160 * 1024;     // gfx950
+
+// Raise a kernel's dynamic LDS limit above the 64 KB default (remembered in *granted).
+template <typename Kernel>
+bool allow_large_lds(Kernel kernel, size_t bytes, size_t *granted)
+{
+    if (bytes <= 64 * 1024 || bytes <= *granted) return true;
+    if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)bytes) != hipSuccess)
+        return false;
+    *granted = bytes;
+    return true;
+}
+
+template <int K, typename Word, int EPW>
+int launch_rollout(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
+                   uint8_t *d_done, int8_t *d_obs, hipStream_t st)
+{
+    using V = View<K, EPW>;
+    using L = Lds<K, Word, EPW>;
+    const StudentDev &p = ctx->dev;
+    const bool grid_lds = L::bytes(p.SP, true) <= LDS_PER_CU - 1024;
+    const size_t shmem = L::bytes(p.SP, grid_lds);
+    const dim3 grid(p.N / EPW), block(64 * V::WAVES);
+    const bool square = p.HP == p.WP;
+    static size_t granted[2] = {0, 0};
+    if (grid_lds && square) {
+        auto kern = k_student_rollout<K, Word, EPW, true, true>;
+        if (!allow_large_lds(kern, shmem, &granted[0])) return 0;
+        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, d_actions, n_steps, d_reward, d_done, d_obs);
+    } else if (grid_lds) {
+        auto kern = k_student_rollout<K, Word, EPW, true, false>;
+        if (!allow_large_lds(kern, shmem, &granted[1])) return 0;
+        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, d_actions, n_steps, d_reward, d_done, d_obs);
+    } else {
+        auto kern = k_student_rollout<K, Word, EPW, false, false>;
+        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, d_actions, n_steps, d_reward, d_done, d_obs);
+    }
+    return EPW * (p.N / EPW);
+}
+
+// Envs per workgroup: the largest of 128 / 64 / 32 whose grids fit in LDS and that still
+// gives every CU a workgroup; small batches take 32 so that more CUs take part.
 template <int K, typename Word>
 int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
-             uint8_t *d_done, int8_t *d_obs, int groups, hipStream_t st)
+             uint8_t *d_done, int8_t *d_obs, hipStream_t st)
 {
-    using V = View<K>;
     const StudentDev &p = ctx->dev;
-    // stage the grids in LDS when the workgroup's envs fit in 64 KB, else read rows from L2
-    bool grid_lds = Lds<K, Word>::bytes(p.SP, true) <= 64 * 1024;
-    size_t shmem = Lds<K, Word>::bytes(p.SP, grid_lds);
-    size_t shmem_render = Lds<K, Word>::bytes(p.SP, false);
-    dim3 grid(groups), block(64 * V::WAVES);
     if (n_steps == 0) {
-        hipLaunchKernelGGL((k_render_tiled<K, Word>), grid, dim3(EPW), shmem_render, st, p, d_obs);
-    } else if (grid_lds && p.HP == p.WP) {
-        hipLaunchKernelGGL((k_student_rollout<K, Word, true, true>), grid, block, shmem, st, p,
-                           d_actions, n_steps, d_reward, d_done, d_obs);
-    } else if (grid_lds) {
-        hipLaunchKernelGGL((k_student_rollout<K, Word, true, false>), grid, block, shmem, st, p,
-                           d_actions, n_steps, d_reward, d_done, d_obs);
-    } else {
-        hipLaunchKernelGGL((k_student_rollout<K, Word, false, false>), grid, block, shmem, st, p,
-                           d_actions, n_steps, d_reward, d_done, d_obs);
+        if (p.N < REPW) return 0;
+        const size_t shmem_render = Lds<K, Word, REPW>::bytes(p.SP, false);
+        hipLaunchKernelGGL((k_render_tiled<K, Word>), dim3(p.N / REPW), dim3(REPW), shmem_render, st,
+                           p, d_obs);
+        return REPW * (p.N / REPW);
     }
-    return 1;
+    const int cus = 256;
+    const bool fit128 = Lds<K, Word, 128>::bytes(p.SP, true) <= LDS_PER_CU - 1024;
+    const bool fit64 = Lds<K, Word, 64>::bytes(p.SP, true) <= LDS_PER_CU - 1024;
+    const bool fit32 = Lds<K, Word, 32>::bytes(p.SP, true) <= LDS_PER_CU - 1024;
+    if (p.N >= 128 * cus && fit128)
+        return launch_rollout<K, Word, 128>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
+    if (p.N >= 64 * cus && fit64)
+        return launch_rollout<K, Word, 64>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
+    if (p.N >= 32 && (fit32 || !fit64))
+        return launch_rollout<K, Word, 32>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
+    if (p.N >= 64)
+        return launch_rollout<K, Word, 64>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
+    return 0;
 }
 
 }  // namespace
 
-// Launch the tiled kernel on the first `*covered` envs (a multiple of EPW) and
-// report how many it took; the caller runs the per-cell kernel on the rest.
+// Launch the tiled kernel on the first `*covered` envs (a multiple of the workgroup's
+// envs) and report how many it took; the caller runs the per-cell kernel on the rest.
 // n_steps == 0 renders the current state.  Returns 0 if no tiled kernel applies.
 int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
                          uint8_t *d_done, int8_t *d_obs, int *covered, hipStream_t st)
@@ -512,18 +572,16 @@ int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_ste
     // actions must be 16-byte aligned
     if ((((size_t)p.N * 3 * K * K) & 15) != 0 || ((uintptr_t)d_obs & 15) != 0) return 0;
     if (n_steps > 0 && ((p.N & 15) != 0 || ((uintptr_t)d_actions & 15) != 0)) return 0;
-    int full = p.N / EPW;
-    if (full == 0) return 0;
-    int rc;
+    int done_envs;
     if (ctx->word64) {
-        if (K == 3) rc = launch_k<3, uint64_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, full, st);
-        else if (K == 5) rc = launch_k<5, uint64_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, full, st);
-        else rc = launch_k<7, uint64_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, full, st);
+        if (K == 3) done_envs = launch_k<3, uint64_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
+        else if (K == 5) done_envs = launch_k<5, uint64_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
+        else done_envs = launch_k<7, uint64_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
     } else {
-        if (K == 3) rc = launch_k<3, uint32_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, full, st);
-        else if (K == 5) rc = launch_k<5, uint32_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, full, st);
-        else rc = launch_k<7, uint32_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, full, st);
+        if (K == 3) done_envs = launch_k<3, uint32_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
+        else if (K == 5) done_envs = launch_k<5, uint32_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
+        else done_envs = launch_k<7, uint32_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
     }
-    if (rc) *covered = full * EPW;
-    return rc;
+    *covered = done_envs;
+    return done_envs > 0;
 }
