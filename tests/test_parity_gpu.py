@@ -157,6 +157,29 @@ def test_chunked_rollout_equals_one_launch():
     assert_state_equal(env, o)
 
 
+@pytest.mark.parametrize("N", [128, 256 + 32, 8192 + 64 + 5, 16384, 32768 + 128 + 40])
+def test_workgroup_size_choices(N):
+    """Batch sizes that make the launcher pick 32, 64 or 128 envs per workgroup, with tails."""
+    w = wl.student_random(f"epw{N}", 4000 + N, N=N, T=37, n_walls=50, max_steps=25)
+    note(w.name)
+    run_fused(w)
+
+
+def test_unaligned_buffers_take_the_per_cell_path():
+    """Views into larger tensors whose addresses are not 16-byte aligned still give exact results."""
+    w = wl.student_random("unaligned", 66, N=640, T=40, n_walls=50, max_steps=30)
+    env, o = gpu_student(w), cpu_student(w)
+    N, k, T = w.N, w.view, w.T
+    big_obs = torch.empty(T * N * k * k * 3 + 64, dtype=torch.int8, device=DEV)
+    obs = big_obs[3:3 + T * N * k * k * 3].view(T, N, k, k, 3)
+    big_act = torch.empty(T * N + 64, dtype=torch.int8, device=DEV)
+    acts = big_act[5:5 + T * N].view(T, N)
+    acts.copy_(to_gpu(w.actions))
+    r, d, obs = env.step(acts, obs=obs)
+    assert_rollout_equal((r, d, obs), o.step(w.actions, T), "unaligned")
+    assert_state_equal(env, o)
+
+
 def test_reset_to_new_levels_replaces_everything():
     w1 = wl.student_random("first", 1, N=500, T=50, n_walls=50)
     w2 = wl.student_random("second", 2, N=500, T=50, n_walls=10)
