@@ -69,7 +69,9 @@ int maze_destroy(maze_ctx *ctx);
  *   d_goal_xy   int32 [N,2]
  * Preconditions (caller's): agent and goal inside the interior, on free,
  * distinct cells.  For memory safety coordinates are clamped into the interior
- * and the heading is taken modulo 4.                                          */
+ * and the heading is taken modulo 4.  Other violations are simulated as they
+ * stand: a goal on a wall cell is never reached and renders as wall; an agent
+ * that starts on the goal finishes the episode on its first step.             */
 int maze_reset_to_levels(maze_ctx *ctx, const int8_t *d_walls, const int32_t *d_agent_xy,
                          const int8_t *d_agent_dir, const int32_t *d_goal_xy, void *stream);
 

@@ -160,8 +160,13 @@ __device__ __forceinline__ void produce_record(const uint32_t *lut, uint32_t *re
 #pragma unroll
     for (int q = 0; q < V::REC; ++q) rec[q] = D[q];
     // goal: the empty cell (100b) becomes a goal cell (010b): flip stream bits 3c+1, 3c+2
+    // (a goal that sits on a wall cell -- a level the caller should not build -- shows as wall)
     int c = gc + K / 2;                            // view column
     bool inview = ((unsigned)gf < (unsigned)K) & ((unsigned)c < (unsigned)K);
+    const int grow = inview ? K - 1 - gf : 0;      // view row of the goal
+    const uint32_t gword = (V::WV == 1 || grow < V::RPD) ? vw[0] : vw[V::WV - 1];
+    const int gshift = K * (grow < V::RPD ? grow : grow - V::RPD) + c;
+    inview = inview & !((gword >> (gshift & 31)) & 1);
     int cell = (K - 1 - gf) * K + c;
     int bit = 3 * cell + 1;
     if (inview) {

@@ -142,6 +142,20 @@ def test_degenerate_cases(variant):
     run_fused(w, variant)
 
 
+@pytest.mark.parametrize("k,S", [(5, 13), (7, 20), (3, 9)])
+@pytest.mark.parametrize("variant", [0, 1])
+def test_levels_outside_the_preconditions(k, S, variant):
+    """Goal on a wall, agent on a wall, agent on the goal: the oracle is total, so is the library."""
+    w = wl.student_random(f"odd-levels-k{k}", 91 + k, N=384, H=S, W=S, view=k, T=120, n_walls=S * S // 3,
+                          max_steps=50)
+    n = np.arange(w.N)
+    third = w.N // 3
+    w.walls[n[:third], w.goal_xy[:third, 1], w.goal_xy[:third, 0]] = 1            # goal on a wall
+    w.walls[n[third:2 * third], w.agent_xy[third:2 * third, 1], w.agent_xy[third:2 * third, 0]] = 1
+    w.goal_xy[2 * third:] = w.agent_xy[2 * third:]                                 # agent on the goal
+    run_fused(w, variant)
+
+
 def test_chunked_rollout_equals_one_launch():
     """State carried across calls: 256 steps as 1+7+64+184 equals one 256-step launch."""
     w = wl.student_random("chunks", 5, N=777, T=256, n_walls=50)
