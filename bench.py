@@ -185,6 +185,10 @@ def main():
         ms, mn = time_calls(torch, per_step, 200, warmup=20)
         rows["per_step_call_pattern_c3"] = {"ms": ms, "env-steps/s": N / ms * 1e3,
                                             "note": "maze_step(n=1) + maze_render_obs, launch-bound"}
+        o1 = obs[:1]
+        ms, mn = time_calls(torch, lambda: env.step(a1, r1, d1, o1), 200, warmup=20)
+        rows["per_step_with_obs_c3"] = {"ms": ms, "env-steps/s": N / ms * 1e3,
+                                        "note": "maze_step(n=1) writing obs: one launch per step"}
         # GAE on this rollout's outputs
         values = torch.rand((T + 1, N), dtype=torch.float32, device=dev)
         adv = torch.empty((T, N), dtype=torch.float32, device=dev)
@@ -243,7 +247,7 @@ def main():
         o = oracle.MazeOracle(N, w.H, w.W, k, w.max_steps)
         cpu_steps, t_cpu = 0, 0.0
         reps = 0
-        while t_cpu < 10.0 and reps < 64:
+        while t_cpu < 10.0 and reps < 1000:
             o.reset_to_levels(w.walls, w.agent_xy, w.agent_dir, w.goal_xy)
             c0 = time.perf_counter()
             o.render_obs()

@@ -456,13 +456,16 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     }
 }
 
-// ---------------------------------------------------- observation of the state
-// One workgroup of REPW threads per REPW envs: produce the records, then expand them
-// (no time loop).
+// ------------------------------- observation of the state / one step + observation
+// One workgroup of REPW threads per REPW envs, no time loop: optionally advance every
+// env by one step (the call a policy loop makes: state in and out of global memory, wall
+// rows from the packed grids in L2), then produce the records and expand them.
 constexpr int REPW = 64;
 
-template <int K, typename Word>
-__global__ __launch_bounds__(REPW) void k_render_tiled(StudentDev p, int8_t *__restrict__ obs)
+template <int K, typename Word, bool DO_STEP>
+__global__ __launch_bounds__(REPW) void k_step_render_tiled(
+    StudentDev p, const int8_t *__restrict__ actions, float *__restrict__ reward,
+    uint8_t *__restrict__ done, int8_t *__restrict__ obs)
 {
     using V = View<K, REPW>;
     using L = Lds<K, Word, REPW>;
@@ -474,7 +477,21 @@ __global__ __launch_bounds__(REPW) void k_render_tiled(StudentDev p, int8_t *__r
     __syncthreads();
     const Word *glob_env = (const Word *)p.grids + (size_t)n * 4 * p.SP;
     uint32_t pose = p.pose[n];
-    int xd = pose & 255, yd = (pose >> 8) & 255, d = (pose >> 16) & 3;
+    if (DO_STEP) {
+        const int a = actions[n];
+        const int xd0 = pose & 255, yd0 = (pose >> 8) & 255, d0 = (pose >> 16) & 3;
+        const bool blocked = (glob_env[d0 * p.SP + yd0 - 1] >> xd0) & 1;
+        pose = student_move(p, pose, a, blocked);
+        uint32_t t = p.tcount[n] + 1;
+        const bool reached = (pose & 0xFFFF) == p.goalrot[4 * (size_t)n + ((pose >> 16) & 3)];
+        const bool fin = reached || t >= (uint32_t)p.max_steps;
+        reward[n] = reached ? (float)(1.0 - (double)t * p.reward_slope) : 0.0f;
+        done[n] = fin ? 1 : 0;
+        if (fin) { pose = p.start[n]; t = 0; }
+        p.pose[n] = pose;
+        p.tcount[n] = t;
+    }
+    const int xd = pose & 255, yd = (pose >> 8) & 255, d = (pose >> 16) & 3;
     Word rows[K];
     load_view_rows<K, Word, false>(nullptr, glob_env, p.SP, d, yd, rows);
     uint32_t vw[V::WV];
@@ -538,11 +555,17 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
              uint8_t *d_done, int8_t *d_obs, hipStream_t st)
 {
     const StudentDev &p = ctx->dev;
-    if (n_steps == 0) {
+    if (n_steps <= 1) {
+        // render only (0) or the single step of a policy loop (1): one light launch
         if (p.N < REPW) return 0;
         const size_t shmem_render = Lds<K, Word, REPW>::bytes(p.SP, false);
-        hipLaunchKernelGGL((k_render_tiled<K, Word>), dim3(p.N / REPW), dim3(REPW), shmem_render, st,
-                           p, d_obs);
+        const dim3 grid(p.N / REPW), block(REPW);
+        if (n_steps == 0)
+            hipLaunchKernelGGL((k_step_render_tiled<K, Word, false>), grid, block, shmem_render, st, p,
+                               d_actions, d_reward, d_done, d_obs);
+        else
+            hipLaunchKernelGGL((k_step_render_tiled<K, Word, true>), grid, block, shmem_render, st, p,
+                               d_actions, d_reward, d_done, d_obs);
         return REPW * (p.N / REPW);
     }
     const int cus = 256;
@@ -564,7 +587,8 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
 
 // Launch the tiled kernel on the first `*covered` envs (a multiple of the workgroup's
 // envs) and report how many it took; the caller runs the per-cell kernel on the rest.
-// n_steps == 0 renders the current state.  Returns 0 if no tiled kernel applies.
+// n_steps == 0 renders the current state; n_steps == 1 is one step + observation in one
+// light launch.  Returns 0 if no tiled kernel applies.
 int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
                          uint8_t *d_done, int8_t *d_obs, int *covered, hipStream_t st)
 {
@@ -576,7 +600,7 @@ int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_ste
     // 16-byte accesses: every time step's obs block, the obs buffer and each step's row of
     // actions must be 16-byte aligned
     if ((((size_t)p.N * 3 * K * K) & 15) != 0 || ((uintptr_t)d_obs & 15) != 0) return 0;
-    if (n_steps > 0 && ((p.N & 15) != 0 || ((uintptr_t)d_actions & 15) != 0)) return 0;
+    if (n_steps > 1 && ((p.N & 15) != 0 || ((uintptr_t)d_actions & 15) != 0)) return 0;
     int done_envs;
     if (ctx->word64) {
         if (K == 3) done_envs = launch_k<3, uint64_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
