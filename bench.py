@@ -217,7 +217,7 @@ def main():
             ed.reset(edir)
             ed.step(eact, eobs, et, edn)
         ms, mn = time_calls(torch, editor_pass, 10)
-        ebytes = 515.0 * ew.N * ew.T
+        ebytes = 516.0 * ew.N * ew.T   # 4 action + 507 obs + 4 t + 1 done
         rows["editor_c4"] = {"ms": ms, "editor-steps/s": ew.N * ew.T / ms * 1e3,
                              "GB/s": ebytes / ms / 1e6, "frac_of_hbm_peak": ebytes / ms / 1e6 / HBM_PEAK_GBS}
         del eobs, et, edn, ed
