@@ -12,26 +12,25 @@
 // consecutive lanes take consecutive pieces, so one store instruction of a wave
 // writes 1 KB of contiguous, aligned output.
 //
-// The per-step work is a three-stage pipeline over the waves of the workgroup,
+// The per-step work is a four-stage pipeline over the waves of the workgroup,
 // advanced by one barrier per block of SPB steps:
-//   first  ("dynamics") block b  : action, move, goal/done/reset, read the K
-//                                     wall rows of the new view and publish the
-//                                     K x K view bits, the goal offset, reward, done
-//   next   ("records")  block b-1: view bits -> stream record (row lookup table),
-//                                     goal cell patched in; store reward and done
-//   rest   ("stores")   block b-2: expand records to bytes, store obs
-// (one dynamics and one records wave per 64 envs)
+//   first  ("dynamics") block b  : action, move (one wall word: the row ahead),
+//                                  goal/done/reset; publish pose, goal offset, outcome
+//   next   ("views")    block b-1: K wall rows of the view -> K x K view bits
+//   next   ("records")  block b-2: view bits -> stream record (row lookup table),
+//                                  goal cell patched in; store reward and done
+//   rest   ("stores")   block b-3: expand records to bytes, store obs
+// (one dynamics, one views and one records wave per 64 envs; every stage has at most
+// two dependent LDS round trips)
 // Only the dynamics wave carries a dependency from step to step, so the time per
 // step is that wave's short chain; the store waves never load from global memory
 // and the dynamics wave touches it once every 16 steps (actions, staged in LDS).
 #include "maze_internal.h"
 #include "maze_student_device.h"
 
-#include <type_traits>
-
 // Compile-time knobs (overridable for measurements).
 #ifndef MAZE_SPB
-#define MAZE_SPB 2
+#define MAZE_SPB 8
 #endif
 #ifndef MAZE_STORE_WAVES
 #define MAZE_STORE_WAVES 10
@@ -40,6 +39,14 @@
 namespace {
 
 constexpr int SPB = MAZE_SPB;   // steps per barrier: every stage handles SPB steps between barriers
+// Steps a stage handles together (all reads, then all writes): the largest power of two
+// that divides SPB and keeps the group's registers within `budget` dwords.
+constexpr int step_group(int dwords_per_step, int budget)
+{
+    int g = 1;
+    while (2 * g <= SPB && SPB % (2 * g) == 0 && 2 * g * dwords_per_step <= budget) g *= 2;
+    return g;
+}
 
 // Compile-time shape of a workgroup: view size K, EPW envs.
 template <int K, int EPW>
@@ -57,7 +64,7 @@ struct View {
     static constexpr int NWIN = EPW * SB / 16;     // 16-bit windows per workgroup step
     static constexpr int ROUNDS = (NWIN + 63) / 64;
     static constexpr int NC = ROUNDS < MAZE_STORE_WAVES ? ROUNDS : MAZE_STORE_WAVES;   // store waves
-    static constexpr int WAVES = 2 * NDYN + NC;
+    static constexpr int WAVES = 3 * NDYN + NC;
     // actions: one 16-byte load per lane covers 16 envs of one step, so a dynamics wave
     // stages ACT_BLOCK steps of its LA envs per load
     static constexpr int ACT_LPR = LA / 16;
@@ -84,9 +91,11 @@ struct Lds {
     static constexpr int LUT = 0;                                  // [LUTN]
     static constexpr int ACT = LUT + V::LUTN;                      // [2][ACT_BLOCK][EPW] action bytes
     static constexpr int ACT_ROW = EPW;                            // bytes per step
-    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][WV+2][EPW] view bits, goal, out
-    static constexpr int ST_SIZE = (V::WV + 2) * EPW;
-    static constexpr int REC = ST + 2 * SPB * ST_SIZE;             // [2][SPB][EPW*REC] stream records
+    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][3][EPW] pose, goal offset, out
+    static constexpr int ST_SIZE = 3 * EPW;
+    static constexpr int VW = ST + 2 * SPB * ST_SIZE;              // [2][SPB][WV+2][EPW] view bits, goal, out
+    static constexpr int VW_SIZE = (V::WV + 2) * EPW;
+    static constexpr int REC = VW + 2 * SPB * VW_SIZE;             // [2][SPB][EPW*REC] stream records
     static constexpr int REC_SIZE = EPW * V::REC;
     static constexpr int GRID0 = REC + 2 * SPB * REC_SIZE;         // [EPW][grid_stride]
     __host__ __device__ static int grid_stride(int SP)             // dwords per env, odd
@@ -141,39 +150,61 @@ __device__ __forceinline__ void pack_view(const Word (&rows)[K], int xd, uint32_
 
 // Stream record of one env from its view bits; goal at (gf cells ahead, gc cells to
 // the right) of the agent.  An empty cell is 100b, a wall 001b, the goal 010b.
+// record_lookup() only reads (the row table), record_finish() only computes, so a caller
+// that builds several records can issue all table reads before the first write.
+template <int K>
+__device__ __forceinline__ void record_lookup(const uint32_t *lut, const uint32_t (&vw)[View<K, 64>::WV],
+                                              uint32_t (&piece)[K])
+{
+    using V = View<K, 64>;
+#pragma unroll
+    for (int r = 0; r < K; ++r)
+        piece[r] = lut[(vw[r / V::RPD] >> (K * (r % V::RPD))) & (V::LUTN - 1)];
+}
+
+template <int K>
+__device__ __forceinline__ void record_finish(const uint32_t (&piece)[K],
+                                              const uint32_t (&vw)[View<K, 64>::WV], int gf, int gc,
+                                              uint32_t (&D)[View<K, 64>::ND], uint32_t *rec)
+{
+    using V = View<K, 64>;
+#pragma unroll
+    for (int q = 0; q < V::ND; ++q) D[q] = 0;
+#pragma unroll
+    for (int r = 0; r < K; ++r) {
+        const int off = V::ROWBITS * r, q = off >> 5, b = off & 31;
+        D[q] |= piece[r] << b;
+        if (b + V::ROWBITS > 32) D[q + 1] |= piece[r] >> (32 - b);
+    }
+    // goal: the empty cell (100b) becomes a goal cell (010b): flip stream bits 3c+1, 3c+2
+    // (a goal that sits on a wall cell -- a level the caller should not build -- shows as wall)
+    const int c = gc + K / 2;                      // view column
+    bool inview = ((unsigned)gf < (unsigned)K) & ((unsigned)c < (unsigned)K);
+    const int grow = inview ? K - 1 - gf : 0;      // view row of the goal
+    const uint32_t vw_first = vw[0], vw_last = vw[V::WV - 1];   // scalars: no indexed select
+    const uint32_t gword = (V::WV == 1 || grow < V::RPD) ? vw_first : vw_last;
+    const int gshift = K * (grow < V::RPD ? grow : grow - V::RPD) + c;
+    inview = inview & !((gword >> (gshift & 31)) & 1);
+    const int bit = inview ? 3 * (grow * K + c) + 1 : 0;
+    const uint64_t flip = inview ? (uint64_t)3 << (bit & 31) : 0;
+    const int fq = bit >> 5;
+#pragma unroll
+    for (int q = 0; q < V::ND; ++q) {
+        uint32_t m = (q == fq) ? (uint32_t)flip : 0u;
+        if (q > 0) m |= (q - 1 == fq) ? (uint32_t)(flip >> 32) : 0u;
+        rec[q] = D[q] ^ m;
+    }
+}
+
 template <int K>
 __device__ __forceinline__ void produce_record(const uint32_t *lut, uint32_t *rec,
                                                const uint32_t (&vw)[View<K, 64>::WV], int gf, int gc)
 {
     using V = View<K, 64>;
-    uint32_t D[V::REC];
-#pragma unroll
-    for (int q = 0; q < V::REC; ++q) D[q] = 0;
-#pragma unroll
-    for (int r = 0; r < K; ++r) {
-        uint32_t idx = (vw[r / V::RPD] >> (K * (r % V::RPD))) & (V::LUTN - 1);
-        uint32_t piece = lut[idx];
-        const int off = V::ROWBITS * r, q = off >> 5, b = off & 31;
-        D[q] |= piece << b;
-        if (b + V::ROWBITS > 32) D[q + 1] |= piece >> (32 - b);
-    }
-#pragma unroll
-    for (int q = 0; q < V::REC; ++q) rec[q] = D[q];
-    // goal: the empty cell (100b) becomes a goal cell (010b): flip stream bits 3c+1, 3c+2
-    // (a goal that sits on a wall cell -- a level the caller should not build -- shows as wall)
-    int c = gc + K / 2;                            // view column
-    bool inview = ((unsigned)gf < (unsigned)K) & ((unsigned)c < (unsigned)K);
-    const int grow = inview ? K - 1 - gf : 0;      // view row of the goal
-    const uint32_t gword = (V::WV == 1 || grow < V::RPD) ? vw[0] : vw[V::WV - 1];
-    const int gshift = K * (grow < V::RPD ? grow : grow - V::RPD) + c;
-    inview = inview & !((gword >> (gshift & 31)) & 1);
-    int cell = (K - 1 - gf) * K + c;
-    int bit = 3 * cell + 1;
-    if (inview) {
-        int q = bit >> 5, b = bit & 31;
-        atomicXor(&rec[q], 3u << b);
-        if (b == 31) atomicXor(&rec[q + 1], 1u);
-    }
+    uint32_t piece[K], D[V::ND];
+    record_lookup<K>(lut, vw, piece);
+    record_finish<K>(piece, vw, gf, gc, D, rec);
+    rec[V::ND] = 0;
 }
 
 // Lane-constant description of the 16 stream bits a lane expands in one round.
@@ -254,13 +285,123 @@ __device__ __forceinline__ void stage_grids(const StudentDev &p, uint32_t *lds, 
 }
 
 // ------------------------------------------------------------------ rollout
+// Wall word of row `row` of heading frame `dir` of one env.
+template <typename Word, bool GRID_LDS>
+__device__ __forceinline__ Word wall_row(const uint32_t *lds_env, const Word *glob_env, int SP,
+                                         int dir, int row)
+{
+    const int r = (int)__umul24((unsigned)dir, (unsigned)SP) + row;
+    if (!GRID_LDS) return glob_env[r];
+    if (sizeof(Word) == 4) return (Word)lds_env[r];
+    return (Word)(((uint64_t)lds_env[2 * r + 1] << 32) | lds_env[2 * r]);
+}
+
+// Per-lane state of the dynamics stage (one env per lane).
+template <typename Word>
+struct DynState {
+    int xd, yd, d;            // pose in the frame of its heading
+    int gf, gc;               // goal relative to the agent: cells ahead, cells to the right
+    uint32_t t;               // steps since the episode began
+    // The word of the row just ahead of the agent (row yd-1 of its frame) decides whether a
+    // forward step is blocked.  It is fetched one step early: as soon as the action is known
+    // the row ahead of the pose the action leads to -- taking a forward step as successful --
+    // is requested (`spec`), and the choice between that word, the previous one (the forward
+    // step hit a wall: pose unchanged) and the start pose's word (episode ended) is made at
+    // the top of the next step, when the LDS read has long returned.
+    Word ahead_keep, spec;
+    bool use_start, use_keep;
+    uint32_t act_off, a_next; // action ring cursor (bytes) and the next step's action
+};
+
+template <typename Word>
+struct DynConst {
+    int sxd, syd, sd, sgf, sgc;        // start pose and the goal's offset from it
+    Word ahead_start;                  // row ahead of the start pose
+    uint32_t tmax;
+    int HPm1, WPm1, SP;
+    const uint32_t *lds_env;
+    const Word *glob_env;
+    const uint8_t *act_lds;            // this env's column of the action ring
+    uint32_t act_mask, act_row;        // ring size - 1 and row pitch, bytes
+};
+
+// One env step of the dynamics stage; publishes pose, goal offset and outcome to st[].
+template <typename Word, int EPW, bool GRID_LDS, bool SQUARE>
+__device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word> &c, uint32_t *st)
+{
+    const uint32_t a = s.a_next;
+    s.act_off = (s.act_off + c.act_row) & c.act_mask;
+    s.a_next = c.act_lds[s.act_off];        // next step's action (staged >= half a block ago)
+    const bool tl = (a == 0), tr = (a == 1), f2 = (a == 2);
+    int rows_m1 = c.WPm1, bits_m1 = c.WPm1;
+    if (!SQUARE) {
+        const bool odd = s.d & 1;
+        rows_m1 = odd ? c.HPm1 : c.WPm1;
+        bits_m1 = odd ? c.WPm1 : c.HPm1;
+    }
+    // pose the action leads to if a forward step succeeds; request its row ahead
+    const int nx = tl ? rows_m1 - s.yd : (tr ? s.yd : s.xd);
+    const int sy = tl ? s.xd : (tr ? bits_m1 - s.xd : s.yd - (f2 ? 1 : 0));
+    const int nd = (s.d + (tl ? 3 : 0) + (tr ? 1 : 0)) & 3;
+    const Word ahead = s.use_start ? c.ahead_start : (s.use_keep ? s.ahead_keep : s.spec);
+    s.spec = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, c.SP, nd, sy - 1);
+    // the wall test for the current pose
+    const int blocked = sizeof(Word) == 4 ? (int)__builtin_amdgcn_ubfe((uint32_t)ahead, s.xd, 1)
+                                          : (int)((ahead >> s.xd) & 1);
+    const bool stay = f2 & (blocked != 0);          // forward into a wall: nothing moves
+    const int fw = f2 ? (blocked ^ 1) : 0;
+    const int ny = stay ? s.yd : sy;
+    const uint32_t t1 = s.t + 1;
+    const int nf = tl ? -s.gc : (tr ? s.gc : s.gf - fw);
+    const int nc = tl ? s.gf : (tr ? -s.gf : s.gc);
+    const bool reached = ((nf | nc) == 0);
+    const bool fin = reached | (t1 >= c.tmax);
+    // out word: step count if the goal was reached, done in bit 31
+    const uint32_t out = (reached ? t1 : 0u) | (fin ? 0x80000000u : 0u);
+    s.xd = fin ? c.sxd : nx;
+    s.yd = fin ? c.syd : ny;
+    s.d = fin ? c.sd : nd;
+    s.t = fin ? 0u : t1;
+    s.gf = fin ? c.sgf : nf;
+    s.gc = fin ? c.sgc : nc;
+    s.use_start = fin;
+    s.use_keep = stay;
+    s.ahead_keep = ahead;
+    st[0] = (uint32_t)s.xd | ((uint32_t)s.yd << 8) | ((uint32_t)s.d << 16);
+    st[EPW] = (uint32_t)(s.gf & 0xFFFF) | ((uint32_t)s.gc << 16);
+    st[2 * EPW] = out;
+}
+
 // Each role runs its own loop over blocks of SPB steps; every wave passes exactly
-// ceil(n_steps / SPB) + 3 barriers.
+// ceil(n_steps / SPB) + 4 barriers.
 //   between barriers b and b+1:  dynamics builds block b   -> ST[b&1]
-//                                records  builds block b-1 -> REC[(b-1)&1]  (reads ST[(b-1)&1])
-//                                stores   drain  block b-2                  (read REC[(b-2)&1])
+//                                views    builds block b-1 -> VW[(b-1)&1]   (reads ST[(b-1)&1])
+//                                records  builds block b-2 -> REC[(b-2)&1]  (reads VW[(b-2)&1])
+//                                stores   drain  block b-3                  (read REC[(b-3)&1])
 // so no buffer is written while it is read.  The block loops are unrolled by two so
 // every LDS address is a lane constant plus an immediate.
+// The body of a role handles one block: it sees i0 (the block's first step), par (the
+// block's parity: its buffers), and `full` (a compile-time flag: every one of the SPB
+// steps exists; otherwise step i0+u must be tested against n_steps).  Bodies are written
+// in phases over the block's steps -- all reads, then all writes -- so that independent
+// steps overlap their LDS round trips.
+#define MAZE_STEP_ON(u) (full || i0 + (u) < n_steps)
+#define MAZE_FOR_EACH_BLOCK(...)                                                           \
+    for (int blk0 = 0; blk0 < n_steps; blk0 += 2 * SPB) {                                  \
+        _Pragma("unroll") for (int par = 0; par < 2; ++par) {                              \
+            const int i0 = blk0 + par * SPB;                                               \
+            if (i0 + SPB <= n_steps) {                                                     \
+                constexpr bool full = true;                                                \
+                { __VA_ARGS__; }                                                           \
+                __syncthreads();                                                           \
+            } else if (i0 < n_steps) {                                                     \
+                constexpr bool full = false;                                               \
+                { __VA_ARGS__; }                                                           \
+                __syncthreads();                                                           \
+            }                                                                              \
+        }                                                                                  \
+    }
+
 template <int K, typename Word, int EPW, bool GRID_LDS, bool SQUARE>
 __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     StudentDev p, const int8_t *__restrict__ actions, int n_steps, float *__restrict__ reward,
@@ -270,10 +411,13 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     using L = Lds<K, Word, EPW>;
     constexpr int NT = 64 * V::WAVES;
     constexpr int ACT_BLOCK = V::ACT_BLOCK;
+    constexpr int UGV = step_group(K * WordOps<Word>::DW + 3, 40);   // views: wall rows + state
+    constexpr int UGR = step_group(K + V::WV + 2, 48);               // records: table words + view
     extern __shared__ uint32_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int env0 = blockIdx.x * EPW;
+    const int SP = p.SP, N = p.N;
 
     fill_lut<K>(lds + L::LUT, tid, NT);
     if (GRID_LDS) stage_grids<K, Word, EPW>(p, lds, tid, NT, env0);
@@ -284,175 +428,151 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         const int e = wave * 64 + (active ? lane : 0);   // env within the workgroup
         const int n = env0 + e;
         const int last = n_steps - 1;
-        uint32_t pose = p.pose[n];
-        int xd = pose & 255, yd = (pose >> 8) & 255, d = (pose >> 16) & 3;
-        uint32_t t = p.tcount[n];
-        const uint32_t start = p.start[n];
-        const int sxd = start & 255, syd = (start >> 8) & 255, sd = (start >> 16) & 3;
-        // goal relative to the agent in the agent's own frame: gf cells ahead, gc cells to
-        // the right.  Turning rotates this vector, moving forward shortens gf.
-        const uint32_t g_now = p.goalrot[4 * (size_t)n + d], g_start = p.goalrot[4 * (size_t)n + sd];
-        int gf = yd - (int)(g_now >> 8), gc = (int)(g_now & 255) - xd;
-        const int sgf = syd - (int)(g_start >> 8), sgc = (int)(g_start & 255) - sxd;
-        const uint32_t tmax = (uint32_t)p.max_steps;
-        const int HPm1 = p.HP - 1, WPm1 = p.WP - 1;
-        const uint32_t *lds_env = lds + L::GRID0 + e * (GRID_LDS ? L::grid_stride(p.SP) : 0);
-        const Word *glob_env = (const Word *)p.grids + (size_t)n * 4 * p.SP;
+        DynState<Word> s;
+        DynConst<Word> c;
+        const uint32_t pose = p.pose[n], start = p.start[n];
+        s.xd = pose & 255; s.yd = (pose >> 8) & 255; s.d = (pose >> 16) & 3;
+        s.t = p.tcount[n];
+        c.sxd = start & 255; c.syd = (start >> 8) & 255; c.sd = (start >> 16) & 3;
+        // goal relative to the agent in the agent's own frame; turning rotates this vector,
+        // moving forward shortens gf
+        const uint32_t g_now = p.goalrot[4 * (size_t)n + s.d], g_start = p.goalrot[4 * (size_t)n + c.sd];
+        s.gf = s.yd - (int)(g_now >> 8); s.gc = (int)(g_now & 255) - s.xd;
+        c.sgf = c.syd - (int)(g_start >> 8); c.sgc = (int)(g_start & 255) - c.sxd;
+        c.tmax = (uint32_t)p.max_steps;
+        c.HPm1 = p.HP - 1; c.WPm1 = p.WP - 1; c.SP = SP;
+        c.lds_env = lds + L::GRID0 + e * (GRID_LDS ? L::grid_stride(SP) : 0);
+        c.glob_env = (const Word *)p.grids + (size_t)n * 4 * SP;
+        c.act_lds = (const uint8_t *)(lds + L::ACT) + e;
+        c.act_row = L::ACT_ROW;
+        c.act_mask = 2 * ACT_BLOCK * L::ACT_ROW - 1;
         // actions: lane l of this wave stages the bytes of step block*ACT_BLOCK + l/ACT_LPR
         // for 16 of the wave's envs (all 64 lanes stage, whatever LA is)
         const int stage_row = lane / V::ACT_LPR;
         const int stage_col = wave * 64 + 16 * (lane % V::ACT_LPR);
         const int8_t *act_lane = actions + env0 + stage_col;
         uint8_t *act_stage = (uint8_t *)(lds + L::ACT) + stage_row * L::ACT_ROW + stage_col;
-        auto load_actions = [&](int block) {
-            int s = min(block * ACT_BLOCK + stage_row, last);
-            return *(const uint4 *)(act_lane + (size_t)s * p.N);
-        };
-        *(uint4 *)act_stage = load_actions(0);
-        uint4 act_regs = load_actions(1);
+        *(uint4 *)act_stage = *(const uint4 *)(act_lane + (size_t)min(stage_row, last) * N);
+        uint4 act_regs = *(const uint4 *)(act_lane + (size_t)min(ACT_BLOCK + stage_row, last) * N);
         __syncthreads();                                             // barrier 0 (set-up)
-        Word rows[K];
-        load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, p.SP, d, yd, rows);
-        Word ahead = rows[K - 2];          // wall word of the row just ahead of the agent
-        const uint8_t *act_lds = (const uint8_t *)(lds + L::ACT) + e;
-        uint32_t act_off = 0;              // byte offset of the current step's row in the ring
-        uint32_t a_next = act_lds[0];
-
-        auto env_step = [&](int slot) {
-            const uint32_t a = a_next;
-            act_off = (act_off + L::ACT_ROW) & (2 * ACT_BLOCK * L::ACT_ROW - 1);
-            a_next = act_lds[act_off];     // next step's action (staged >= 8 steps ago)
-            t += 1;
-            const int blocked = sizeof(Word) == 4 ? (int)__builtin_amdgcn_ubfe((uint32_t)ahead, xd, 1)
-                                                  : (int)((ahead >> xd) & 1);
-            const bool tl = (a == 0), tr = (a == 1);
-            const int fw = (a == 2) ? (blocked ^ 1) : 0;
-            int rows_m1 = WPm1, bits_m1 = WPm1;
-            if (!SQUARE) {
-                const bool odd = d & 1;
-                rows_m1 = odd ? HPm1 : WPm1;
-                bits_m1 = odd ? WPm1 : HPm1;
-            }
-            const int nx = tl ? rows_m1 - yd : (tr ? yd : xd);
-            const int ny = tl ? xd : (tr ? bits_m1 - xd : yd - fw);
-            const int nf = tl ? -gc : (tr ? gc : gf - fw);
-            const int nc = tl ? gf : (tr ? -gf : gc);
-            d = (d + (tl ? 3 : 0) + (tr ? 1 : 0)) & 3;
-            const bool reached = ((nf | nc) == 0);
-            const bool fin = reached | (t >= tmax);
-            // out word: step count if the goal was reached, done in bit 31
-            const uint32_t out = (reached ? t : 0u) | (fin ? 0x80000000u : 0u);
-            xd = fin ? sxd : nx;
-            yd = fin ? syd : ny;
-            d = fin ? sd : d;
-            t = fin ? 0u : t;
-            gf = fin ? sgf : nf;
-            gc = fin ? sgc : nc;
-            load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, p.SP, d, yd, rows);
-            ahead = rows[K - 2];
-            uint32_t vw[V::WV];
-            pack_view<K, Word>(rows, xd, vw);
-            uint32_t *st = lds + L::ST + slot * L::ST_SIZE + e;
-#pragma unroll
-            for (int q = 0; q < V::WV; ++q) st[q * EPW] = vw[q];
-            st[V::WV * EPW] = (uint32_t)(gf & 0xFFFF) | ((uint32_t)gc << 16);
-            st[(V::WV + 1) * EPW] = out;
-        };
-        auto step = [&](int i, int slot) {
-            if (active) env_step(slot);
-            // stage the next block of actions half way through the current one
-            if ((i & (ACT_BLOCK - 1)) == ACT_BLOCK / 2) {
-                const int nb = i / ACT_BLOCK + 1;
-                *(uint4 *)(act_stage + (nb & 1) * (ACT_BLOCK * L::ACT_ROW)) = act_regs;
-                act_regs = load_actions(nb + 1);
-            }
-        };
-        auto block = [&](int i0, auto PAR) {
-#pragma unroll
-            for (int u = 0; u < SPB; ++u)
-                if (i0 + u < n_steps) step(i0 + u, decltype(PAR)::value * SPB + u);
-            __syncthreads();
-        };
-        int i = 0;
-        for (; i + SPB < n_steps; i += 2 * SPB) {
-            block(i, std::integral_constant<int, 0>());
-            block(i + SPB, std::integral_constant<int, 1>());
-        }
-        if (i < n_steps) block(i, std::integral_constant<int, 0>());
+        c.ahead_start = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, SP, c.sd, c.syd - 1);
+        s.ahead_keep = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, SP, s.d, s.yd - 1);
+        s.spec = s.ahead_keep;
+        s.use_start = false; s.use_keep = true;
+        s.act_off = 0;
+        s.a_next = c.act_lds[0];
+        uint32_t *st_e = lds + L::ST + e;
+        MAZE_FOR_EACH_BLOCK(
+            _Pragma("unroll") for (int u = 0; u < SPB; ++u) {
+                const int i = i0 + u;
+                if (!MAZE_STEP_ON(u)) continue;
+                if (active)
+                    dyn_step<Word, EPW, GRID_LDS, SQUARE>(s, c, st_e + (par * SPB + u) * L::ST_SIZE);
+                // stage the next block of actions half way through the current one
+                if ((i & (ACT_BLOCK - 1)) == ACT_BLOCK / 2) {
+                    const int nb = i / ACT_BLOCK + 1;
+                    *(uint4 *)(act_stage + (nb & 1) * (ACT_BLOCK * L::ACT_ROW)) = act_regs;
+                    act_regs = *(const uint4 *)(act_lane +
+                                                (size_t)min((nb + 1) * ACT_BLOCK + stage_row, last) * N);
+                }
+            })
         if (active) {
-            p.pose[n] = (uint32_t)xd | ((uint32_t)yd << 8) | ((uint32_t)d << 16);
-            p.tcount[n] = t;
+            p.pose[n] = (uint32_t)s.xd | ((uint32_t)s.yd << 8) | ((uint32_t)s.d << 16);
+            p.tcount[n] = s.t;
         }
+        __syncthreads();
         __syncthreads();
         __syncthreads();
     } else if (wave < 2 * V::NDYN) {
-        // ================================================================= records
+        // =================================================================== views
         const bool active = lane < V::LA;
         const int e = (wave - V::NDYN) * 64 + (active ? lane : 0);
+        const uint32_t *lds_env = lds + L::GRID0 + e * (GRID_LDS ? L::grid_stride(SP) : 0);
+        const Word *glob_env = (const Word *)p.grids + (size_t)(env0 + e) * 4 * SP;
+        __syncthreads();                                             // barrier 0 (set-up)
+        __syncthreads();                                             // block 0 published
+        MAZE_FOR_EACH_BLOCK(
+            if (active) {
+                _Pragma("unroll") for (int u0 = 0; u0 < SPB; u0 += UGV) {
+                    uint32_t pose[UGV], g[UGV], out[UGV];
+                    Word rows[UGV][K];
+                    _Pragma("unroll") for (int w = 0; w < UGV; ++w) if (MAZE_STEP_ON(u0 + w)) {
+                        const uint32_t *st = lds + L::ST + (par * SPB + u0 + w) * L::ST_SIZE + e;
+                        pose[w] = st[0]; g[w] = st[EPW]; out[w] = st[2 * EPW];
+                    }
+                    _Pragma("unroll") for (int w = 0; w < UGV; ++w) if (MAZE_STEP_ON(u0 + w))
+                        load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, SP, (pose[w] >> 16) & 3,
+                                                          (pose[w] >> 8) & 255, rows[w]);
+                    _Pragma("unroll") for (int w = 0; w < UGV; ++w) if (MAZE_STEP_ON(u0 + w)) {
+                        uint32_t vw[V::WV];
+                        pack_view<K, Word>(rows[w], pose[w] & 255, vw);
+                        uint32_t *v = lds + L::VW + (par * SPB + u0 + w) * L::VW_SIZE + e;
+                        _Pragma("unroll") for (int q = 0; q < V::WV; ++q) v[q * EPW] = vw[q];
+                        v[V::WV * EPW] = g[w];
+                        v[(V::WV + 1) * EPW] = out[w];
+                    }
+                }
+            })
+        __syncthreads();
+        __syncthreads();
+    } else if (wave < 3 * V::NDYN) {
+        // ================================================================= records
+        const bool active = lane < V::LA;
+        const int e = (wave - 2 * V::NDYN) * 64 + (active ? lane : 0);
         float *rw = reward + env0 + e;
         uint8_t *dn = done + env0 + e;
         const double slope = p.reward_slope;
+        // the zero dword that ends every record is written once
+        if (active)
+            for (int sl = 0; sl < 2 * SPB; ++sl) lds[L::REC + sl * L::REC_SIZE + e * V::REC + V::ND] = 0;
         __syncthreads();                                             // barrier 0 (set-up)
         __syncthreads();                                             // block 0 published
-        auto step = [&](int slot) {
-            const uint32_t *st = lds + L::ST + slot * L::ST_SIZE + e;
-            uint32_t vw[V::WV];
-#pragma unroll
-            for (int q = 0; q < V::WV; ++q) vw[q] = st[q * EPW];
-            const uint32_t g = st[V::WV * EPW];
-            const uint32_t out = st[(V::WV + 1) * EPW];
-            produce_record<K>(lds + L::LUT, lds + L::REC + slot * L::REC_SIZE + e * V::REC, vw,
-                              (int)(int16_t)(g & 0xFFFF), (int)g >> 16);
-            const uint32_t tr = out & 0x7FFFFFFFu;
-            *rw = tr ? (float)(1.0 - (double)tr * slope) : 0.0f;
-            *dn = (uint8_t)(out >> 31);
-            rw += p.N;
-            dn += p.N;
-        };
-        auto block = [&](int s0, auto PAR) {
-#pragma unroll
-            for (int u = 0; u < SPB; ++u)
-                if (s0 + u < n_steps && active) step(decltype(PAR)::value * SPB + u);
-            __syncthreads();
-        };
-        int s = 0;
-        for (; s + SPB < n_steps; s += 2 * SPB) {
-            block(s, std::integral_constant<int, 0>());
-            block(s + SPB, std::integral_constant<int, 1>());
-        }
-        if (s < n_steps) block(s, std::integral_constant<int, 0>());
+        __syncthreads();                                             // block 0 viewed
+        MAZE_FOR_EACH_BLOCK(
+            if (active) {
+                _Pragma("unroll") for (int u0 = 0; u0 < SPB; u0 += UGR) {
+                    uint32_t vw[UGR][V::WV], g[UGR], out[UGR], piece[UGR][K];
+                    _Pragma("unroll") for (int w = 0; w < UGR; ++w) if (MAZE_STEP_ON(u0 + w)) {
+                        const uint32_t *v = lds + L::VW + (par * SPB + u0 + w) * L::VW_SIZE + e;
+                        _Pragma("unroll") for (int q = 0; q < V::WV; ++q) vw[w][q] = v[q * EPW];
+                        g[w] = v[V::WV * EPW]; out[w] = v[(V::WV + 1) * EPW];
+                    }
+                    _Pragma("unroll") for (int w = 0; w < UGR; ++w) if (MAZE_STEP_ON(u0 + w))
+                        record_lookup<K>(lds + L::LUT, vw[w], piece[w]);
+                    _Pragma("unroll") for (int w = 0; w < UGR; ++w) if (MAZE_STEP_ON(u0 + w)) {
+                        uint32_t D[V::ND];
+                        uint32_t *rec = lds + L::REC + (par * SPB + u0 + w) * L::REC_SIZE + e * V::REC;
+                        record_finish<K>(piece[w], vw[w], (int)(int16_t)(g[w] & 0xFFFF), (int)g[w] >> 16,
+                                         D, rec);
+                        const uint32_t tr = out[w] & 0x7FFFFFFFu;
+                        rw[(size_t)(u0 + w) * N] = tr ? (float)(1.0 - (double)tr * slope) : 0.0f;
+                        dn[(size_t)(u0 + w) * N] = (uint8_t)(out[w] >> 31);
+                    }
+                }
+                rw += (size_t)SPB * N;
+                dn += (size_t)SPB * N;
+            })
         __syncthreads();
     } else {
         // ================================================================== stores
-        const int c = wave - 2 * V::NDYN;
+        const int cw = wave - 3 * V::NDYN;
         constexpr int MYR = (V::ROUNDS + V::NC - 1) / V::NC;     // rounds per store wave, at most
         Window win[MYR];
 #pragma unroll
-        for (int j = 0; j < MYR; ++j) win[j] = make_window<K, EPW>(lane, c + j * V::NC);
-        const size_t step_obs = (size_t)p.N * V::SB;
+        for (int j = 0; j < MYR; ++j) win[j] = make_window<K, EPW>(lane, cw + j * V::NC);
+        const size_t step_obs = (size_t)N * V::SB;
         int8_t *out_block = obs + (size_t)env0 * V::SB;
         __syncthreads();                                             // barrier 0 (set-up)
         __syncthreads();                                             // block 0 published
+        __syncthreads();                                             // block 0 viewed
         __syncthreads();                                             // block 0 recorded
-        auto step = [&](int slot) {
-            const uint32_t *rec = lds + L::REC + slot * L::REC_SIZE;
-#pragma unroll
-            for (int j = 0; j < MYR; ++j)
-                if (win[j].active) consume_window(rec, win[j], out_block);
-            out_block += step_obs;
-        };
-        auto block = [&](int s0, auto PAR) {
-#pragma unroll
-            for (int u = 0; u < SPB; ++u)
-                if (s0 + u < n_steps) step(decltype(PAR)::value * SPB + u);
-            __syncthreads();
-        };
-        int s = 0;
-        for (; s + SPB < n_steps; s += 2 * SPB) {
-            block(s, std::integral_constant<int, 0>());
-            block(s + SPB, std::integral_constant<int, 1>());
-        }
-        if (s < n_steps) block(s, std::integral_constant<int, 0>());
+        MAZE_FOR_EACH_BLOCK(
+            _Pragma("unroll") for (int u = 0; u < SPB; ++u) if (MAZE_STEP_ON(u)) {
+                const uint32_t *rec = lds + L::REC + (par * SPB + u) * L::REC_SIZE;
+                _Pragma("unroll") for (int j = 0; j < MYR; ++j)
+                    if (win[j].active) consume_window(rec, win[j], out_block + u * step_obs);
+            }
+            out_block += SPB * step_obs;)
     }
 }
 
@@ -568,6 +688,10 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
                                d_actions, d_reward, d_done, d_obs);
         return REPW * (p.N / REPW);
     }
+#ifdef MAZE_FORCE_EPW
+    if (p.N >= MAZE_FORCE_EPW)
+        return launch_rollout<K, Word, MAZE_FORCE_EPW>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
+#endif
     const int cus = 256;
     const bool fit128 = Lds<K, Word, 128>::bytes(p.SP, true) <= LDS_PER_CU - 1024;
     const bool fit64 = Lds<K, Word, 64>::bytes(p.SP, true) <= LDS_PER_CU - 1024;
