@@ -165,3 +165,44 @@ def compute_gae(rewards, values, dones, gamma: float, lam: float):
     _load().orc_gae(T, N, ctypes.c_double(gamma), ctypes.c_double(lam),
                     _p(rewards), _p(values), _p(dones), _p(adv), _p(ret))
     return adv, ret
+
+
+def level_metrics(walls, agent_xy, goal_xy):
+    """walls i8 [N,H,W], agent_xy / goal_xy i32 [N,2] -> (n_walls, path_len) int32 [N].
+
+    path_len: fewest moves between 4-neighbours from the start cell to the goal cell
+    (-1 if unreachable), by breadth-first search (Section 3, shortest paths).
+    """
+    walls = _req(walls, np.int8)
+    N, H, W = walls.shape
+    agent_xy = _req(agent_xy, np.int32, (N, 2))
+    goal_xy = _req(goal_xy, np.int32, (N, 2))
+    n_walls = np.empty(N, np.int32)
+    path_len = np.empty(N, np.int32)
+    scratch = np.empty((max(1, num_threads()), 2 * H * W), np.int32)
+    _load().orc_level_metrics(N, H, W, _p(walls), _p(agent_xy), _p(goal_xy), _p(n_walls),
+                              _p(path_len), _p(scratch))
+    return n_walls, path_len
+
+
+def apsp_seidel(adj: np.ndarray) -> np.ndarray:
+    """All-pairs distances of a connected, undirected, unweighted graph by the
+    matrix-product recursion the paper names for its shortest paths (Section 3).
+
+    adj: [V,V] 0/1 symmetric, zero diagonal.  Returns int64 [V,V].
+    The square of the graph (pairs at distance <= 2) is solved first; a distance is
+    then twice the squared graph's distance, minus one when it is odd, and parity is
+    read off from how the squared-graph distances of j's neighbours compare with j's.
+    """
+    A = np.asarray(adj, dtype=np.int64)
+    V = A.shape[0]
+    if V <= 1:
+        return np.zeros((V, V), np.int64)
+    off = ~np.eye(V, dtype=bool)
+    B = (((A @ A) > 0) | (A > 0)) & off
+    if B[off].all():
+        return (2 * B - A) * off
+    T = apsp_seidel(B.astype(np.int64))
+    X = T @ A
+    deg = A.sum(axis=0)
+    return 2 * T - (X < T * deg[None, :])

@@ -300,3 +300,62 @@ void orc_gae(int T, int N, double gamma, double lambda,
         }
     }
 }
+
+/* ---------------------------------------------------------------------------
+ * Level metrics (Section 2.2: environments may report per-level metrics such
+ * as the number of walls; Section 3 and the shortest-path figure of Section 4:
+ * shortest path length of a maze).
+ *
+ *   n_walls[n]  = number of interior wall cells
+ *   path_len[n] = fewest forward moves that take the agent from its start cell
+ *                 to the goal cell through cells that are not walls, moving
+ *                 between 4-neighbours; turns cost nothing; 0 if start = goal;
+ *                 -1 if the goal cannot be reached.
+ *
+ * The paper obtains the distances with a matrix-based all-pairs algorithm; a
+ * breadth-first search from the start cell defines the same number and is what
+ * is written here.  `queue` is caller-provided scratch of H*W ints per thread.
+ * ------------------------------------------------------------------------- */
+static int bfs_one(int H, int W, const int8_t *walls, int sx, int sy, int gx, int gy,
+                   int32_t *dist /* [H*W] */, int32_t *queue /* [H*W] */)
+{
+    for (int i = 0; i < H * W; ++i) dist[i] = -1;
+    if (is_wall(walls, H, W, sx, sy)) return -1;
+    int head = 0, tail = 0;
+    dist[sy * W + sx] = 0;
+    queue[tail++] = sy * W + sx;
+    while (head < tail) {
+        int c = queue[head++];
+        int x = c % W, y = c / W;
+        if (x == gx && y == gy) return dist[c];
+        for (int d = 0; d < 4; ++d) {
+            int nx = x + DX[d], ny = y + DY[d];
+            if (is_wall(walls, H, W, nx, ny)) continue;
+            if (dist[ny * W + nx] >= 0) continue;
+            dist[ny * W + nx] = dist[c] + 1;
+            queue[tail++] = ny * W + nx;
+        }
+    }
+    return -1;
+}
+
+void orc_level_metrics(int N, int H, int W, const int8_t *walls /* [N,H,W] */,
+                       const int32_t *agent_xy /* [N,2] */, const int32_t *goal_xy /* [N,2] */,
+                       int32_t *n_walls /* [N] */, int32_t *path_len /* [N] */,
+                       int32_t *scratch /* [threads, 2*H*W] */)
+{
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+#ifdef _OPENMP
+        int32_t *s = scratch + (size_t)omp_get_thread_num() * 2 * H * W;
+#else
+        int32_t *s = scratch;
+#endif
+        const int8_t *w = walls + (size_t)n * H * W;
+        int count = 0;
+        for (int i = 0; i < H * W; ++i) count += w[i] ? 1 : 0;
+        n_walls[n] = count;
+        path_len[n] = bfs_one(H, W, w, agent_xy[2 * n], agent_xy[2 * n + 1],
+                              goal_xy[2 * n], goal_xy[2 * n + 1], s, s + H * W);
+    }
+}
