@@ -185,6 +185,11 @@ def main():
         ms, mn = time_calls(torch, per_step, 200, warmup=20)
         rows["per_step_call_pattern_c3"] = {"ms": ms, "env-steps/s": N / ms * 1e3,
                                             "note": "maze_step(n=1) + maze_render_obs, launch-bound"}
+        nwalls = torch.empty((N,), dtype=torch.int32, device=dev)
+        plen = torch.empty((N,), dtype=torch.int32, device=dev)
+        ms, mn = time_calls(torch, lambda: env.level_metrics(nwalls, plen), 50)
+        rows["maze_level_metrics_c3"] = {"ms": ms, "levels/s": N / ms * 1e3,
+                                         "note": "wall count + shortest path (bit-parallel flood)"}
         o1 = obs[:1]
         ms, mn = time_calls(torch, lambda: env.step(a1, r1, d1, o1), 200, warmup=20)
         rows["per_step_with_obs_c3"] = {"ms": ms, "env-steps/s": N / ms * 1e3,
@@ -234,6 +239,11 @@ def main():
         b5 = 153.0 * w5.N * w5.T
         rows["student_rollout_c5"] = {"ms": ms, "env-steps/s": w5.N * w5.T / ms * 1e3,
                                       "GB/s": b5 / ms / 1e6, "frac_of_hbm_peak": b5 / ms / 1e6 / HBM_PEAK_GBS}
+        nw5 = torch.empty((w5.N,), dtype=torch.int32, device=dev)
+        pl5 = torch.empty((w5.N,), dtype=torch.int32, device=dev)
+        ms, mn = time_calls(torch, lambda: env5.level_metrics(nw5, pl5), 20)
+        rows["maze_level_metrics_c5"] = {"ms": ms, "levels/s": w5.N / ms * 1e3,
+                                         "mean_path_len": float(pl5.float().mean())}
         del o5, env5
         # plain streaming-write ceiling of this GPU (torch fill of the obs buffer)
         ms, mn = time_calls(torch, lambda: obs.fill_(1), 10)

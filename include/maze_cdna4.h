@@ -106,6 +106,19 @@ int maze_get_state(maze_ctx *ctx, int32_t *d_xy, int8_t *d_dir, int32_t *d_t, vo
 int maze_get_levels(maze_ctx *ctx, int8_t *d_walls, int32_t *d_agent_xy, int8_t *d_agent_dir,
                     int32_t *d_goal_xy, void *stream);
 
+/* Level metrics of the levels held by ctx (Section 2.2: per-level metrics such as
+ * the number of walls; Section 3: shortest paths, which the paper computes with a
+ * matrix-based all-pairs algorithm -- the distance between two given cells is the
+ * same number whichever way it is found).
+ *   d_n_walls  int32 [N]: interior wall cells
+ *   d_path_len int32 [N]: fewest moves between 4-neighbouring non-wall cells from
+ *                         the level's start cell to its goal cell (turns are free);
+ *                         0 if they coincide, -1 if the goal cannot be reached or
+ *                         the start cell is a wall.
+ * Either pointer may be NULL.  Depends only on the levels, not on the current
+ * state.  MAZE_ESIZE if H > 64.                                                  */
+int maze_level_metrics(maze_ctx *ctx, int32_t *d_n_walls, int32_t *d_path_len, void *stream);
+
 /* Choose the kernel family used by maze_step / maze_render_obs: 0 = automatic
  * (the tiled store-layout kernels when the shape allows, else the per-cell
  * kernel), 1 = always the per-cell kernel.  Results are identical; meant for

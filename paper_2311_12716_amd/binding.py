@@ -28,6 +28,7 @@ SIGNATURES = {
     "maze_render_obs": (c_int, [c_void_p, c_void_p, c_void_p]),
     "maze_get_state": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_get_levels": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
+    "maze_level_metrics": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_set_kernel_variant": (c_int, [c_void_p, c_int]),
     "editor_workspace_bytes": (c_int, [c_int, c_int, c_int, POINTER(c_size_t)]),
     "editor_create": (c_int, [POINTER(c_void_p), c_int, c_int, c_int, c_int, c_void_p, c_size_t]),
@@ -166,6 +167,18 @@ class MazeEnv:
                                               ad.data_ptr(), gxy.data_ptr(), _stream()),
                "maze_get_levels")
         return walls, axy, ad, gxy
+
+
+    def level_metrics(self, n_walls=None, path_len=None):
+        """(n_walls, path_len) int32 [N] of the current levels; path_len -1 = unreachable."""
+        N, dev = self.N, self.device
+        if n_walls is None:
+            n_walls = torch.empty((N,), dtype=torch.int32, device=dev)
+        if path_len is None:
+            path_len = torch.empty((N,), dtype=torch.int32, device=dev)
+        _check(load_library().maze_level_metrics(self._h, n_walls.data_ptr(), path_len.data_ptr(),
+                                                 _stream()), "maze_level_metrics")
+        return n_walls, path_len
 
 
 class EditorEnv:
