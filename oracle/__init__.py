@@ -153,6 +153,59 @@ class EditorOracle:
         return Levels(self.walls.copy(), self.agent_xy.copy(), self.agent_dir.copy(),
                       self.goal_xy.copy())
 
+    def set_levels(self, walls, agent_xy, agent_dir, goal_xy) -> None:
+        """Load finished levels (Section 2.2: setter of the free parameters); coordinates
+        are clamped into the interior, everything else is copied as it is."""
+        N, H, W = self.N, self.H, self.W
+        self.walls = (_req(walls, np.int8, (N, H, W)) != 0).astype(np.int8)
+        hi = np.array([W - 1, H - 1], np.int32)
+        self.agent_xy = np.clip(_req(agent_xy, np.int32, (N, 2)), 0, hi).astype(np.int32)
+        self.goal_xy = np.clip(_req(goal_xy, np.int32, (N, 2)), 0, hi).astype(np.int32)
+        self.agent_dir = (_req(agent_dir, np.int8, (N,)) & 3).astype(np.int8)
+        self.dir_init = self.agent_dir.copy()
+        self.t = np.full(N, self.n_walls + 2, np.int32)
+
+    def random_levels(self, seed: int, first_id: int = 0) -> None:
+        """Replace all levels by levels first_id .. first_id+N-1 of the random generator."""
+        N, H, W = self.N, self.H, self.W
+        self.walls = np.empty((N, H, W), np.int8)
+        self.agent_xy = np.empty((N, 2), np.int32)
+        self.agent_dir = np.empty(N, np.int8)
+        self.goal_xy = np.empty((N, 2), np.int32)
+        self.t = np.empty(N, np.int32)
+        self.dir_init = np.empty(N, np.int8)
+        _load().orc_editor_random_levels(
+            N, H, W, self.n_walls, ctypes.c_uint64(seed), ctypes.c_uint64(first_id), _p(self.walls),
+            _p(self.agent_xy), _p(self.agent_dir), _p(self.goal_xy), _p(self.t), _p(self.dir_init))
+
+    def mutate(self, seed: int, first_id: int, n_edits: int) -> None:
+        """n_edits random wall flips per level (cells of the agent and the goal are skipped)."""
+        _load().orc_editor_mutate(self.N, self.H, self.W, ctypes.c_uint64(seed),
+                                  ctypes.c_uint64(first_id), int(n_edits), _p(self.walls),
+                                  _p(self.agent_xy), _p(self.goal_xy))
+
+
+def philox4x32(counter, key) -> np.ndarray:
+    """One block of the counter-based generator: 4 counter words, 2 key words -> 4 words."""
+    c = np.asarray(counter, np.uint32).copy()
+    k = np.asarray(key, np.uint32).copy()
+    out = np.empty(4, np.uint32)
+    _load().orc_philox4x32(_p(c), _p(k), _p(out))
+    return out
+
+
+def level_draw(seed: int, level_id: int, purpose: int, index: int) -> int:
+    f = _load().orc_level_draw
+    f.restype = ctypes.c_uint32
+    return int(f(ctypes.c_uint64(seed), ctypes.c_uint64(level_id), ctypes.c_uint32(purpose),
+                 ctypes.c_uint32(index)))
+
+
+def draw_below(u: int, n: int) -> int:
+    f = _load().orc_draw_below
+    f.restype = ctypes.c_uint32
+    return int(f(ctypes.c_uint32(u), ctypes.c_uint32(n)))
+
 
 def compute_gae(rewards, values, dones, gamma: float, lam: float):
     """rewards f32 [T,N], values f32 [T+1,N], dones u8 [T,N] -> (adv, returns) float64 [T,N]."""

@@ -359,3 +359,99 @@ void orc_level_metrics(int N, int H, int W, const int8_t *walls /* [N,H,W] */,
                               goal_xy[2 * n], goal_xy[2 * n + 1], s, s + H * W);
     }
 }
+
+/* ---------------------------------------------------------------------------
+ * Random levels and level mutations drawn on the device (Section 3: mazes with
+ * randomly sampled wall, goal and agent positions; Table of baselines: DR uses a
+ * random generator, ACCEL mutates levels of its buffer; hyperparameter table:
+ * number of mutations).
+ *
+ * The paper fixes neither the random number generator nor the sampling rule;
+ * the readings taken here:
+ *
+ *  - Random numbers are counter based, so a level's draws depend only on
+ *    (seed, level id, purpose, draw index), never on the batch it is part of:
+ *    Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random
+ *    numbers: as easy as 1, 2, 3", SC'11), key = seed (low, high word),
+ *    counter = (level id low, level id high, draw index / 4, purpose), and draw
+ *    `index` is output word index % 4.  purpose 0 = generation, 1 = mutation.
+ *  - A 32-bit draw u becomes an integer below n as floor(u * n / 2^32).
+ *  - A random level is what the teacher's design episode produces under
+ *    uniformly random actions: n_walls wall placements (repeats allowed), then
+ *    the agent, then the goal, each a uniformly drawn cell (draws 0 ..
+ *    n_walls+1); the agent's heading is draw n_walls+2 modulo 4.
+ *  - One mutation draws a cell uniformly; if it holds the agent or the goal
+ *    nothing happens, otherwise its wall bit is flipped.
+ * ------------------------------------------------------------------------- */
+static void mulhilo32(uint32_t a, uint32_t b, uint32_t *hi, uint32_t *lo)
+{
+    uint64_t p = (uint64_t)a * (uint64_t)b;
+    *hi = (uint32_t)(p >> 32);
+    *lo = (uint32_t)p;
+}
+
+void orc_philox4x32(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint32_t hi0, lo0, hi1, lo1;
+        mulhilo32(0xD2511F53u, c0, &hi0, &lo0);
+        mulhilo32(0xCD9E8D57u, c2, &hi1, &lo1);
+        uint32_t n0 = hi1 ^ c1 ^ k0, n1 = lo1, n2 = hi0 ^ c3 ^ k1, n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;          /* key schedule: golden-ratio and sqrt(3)-1 increments */
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+uint32_t orc_level_draw(uint64_t seed, uint64_t level_id, uint32_t purpose, uint32_t index)
+{
+    uint32_t ctr[4] = { (uint32_t)level_id, (uint32_t)(level_id >> 32), index / 4, purpose };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    orc_philox4x32(ctr, key, out);
+    return out[index % 4];
+}
+
+uint32_t orc_draw_below(uint32_t u, uint32_t n)
+{
+    return (uint32_t)(((uint64_t)u * (uint64_t)n) >> 32);
+}
+
+/* Levels first_id .. first_id+N-1 of the random generator; the arrays end up in
+ * the state of a finished design episode (t = n_walls + 2). */
+void orc_editor_random_levels(int N, int H, int W, int n_walls, uint64_t seed, uint64_t first_id,
+                              int8_t *walls, int32_t *agent_xy, int8_t *agent_dir,
+                              int32_t *goal_xy, int32_t *t, int8_t *dir_init)
+{
+    orc_editor_reset(N, H, W, walls, agent_xy, agent_dir, goal_xy, t);
+    for (int n = 0; n < N; ++n) {
+        uint64_t id = first_id + (uint64_t)n;
+        dir_init[n] = (int8_t)(orc_level_draw(seed, id, 0, (uint32_t)n_walls + 2) & 3);
+        for (int j = 0; j < n_walls + 2; ++j) {
+            int action = (int)orc_draw_below(orc_level_draw(seed, id, 0, (uint32_t)j),
+                                             (uint32_t)(H * W));
+            editor_step_one(H, W, n_walls, walls + (size_t)n * H * W, agent_xy + 2 * n,
+                            agent_dir + n, goal_xy + 2 * n, t + n, dir_init[n], action);
+        }
+    }
+}
+
+/* n_edits mutations of each level; mutation draws of level first_id+n. */
+void orc_editor_mutate(int N, int H, int W, uint64_t seed, uint64_t first_id, int n_edits,
+                       int8_t *walls, const int32_t *agent_xy, const int32_t *goal_xy)
+{
+    for (int n = 0; n < N; ++n) {
+        int8_t *w = walls + (size_t)n * H * W;
+        for (int j = 0; j < n_edits; ++j) {
+            int c = (int)orc_draw_below(orc_level_draw(seed, first_id + (uint64_t)n, 1, (uint32_t)j),
+                                        (uint32_t)(H * W));
+            int x = c % W, y = c / W;
+            if (x == agent_xy[2 * n] && y == agent_xy[2 * n + 1]) continue;
+            if (x == goal_xy[2 * n] && y == goal_xy[2 * n + 1]) continue;
+            w[c] = w[c] ? 0 : 1;
+        }
+    }
+}
