@@ -225,6 +225,11 @@ def main():
         ebytes = 516.0 * ew.N * ew.T   # 4 action + 507 obs + 4 t + 1 done
         rows["editor_c4"] = {"ms": ms, "editor-steps/s": ew.N * ew.T / ms * 1e3,
                              "GB/s": ebytes / ms / 1e6, "frac_of_hbm_peak": ebytes / ms / 1e6 / HBM_PEAK_GBS}
+        ms, mn = time_calls(torch, lambda: ed.random_levels(1, 0), 20)
+        rows["editor_random_levels_c4"] = {"ms": ms, "levels/s": ew.N / ms * 1e3,
+                                           "note": "52 placements per level from the counter-based generator"}
+        ms, mn = time_calls(torch, lambda: ed.mutate_levels(2, 0, 20), 20)
+        rows["editor_mutate_levels_c4_20edits"] = {"ms": ms, "levels/s": ew.N / ms * 1e3}
         del eobs, et, edn, ed
         # config 5: 51x51 perfect mazes, view 7
         w5 = wl.config(5)

@@ -163,6 +163,36 @@ int editor_step(editor_ctx *ctx, const int32_t *d_actions, int n_steps, int8_t *
 int editor_get_levels(editor_ctx *ctx, int8_t *d_walls, int32_t *d_agent_xy,
                       int8_t *d_agent_dir, int32_t *d_goal_xy, void *stream);
 
+/* Load finished levels into the editor env (Section 2.2: setter of the free
+ * parameters), e.g. levels of a replay buffer that are to be mutated.  Arrays as
+ * in maze_reset_to_levels; any non-zero wall byte is a wall; coordinates are
+ * clamped into the interior; the heading is taken modulo 4; everything else is
+ * copied as it is.  Afterwards the design episode counts as finished
+ * (t = n_walls + 2).                                                             */
+int editor_set_levels(editor_ctx *ctx, const int8_t *d_walls, const int32_t *d_agent_xy,
+                      const int8_t *d_agent_dir, const int32_t *d_goal_xy, void *stream);
+
+/* Random levels drawn on the device (Section 3: mazes with randomly sampled wall,
+ * goal and agent positions; the random generator of the DR and replay baselines).
+ * Env n becomes level first_level_id + n of the generator `seed`: the outcome of a
+ * design episode under uniformly random actions -- n_walls wall placements
+ * (repeats allowed), the agent, the goal -- with a uniformly random heading.  The
+ * draws come from the counter-based generator Philox-4x32-10 with key = seed and
+ * counter = (id low, id high, draw / 4, 0), draw j = word j % 4; draws 0 ..
+ * n_walls+1 are the placements, draw n_walls+2 the heading (low two bits); a draw
+ * u selects cell floor(u * H*W / 2^32).  A level depends on (seed, id, H, W,
+ * n_walls) only, not on N.  Replaces the env's whole state; no observation is
+ * written.                                                                       */
+int editor_random_levels(editor_ctx *ctx, uint64_t seed, uint64_t first_level_id, void *stream);
+
+/* Mutate the levels held by the editor env (the mutations of the ACCEL baseline,
+ * "number of mutations" in the hyperparameter tables): n_edits times, draw a cell
+ * uniformly (counter (id low, id high, draw / 4, 1) of the same generator); if it
+ * holds the agent or the goal nothing happens, otherwise its wall bit is flipped.
+ * n_edits >= 0 (MAZE_EINVAL otherwise).                                          */
+int editor_mutate_levels(editor_ctx *ctx, uint64_t seed, uint64_t first_level_id, int n_edits,
+                         void *stream);
+
 /* ----------------------------------------------------------------------- GAE
  * Generalised advantage estimation (PPO with GAE, appendix on hyperparameters;
  * gamma, lambda as in the hyperparameter table).  Per env, backwards in time:

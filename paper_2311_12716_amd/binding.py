@@ -9,7 +9,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from ctypes import (POINTER, byref, c_char_p, c_double, c_int, c_size_t, c_void_p)
+from ctypes import (POINTER, byref, c_char_p, c_double, c_int, c_size_t, c_uint64, c_void_p)
 
 import torch
 
@@ -36,6 +36,9 @@ SIGNATURES = {
     "editor_reset": (c_int, [c_void_p, c_void_p, c_void_p]),
     "editor_step": (c_int, [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_void_p]),
     "editor_get_levels": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
+    "editor_set_levels": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
+    "editor_random_levels": (c_int, [c_void_p, c_uint64, c_uint64, c_void_p]),
+    "editor_mutate_levels": (c_int, [c_void_p, c_uint64, c_uint64, c_int, c_void_p]),
     "compute_gae": (c_int, [c_void_p, c_void_p, c_void_p, c_int, c_int, c_double, c_double,
                             c_void_p, c_void_p, c_void_p]),
 }
@@ -236,6 +239,23 @@ class EditorEnv:
                                                 ad.data_ptr(), gxy.data_ptr(), _stream()),
                "editor_get_levels")
         return walls, axy, ad, gxy
+
+    def set_levels(self, walls, agent_xy, agent_dir, goal_xy):
+        N, H, W = self.N, self.H, self.W
+        _check(load_library().editor_set_levels(
+            self._h, _ptr(walls, torch.int8, (N, H, W), "walls"),
+            _ptr(agent_xy, torch.int32, (N, 2), "agent_xy"),
+            _ptr(agent_dir, torch.int8, (N,), "agent_dir"),
+            _ptr(goal_xy, torch.int32, (N, 2), "goal_xy"), _stream()), "editor_set_levels")
+
+    def random_levels(self, seed: int, first_level_id: int = 0):
+        """Replace every env by a level of the counter-based random generator."""
+        _check(load_library().editor_random_levels(self._h, int(seed), int(first_level_id), _stream()),
+               "editor_random_levels")
+
+    def mutate_levels(self, seed: int, first_level_id: int, n_edits: int):
+        _check(load_library().editor_mutate_levels(self._h, int(seed), int(first_level_id),
+                                                   int(n_edits), _stream()), "editor_mutate_levels")
 
 
 def compute_gae(rewards, values, dones, gamma: float, lam: float, adv=None, returns=None,

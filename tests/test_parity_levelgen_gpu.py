@@ -1,0 +1,98 @@
+"""GPU parity of the on-device level generator, level mutations and the editor's level
+setter against the oracle: bit-exact levels, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_12716_amd import binding, workloads as wl
+from parity_util import DEV, note, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def assert_levels_equal(ed, o, what):
+    walls, axy, adir, gxy = (x.cpu().numpy() for x in ed.get_levels())
+    lv = o.get_levels()
+    assert (walls == lv.walls).all(), f"{what}: walls differ in envs {np.flatnonzero((walls != lv.walls).any(axis=(1, 2)))[:5]}"
+    assert (axy == lv.agent_xy).all(), f"{what}: agent cells differ"
+    assert (adir == lv.agent_dir).all(), f"{what}: headings differ"
+    assert (gxy == lv.goal_xy).all(), f"{what}: goal cells differ"
+
+
+@pytest.mark.parametrize("N,H,W,nw", [(32768, 13, 13, 50), (1, 13, 13, 50), (65, 5, 8, 12), (300, 13, 13, 0),
+                                      (130, 25, 25, 120), (40, 64, 64, 500), (77, 1, 2, 3), (1000, 51, 51, 7)])
+def test_random_levels(N, H, W, nw):
+    seed, first = 0xC0FFEE0000 + N, (1 << 33) + 17
+    note(f"random levels N={N} {H}x{W} n_walls={nw}")
+    ed = binding.EditorEnv(N, H, W, nw, device=DEV)
+    ed.random_levels(seed, first)
+    torch.cuda.synchronize()
+    o = oracle.EditorOracle(N, H, W, nw)
+    o.random_levels(seed, first)
+    assert_levels_equal(ed, o, "random levels")
+    # the episode counts as finished: another placement changes nothing, t stays n_walls + 2
+    _, t, done = ed.step(torch.zeros((1, N), dtype=torch.int32, device=DEV), want_obs=False)
+    assert (t.cpu().numpy() == nw + 2).all() and (done.cpu().numpy() == 1).all()
+    assert_levels_equal(ed, o, "after an extra step")
+
+
+@pytest.mark.parametrize("N,H,W,nw,edits", [(32768, 13, 13, 50, 20), (65, 5, 8, 12, 5), (100, 13, 13, 50, 1),
+                                            (40, 64, 64, 500, 37), (513, 25, 25, 100, 10)])
+def test_mutations(N, H, W, nw, edits):
+    note(f"mutations N={N} {H}x{W} edits={edits}")
+    ed = binding.EditorEnv(N, H, W, nw, device=DEV)
+    o = oracle.EditorOracle(N, H, W, nw)
+    ed.random_levels(5, 0)
+    o.random_levels(5, 0)
+    for gen in range(3):                          # three generations of mutations, new draws each
+        ed.mutate_levels(1234, gen * N, edits)
+        o.mutate(1234, gen * N, edits)
+        assert_levels_equal(ed, o, f"generation {gen}")
+    ed.mutate_levels(1, 0, 0)
+    assert_levels_equal(ed, o, "zero edits")
+
+
+def test_set_levels_and_hand_off_to_the_student():
+    w = wl.config(2)
+    ed = binding.EditorEnv(w.N, w.H, w.W, 50, device=DEV)
+    o = oracle.EditorOracle(w.N, w.H, w.W, 50)
+    ed.set_levels(to_gpu(w.walls * 3), to_gpu(w.agent_xy), to_gpu(w.agent_dir + 4), to_gpu(w.goal_xy))
+    o.set_levels(w.walls * 3, w.agent_xy, w.agent_dir + 4, w.goal_xy)
+    assert_levels_equal(ed, o, "set levels")
+    walls, axy, adir, gxy = ed.get_levels()
+    assert (walls.cpu().numpy() == w.walls).all() and (adir.cpu().numpy() == w.agent_dir).all()
+    # the full-grid observation after loading: channels (wall, goal, agent)
+    obs, _, _ = ed.step(torch.zeros((1, w.N), dtype=torch.int32, device=DEV))
+    oobs, _, _ = o.step(np.zeros((1, w.N), np.int32), 1)
+    assert (obs.cpu().numpy() == oobs).all()
+    # mutate, then the student gets the mutated levels; metrics agree with the oracle's
+    ed.mutate_levels(9, 0, 20)
+    o.mutate(9, 0, 20)
+    assert_levels_equal(ed, o, "mutated")
+    env = binding.MazeEnv(w.N, w.H, w.W, w.view, w.max_steps, device=DEV)
+    env.reset_to_levels(*ed.get_levels())
+    nw, pl = env.level_metrics()
+    lv = o.get_levels()
+    onw, opl = oracle.level_metrics(lv.walls, lv.agent_xy, lv.goal_xy)
+    assert (nw.cpu().numpy() == onw).all() and (pl.cpu().numpy() == opl).all()
+
+
+def test_set_levels_clamps_coordinates():
+    N, H, W = 70, 6, 9
+    rng = np.random.default_rng(3)
+    walls = (rng.random((N, H, W)) < 0.3).astype(np.int8)
+    axy = rng.integers(-5, 15, (N, 2)).astype(np.int32)
+    gxy = rng.integers(-5, 15, (N, 2)).astype(np.int32)
+    adir = rng.integers(-128, 128, N).astype(np.int8)
+    ed = binding.EditorEnv(N, H, W, 4, device=DEV)
+    o = oracle.EditorOracle(N, H, W, 4)
+    ed.set_levels(to_gpu(walls), to_gpu(axy), to_gpu(adir), to_gpu(gxy))
+    o.set_levels(walls, axy, adir, gxy)
+    assert_levels_equal(ed, o, "clamped")
+
+
+def test_generator_error_paths():
+    ed = binding.EditorEnv(8, 5, 5, 3, device=DEV)
+    with pytest.raises(binding.MazeError):
+        ed.mutate_levels(1, 0, -1)
