@@ -259,3 +259,21 @@ def apsp_seidel(adj: np.ndarray) -> np.ndarray:
     X = T @ A
     deg = A.sum(axis=0)
     return 2 * T - (X < T * deg[None, :])
+
+
+def replay_scores(rewards, values, dones, adv, gamma: float, rmax=None):
+    """Per-level replay scores of a rollout -> (rmax, maxmc, pvl) float64 [N].
+
+    rewards, adv f32 [T,N]; values f32 [T+1,N]; dones u8 [T,N]; rmax f32 [N] = best
+    return seen on each level so far, or None (Appendix: MaxMC and PVL scoring).
+    """
+    rewards = _req(rewards, np.float32)
+    T, N = rewards.shape
+    values = _req(values, np.float32, (T + 1, N))
+    dones = _req(dones, np.uint8, (T, N))
+    adv = _req(adv, np.float32, (T, N))
+    rmax_in = None if rmax is None else _req(rmax, np.float32, (N,))
+    out = [np.empty(N, np.float64) for _ in range(3)]
+    _load().orc_replay_scores(T, N, ctypes.c_double(gamma), _p(rewards), _p(values), _p(dones),
+                              _p(adv), _p(rmax_in), _p(out[0]), _p(out[1]), _p(out[2]))
+    return tuple(out)

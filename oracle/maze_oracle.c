@@ -455,3 +455,46 @@ void orc_editor_mutate(int N, int H, int W, uint64_t seed, uint64_t first_id, in
         }
     }
 }
+
+/* ---------------------------------------------------------------------------
+ * Replay scores of a rollout (Appendix, hyperparameters: the PLR scoring
+ * function is MaxMC, the maximum Monte Carlo regret estimator, or PVL, the
+ * positive value loss estimator; the paper names them and cites prior work for
+ * the formulas).  Per env (= per level, an env keeps its level for the whole
+ * rollout), in double:
+ *
+ *   G_t      = r_t + gamma * (1-d_t) * G_{t+1},   G_T = V_T
+ *              (Monte Carlo return; an episode cut off by the end of the
+ *               rollout is completed with the value estimate)
+ *   R_max    = max(R_max before, max_t G_t)       (best return seen on the level)
+ *   MaxMC    = mean_t (R_max - V_t)
+ *   PVL      = mean_t max(A_t, 0)                 (A_t = the GAE advantage)
+ *
+ * Readings: the mean runs over all T steps of the rollout; R_max includes this
+ * rollout's returns before the mean is taken.
+ * ------------------------------------------------------------------------- */
+void orc_replay_scores(int T, int N, double gamma,
+                       const float *rewards /* [T,N] */, const float *values /* [T+1,N] */,
+                       const uint8_t *dones /* [T,N] */, const float *adv /* [T,N] */,
+                       const float *rmax_in /* [N] or NULL: no return seen yet */,
+                       double *rmax_out /* [N] */, double *maxmc /* [N] */, double *pvl /* [N] */)
+{
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        double G = (double)values[(size_t)T * N + n];
+        int have = rmax_in != NULL;
+        double best = have ? (double)rmax_in[n] : 0.0;
+        double sum_v = 0.0, sum_pos = 0.0;
+        for (int s = T - 1; s >= 0; --s) {
+            size_t i = (size_t)s * N + n;
+            G = (double)rewards[i] + gamma * (dones[i] ? 0.0 : 1.0) * G;
+            if (!have || G > best) { best = G; have = 1; }
+            sum_v += (double)values[i];
+            double a = (double)adv[i];
+            sum_pos += a > 0.0 ? a : 0.0;
+        }
+        rmax_out[n] = best;
+        maxmc[n] = best - sum_v / T;
+        pvl[n] = sum_pos / T;
+    }
+}
