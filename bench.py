@@ -201,6 +201,9 @@ def main():
         ms, mn = time_calls(torch, lambda: binding.compute_gae(reward, values, done, 0.995, 0.98,
                                                                adv, ret), 20)
         rows["compute_gae_T256_N32768"] = {"ms": ms, "GB/s": 17.0 * N * T / ms / 1e6}
+        ms, mn = time_calls(torch, lambda: binding.replay_scores(reward, values, done, adv, 0.995), 20)
+        rows["replay_scores_T256_N32768"] = {"ms": ms, "GB/s": 13.0 * N * T / ms / 1e6,
+                                             "note": "best return, MaxMC, PVL per level; reads 13 B per env-step"}
         del values, adv, ret
         # config 2 sized GAE
         N2, T2 = 4096, 256

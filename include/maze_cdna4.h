@@ -206,6 +206,20 @@ int compute_gae(const float *d_rewards, const float *d_values, const uint8_t *d_
                 int T, int N, double gamma, double lambda, float *d_adv, float *d_returns,
                 void *stream);
 
+/* Replay scores of a rollout, one per env = per level (Appendix, hyperparameters:
+ * the PLR scoring function is MaxMC, the maximum Monte Carlo regret estimator, or
+ * PVL, the positive value loss estimator).  Inputs as for compute_gae plus its
+ * advantages d_adv float [T,N]; evaluated in double, rounded once to float:
+ *   G_t   = r_t + gamma (1-d_t) G_{t+1},  G_T = V_T   (Monte Carlo return; an episode
+ *           cut off by the end of the rollout is completed with the value estimate)
+ *   best  = max(max_t G_t, d_rmax_in[n] if d_rmax_in is not NULL)
+ *   d_rmax_out[n] = best;  d_maxmc[n] = best - mean_t V_t;  d_pvl[n] = mean_t max(A_t, 0)
+ * Means run over all T steps.  d_rmax_in may be NULL (no return seen yet) and may
+ * alias d_rmax_out; any output may be NULL.  T, N >= 1 (MAZE_EINVAL otherwise).   */
+int replay_scores(const float *d_rewards, const float *d_values, const uint8_t *d_dones,
+                  const float *d_adv, int T, int N, double gamma, const float *d_rmax_in,
+                  float *d_rmax_out, float *d_maxmc, float *d_pvl, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -41,6 +41,8 @@ SIGNATURES = {
     "editor_mutate_levels": (c_int, [c_void_p, c_uint64, c_uint64, c_int, c_void_p]),
     "compute_gae": (c_int, [c_void_p, c_void_p, c_void_p, c_int, c_int, c_double, c_double,
                             c_void_p, c_void_p, c_void_p]),
+    "replay_scores": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_double, c_void_p,
+                              c_void_p, c_void_p, c_void_p, c_void_p]),
 }
 
 _lib = None
@@ -275,3 +277,24 @@ def compute_gae(rewards, values, dones, gamma: float, lam: float, adv=None, retu
         _ptr(adv, torch.float32, (T, N), "adv"),
         _ptr(returns, torch.float32, (T, N), "returns"), _stream()), "compute_gae")
     return adv, returns
+
+
+def replay_scores(rewards, values, dones, adv, gamma: float, rmax=None):
+    """Per-level replay scores -> (rmax, maxmc, pvl) f32 [N]; rmax (f32 [N]) is updated in place
+    when given, else a new tensor holds the rollout's best return."""
+    if rewards.dim() != 2:
+        raise MazeError("rewards must be [T, N]")
+    T, N = rewards.shape
+    dev = rewards.device
+    rmax_in = None if rmax is None else _ptr(rmax, torch.float32, (N,), "rmax")
+    if rmax is None:
+        rmax = torch.empty((N,), dtype=torch.float32, device=dev)
+    maxmc = torch.empty((N,), dtype=torch.float32, device=dev)
+    pvl = torch.empty((N,), dtype=torch.float32, device=dev)
+    _check(load_library().replay_scores(
+        _ptr(rewards, torch.float32, (T, N), "rewards"),
+        _ptr(values, torch.float32, (T + 1, N), "values"),
+        _ptr(dones, torch.uint8, (T, N), "dones"),
+        _ptr(adv, torch.float32, (T, N), "adv"), T, N, float(gamma), rmax_in,
+        rmax.data_ptr(), maxmc.data_ptr(), pvl.data_ptr(), _stream()), "replay_scores")
+    return rmax, maxmc, pvl

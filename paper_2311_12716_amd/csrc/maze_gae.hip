@@ -1,5 +1,5 @@
-// Generalised advantage estimation: reverse scan over time, parallel over envs and
-// over segments of the time axis.
+// Generalised advantage estimation and the replay scores of a rollout: reverse scans
+// over time, parallel over envs and over segments of the time axis.
 #include "maze_internal.h"
 
 namespace {
@@ -83,7 +83,95 @@ __global__ __launch_bounds__(64 * MAX_SEGS) void k_gae_scan(
     }
 }
 
+// Replay scores of a rollout, per env:  G_t = r_t + gamma (1-d_t) G_{t+1} with G_T = V_T,
+// best = max_t G_t (and the best return seen before, if given), MaxMC = best - mean_t V_t,
+// PVL = mean_t max(A_t, 0).  Same decomposition of the time axis as the advantage scan:
+// every wave scans one segment as if G were 0 after it and keeps, per step, that local
+// return and the product of the discount factors up to the segment's end; the true
+// return is local + product * (true return just after the segment).
+__global__ __launch_bounds__(64 * MAX_SEGS) void k_replay_scores(
+    const float *__restrict__ rewards, const float *__restrict__ values,
+    const uint8_t *__restrict__ dones, const float *__restrict__ adv, int T, int N, int S,
+    double gamma, const float *rmax_in, float *rmax_out, float *__restrict__ maxmc,
+    float *__restrict__ pvl)
+{
+    __shared__ double sA[MAX_SEGS][64], sP[MAX_SEGS][64], sCarry[64];
+    const int lane = threadIdx.x & 63;
+    const int j = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_raw = blockIdx.x * 64 + lane;
+    const bool live = n_raw < N;
+    const size_t n = live ? n_raw : N - 1;
+    if (j == 0) sCarry[lane] = (double)values[(size_t)T * N + n];      // G_T = V_T
+    double best = -INFINITY, sum_v = 0.0, sum_pos = 0.0;
+    for (int sb_end = T; sb_end > 0; sb_end -= S * SEG) {
+        const int seg_end = sb_end - (S - 1 - j) * SEG;
+        double a[SEG], pp[SEG];
+        double A = 0.0, P = 1.0;
+        if (seg_end > 0) {
+#pragma unroll
+            for (int u = 0; u < SEG; ++u) {
+                const int t = seg_end - 1 - u;
+                if (t >= 0) {
+                    const size_t i = (size_t)t * N + n;
+                    const double c = dones[i] ? 0.0 : gamma;
+                    A = (double)rewards[i] + c * A;
+                    P = c * P;
+                    sum_v += (double)values[i];
+                    const double ad = (double)adv[i];
+                    sum_pos += ad > 0.0 ? ad : 0.0;
+                }
+                a[u] = A;
+                pp[u] = P;
+            }
+        }
+        sA[j][lane] = A;
+        sP[j][lane] = P;
+        __syncthreads();
+        double carry = sCarry[lane];
+        for (int jj = S - 1; jj > j; --jj) carry = sA[jj][lane] + sP[jj][lane] * carry;
+        if (seg_end > 0) {
+#pragma unroll
+            for (int u = 0; u < SEG; ++u)
+                if (seg_end - 1 - u >= 0) best = fmax(best, a[u] + pp[u] * carry);
+        }
+        __syncthreads();
+        if (j == 0) sCarry[lane] = A + P * carry;
+    }
+    // combine the waves' partial results (sA, sP are free again; sCarry is read by nobody)
+    __shared__ double sV[MAX_SEGS][64];
+    sA[j][lane] = best;
+    sP[j][lane] = sum_pos;
+    sV[j][lane] = sum_v;
+    __syncthreads();
+    if (j == 0 && live) {
+        for (int jj = 1; jj < S; ++jj) {
+            best = fmax(best, sA[jj][lane]);
+            sum_pos += sP[jj][lane];
+            sum_v += sV[jj][lane];
+        }
+        if (rmax_in) best = fmax(best, (double)rmax_in[n]);
+        if (rmax_out) rmax_out[n] = (float)best;
+        if (maxmc) maxmc[n] = (float)(best - sum_v / T);
+        if (pvl) pvl[n] = (float)(sum_pos / T);
+    }
+}
+
 }  // namespace
+
+extern "C" int replay_scores(const float *d_rewards, const float *d_values, const uint8_t *d_dones,
+                             const float *d_adv, int T, int N, double gamma, const float *d_rmax_in,
+                             float *d_rmax_out, float *d_maxmc, float *d_pvl, void *stream)
+{
+    if (!d_rewards || !d_values || !d_dones || !d_adv) return MAZE_ENULL;
+    if (T < 1 || N < 1) return MAZE_EINVAL;
+    int S = (T + SEG - 1) / SEG;
+    if (S > MAX_SEGS) S = MAX_SEGS;
+    hipLaunchKernelGGL(k_replay_scores, dim3((N + 63) / 64), dim3(64 * S), 0, (hipStream_t)stream,
+                       d_rewards, d_values, d_dones, d_adv, T, N, S, gamma, d_rmax_in, d_rmax_out,
+                       d_maxmc, d_pvl);
+    MAZE_HIP_CHECK(hipGetLastError());
+    return MAZE_OK;
+}
 
 extern "C" int compute_gae(const float *d_rewards, const float *d_values, const uint8_t *d_dones,
                            int T, int N, double gamma, double lambda, float *d_adv,
