@@ -12,6 +12,7 @@ if the library is missing it is built on first use.
 from __future__ import annotations
 
 import ctypes
+import math
 import os
 import subprocess
 from dataclasses import dataclass
@@ -277,3 +278,39 @@ def replay_scores(rewards, values, dones, adv, gamma: float, rmax=None):
     _load().orc_replay_scores(T, N, ctypes.c_double(gamma), _p(rewards), _p(values), _p(dones),
                               _p(adv), _p(rmax_in), _p(out[0]), _p(out[1]), _p(out[2]))
     return tuple(out)
+
+
+def replay_distribution(scores, last_seen, now: int, rank: bool, temperature: float,
+                        staleness_coef: float) -> np.ndarray:
+    """Probability of replaying each of the K levels of a buffer -> float64 [K].
+
+    Appendix, hyperparameter tables: prioritization (rank or proportional), temperature
+    beta, staleness coefficient rho; the paper cites prior work (prioritized level replay)
+    for the formulas, which are, written out per level i:
+
+        h_i  = 1 / rank_i            (rank 1 = highest score; ties: lower index first)
+               or max(score_i, 0)    (proportional)
+        P_S  = h_i^(1/beta) / sum_j h_j^(1/beta)      (uniform if the sum is 0)
+        P_C  = (now - last_seen_i) / sum_j (now - last_seen_j)
+        P    = (1 - rho) P_S + rho P_C                (P_S alone if every level was just seen)
+
+    Double arithmetic; the ranks come from one stable sort.
+    """
+    s = np.asarray(scores, np.float32).astype(np.float64)
+    c = np.asarray(last_seen, np.int32).astype(np.int64)
+    K = s.shape[0]
+    if rank:
+        order = np.argsort(-s, kind="stable")        # highest score first, equal scores by index
+        ranks = np.empty(K, np.int64)
+        ranks[order] = np.arange(1, K + 1)
+        h = 1.0 / ranks
+    else:
+        h = np.where(s > 0.0, s, 0.0)
+    w = np.array([math.pow(x, 1.0 / temperature) for x in h])
+    tot = math.fsum(w)
+    p_s = w / tot if tot > 0.0 else np.full(K, 1.0 / K)
+    stale = (int(now) - c).astype(np.float64)
+    stot = math.fsum(stale)
+    if stot > 0.0:
+        return (1.0 - staleness_coef) * p_s + staleness_coef * (stale / stot)
+    return p_s
