@@ -204,6 +204,13 @@ def main():
         ms, mn = time_calls(torch, lambda: binding.replay_scores(reward, values, done, adv, 0.995), 20)
         rows["replay_scores_T256_N32768"] = {"ms": ms, "GB/s": 13.0 * N * T / ms / 1e6,
                                              "note": "best return, MaxMC, PVL per level; reads 13 B per env-step"}
+        # replay distribution over a buffer of the paper's size
+        Kb = 4000
+        sc = torch.rand((Kb,), device=dev)
+        seen = torch.randint(0, 1000, (Kb,), dtype=torch.int32, device=dev)
+        pb = torch.empty((Kb,), dtype=torch.float32, device=dev)
+        ms, mn = time_calls(torch, lambda: binding.replay_distribution(sc, seen, 1000, True, 0.3, 0.3, pb), 50)
+        rows["replay_distribution_K4000_rank"] = {"ms": ms, "note": "one workgroup: ranks by counting, two block sums"}
         del values, adv, ret
         # config 2 sized GAE
         N2, T2 = 4096, 256

@@ -220,6 +220,21 @@ int replay_scores(const float *d_rewards, const float *d_values, const uint8_t *
                   const float *d_adv, int T, int N, double gamma, const float *d_rmax_in,
                   float *d_rmax_out, float *d_maxmc, float *d_pvl, void *stream);
 
+/* Probability of replaying each of the K levels of a buffer (Appendix, hyperparameter
+ * tables: prioritization rank or proportional, temperature beta, staleness
+ * coefficient rho; formulas of the prioritized-level-replay work the paper cites):
+ *   h_i = 1 / rank_i (rank 1 = highest score; equal scores: lower index first), or
+ *         max(score_i, 0) if rank_prioritization == 0
+ *   P_S = h_i^(1/beta) / sum_j h_j^(1/beta)          (uniform if the sum is 0)
+ *   P_C = (now - last_seen_i) / sum_j (now - last_seen_j)
+ *   d_prob[i] = (1 - rho) P_S + rho P_C              (P_S alone if the second sum is 0)
+ * d_scores float [K], d_last_seen int32 [K] (<= now), d_prob float [K]; double
+ * arithmetic, rounded once.  1 <= K <= 12288 (MAZE_ESIZE above), beta > 0,
+ * 0 <= rho <= 1 (MAZE_EINVAL otherwise).                                           */
+int replay_distribution(const float *d_scores, const int32_t *d_last_seen, int K, int now,
+                        int rank_prioritization, double temperature, double staleness_coef,
+                        float *d_prob, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -43,6 +43,8 @@ SIGNATURES = {
                             c_void_p, c_void_p, c_void_p]),
     "replay_scores": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_double, c_void_p,
                               c_void_p, c_void_p, c_void_p, c_void_p]),
+    "replay_distribution": (c_int, [c_void_p, c_void_p, c_int, c_int, c_int, c_double, c_double, c_void_p,
+                                    c_void_p]),
 }
 
 _lib = None
@@ -298,3 +300,18 @@ def replay_scores(rewards, values, dones, adv, gamma: float, rmax=None):
         _ptr(adv, torch.float32, (T, N), "adv"), T, N, float(gamma), rmax_in,
         rmax.data_ptr(), maxmc.data_ptr(), pvl.data_ptr(), _stream()), "replay_scores")
     return rmax, maxmc, pvl
+
+
+def replay_distribution(scores, last_seen, now: int, rank: bool, temperature: float,
+                        staleness_coef: float, prob=None):
+    """scores f32 [K], last_seen i32 [K] -> replay probabilities f32 [K]."""
+    if scores.dim() != 1:
+        raise MazeError("scores must be [K]")
+    K = scores.shape[0]
+    if prob is None:
+        prob = torch.empty((K,), dtype=torch.float32, device=scores.device)
+    _check(load_library().replay_distribution(
+        _ptr(scores, torch.float32, (K,), "scores"), _ptr(last_seen, torch.int32, (K,), "last_seen"),
+        K, int(now), 1 if rank else 0, float(temperature), float(staleness_coef),
+        _ptr(prob, torch.float32, (K,), "prob"), _stream()), "replay_distribution")
+    return prob

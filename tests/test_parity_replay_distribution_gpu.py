@@ -1,0 +1,66 @@
+"""GPU parity of the replay distribution against the oracle: within 1e-6 of the largest
+probability (double arithmetic on both sides, float32 output), through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_12716_amd import binding
+from parity_util import note, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def check(s, seen, now, rank, beta, rho, what=""):
+    note(f"replay distribution {what} K={len(s)} rank={rank} beta={beta} rho={rho}")
+    p = binding.replay_distribution(to_gpu(s), to_gpu(seen), now, rank, beta, rho)
+    torch.cuda.synchronize()
+    ref = oracle.replay_distribution(s, seen, now, rank, beta, rho)
+    p = p.cpu().numpy().astype(np.float64)
+    assert np.abs(p - ref).max() <= 1e-6 * ref.max(), f"{what}: error {np.abs(p - ref).max()}"
+    assert abs(p.sum() - 1.0) < 1e-4
+
+
+@pytest.mark.parametrize("K", [1, 2, 63, 1000, 4000, 4097, 12288])
+@pytest.mark.parametrize("rank", [True, False])
+@pytest.mark.parametrize("beta,rho", [(0.3, 0.3), (0.1, 0.5), (1.0, 0.0), (0.5, 1.0)])
+def test_buffer_sizes(K, rank, beta, rho):
+    rng = np.random.default_rng(K)
+    s = (rng.random(K) * 2 - 0.2).astype(np.float32)
+    seen = rng.integers(0, 5000, K).astype(np.int32)
+    check(s, seen, 5000, rank, beta, rho, "random")
+
+
+@pytest.mark.parametrize("rank", [True, False])
+def test_ties_and_degenerate_sums(rank):
+    rng = np.random.default_rng(3)
+    K = 4000
+    s = rng.integers(0, 5, K).astype(np.float32)                     # many equal scores
+    seen = rng.integers(0, 100, K).astype(np.int32)
+    check(s, seen, 100, rank, 0.3, 0.3, "ties")
+    check(s, np.full(K, 100, np.int32), 100, rank, 0.3, 0.3, "all just seen")
+    check(np.zeros(K, np.float32), seen, 100, rank, 0.3, 0.3, "all scores zero")
+    check(-np.ones(K, np.float32), np.full(K, 7, np.int32), 7, rank, 0.3, 0.5, "nothing positive, nothing stale")
+
+
+def test_scores_from_a_rollout():
+    T, N = 64, 4000
+    rng = np.random.default_rng(5)
+    r = to_gpu(rng.random((T, N), dtype=np.float32))
+    v = to_gpu(rng.random((T + 1, N), dtype=np.float32))
+    d = to_gpu((rng.random((T, N)) < 0.03).astype(np.uint8))
+    adv, _ = binding.compute_gae(r, v, d, 0.995, 0.98)
+    _, maxmc, _ = binding.replay_scores(r, v, d, adv, 0.995)
+    seen = rng.integers(0, 300, N).astype(np.int32)
+    check(maxmc.cpu().numpy(), seen, 300, True, 0.3, 0.3, "MaxMC scores")
+
+
+def test_error_paths():
+    s = torch.zeros(8, device="cuda:0")
+    c = torch.zeros(8, dtype=torch.int32, device="cuda:0")
+    for beta, rho in ((0.0, 0.3), (-1.0, 0.3), (0.3, 1.5), (0.3, -0.1)):
+        with pytest.raises(binding.MazeError):
+            binding.replay_distribution(s, c, 0, True, beta, rho)
+    big = torch.zeros(12289, device="cuda:0")
+    with pytest.raises(binding.MazeError):
+        binding.replay_distribution(big, torch.zeros(12289, dtype=torch.int32, device="cuda:0"), 0, True, 0.3, 0.3)
