@@ -194,6 +194,20 @@ def main():
         ms, mn = time_calls(torch, lambda: env.step(a1, r1, d1, o1), 200, warmup=20)
         rows["per_step_with_obs_c3"] = {"ms": ms, "env-steps/s": N / ms * 1e3,
                                         "note": "maze_step(n=1) writing obs: one launch per step"}
+        # the same single step replayed from a captured HIP graph (what a policy loop can do)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            env.step(a1, r1, d1, o1)
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(16):
+                env.step(a1, r1, d1, o1)
+        ms, mn = time_calls(torch, graph.replay, 50, warmup=5)
+        rows["per_step_with_obs_graph16_c3"] = {"ms": ms / 16, "env-steps/s": 16 * N / ms * 1e3,
+                                                "note": "16 single steps per captured graph replay"}
+        del graph
         # GAE on this rollout's outputs
         values = torch.rand((T + 1, N), dtype=torch.float32, device=dev)
         adv = torch.empty((T, N), dtype=torch.float32, device=dev)
@@ -210,7 +224,7 @@ def main():
         seen = torch.randint(0, 1000, (Kb,), dtype=torch.int32, device=dev)
         pb = torch.empty((Kb,), dtype=torch.float32, device=dev)
         ms, mn = time_calls(torch, lambda: binding.replay_distribution(sc, seen, 1000, True, 0.3, 0.3, pb), 50)
-        rows["replay_distribution_K4000_rank"] = {"ms": ms, "note": "one workgroup: ranks by counting, two block sums"}
+        rows["replay_distribution_K4000_rank"] = {"ms": ms, "note": "one workgroup: bitonic sort in LDS, two block sums"}
         del values, adv, ret
         # config 2 sized GAE
         N2, T2 = 4096, 256

@@ -229,7 +229,7 @@ int replay_scores(const float *d_rewards, const float *d_values, const uint8_t *
  *   P_C = (now - last_seen_i) / sum_j (now - last_seen_j)
  *   d_prob[i] = (1 - rho) P_S + rho P_C              (P_S alone if the second sum is 0)
  * d_scores float [K], d_last_seen int32 [K] (<= now), d_prob float [K]; double
- * arithmetic, rounded once.  1 <= K <= 12288 (MAZE_ESIZE above), beta > 0,
+ * arithmetic, rounded once.  1 <= K <= 16384 (MAZE_ESIZE above), beta > 0,
  * 0 <= rho <= 1 (MAZE_EINVAL otherwise).                                           */
 int replay_distribution(const float *d_scores, const int32_t *d_last_seen, int K, int now,
                         int rank_prioritization, double temperature, double staleness_coef,

@@ -2,20 +2,20 @@
 // levels' scores with a temperature, mixed with a staleness term.
 //
 // The buffer is small (K = 4000 in the paper's tables), so one workgroup does the whole
-// job with the scores in LDS: a level's rank is one plus the number of levels that beat
-// it (higher score, or equal score and lower index), found by counting -- K comparisons
-// per level, spread over 1024 lanes -- and the two normalising sums are block
-// reductions in a fixed order, so the result does not depend on timing.
+// job in LDS.  Ranks come from a bitonic sort of 64-bit keys (score, descending, in the
+// high word; level index in the low word), so equal scores are ordered by index and the
+// result does not depend on timing: the level whose key ends up at position p has rank
+// p + 1.  The two normalising sums are block reductions in a fixed order.
 #include "maze_internal.h"
 
 namespace {
 
 constexpr int RD_THREADS = 1024;
-constexpr int RD_MAX_K = 12288;          // scores (4 B) + last-seen (4 B) in LDS, plus reduction space
+constexpr int RD_MAX_K = 16384;          // 8-byte keys of the padded buffer: 128 KB of LDS
 
 __device__ __forceinline__ double block_sum(double v, double *red, int tid)
 {
-    // lanes of a wave first (fixed butterfly order), then the 16 waves by thread 0
+    // lanes of a wave first (fixed butterfly order), then the 16 waves in order
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
     __syncthreads();
     if ((tid & 63) == 0) red[tid >> 6] = v;
@@ -25,53 +25,65 @@ __device__ __forceinline__ double block_sum(double v, double *red, int tid)
     return tot;
 }
 
+// Key that sorts ascending exactly when the score sorts descending (index ascending among
+// equal scores).  -0 counts as +0.
+__device__ __forceinline__ uint64_t rank_key(float score, int index)
+{
+    uint32_t u = __float_as_uint(score + 0.0f);
+    u ^= (u >> 31) ? 0xFFFFFFFFu : 0x80000000u;          // unsigned order = float order
+    return ((uint64_t)(~u) << 32) | (uint32_t)index;
+}
+
 __global__ __launch_bounds__(RD_THREADS) void k_replay_distribution(
-    const float *__restrict__ scores, const int32_t *__restrict__ last_seen, int K, int now,
+    const float *__restrict__ scores, const int32_t *__restrict__ last_seen, int K, int n2, int now,
     int use_rank, double inv_temperature, double rho, float *__restrict__ prob)
 {
-    extern __shared__ uint32_t lds[];
-    float *s = (float *)lds;                                 // [K]
-    double *red = (double *)(lds + ((K + 1) & ~1));          // [16], 8-byte aligned
+    extern __shared__ uint64_t keys[];                       // [n2] (rank mode)
+    __shared__ double red[RD_THREADS / 64];
     const int tid = threadIdx.x;
-    for (int i = tid; i < K; i += RD_THREADS) s[i] = scores[i];
-    __syncthreads();
-    constexpr int PER = (RD_MAX_K + RD_THREADS - 1) / RD_THREADS;
-    double w[PER], stale[PER];
-    double wsum = 0.0, ssum = 0.0;
-#pragma unroll
-    for (int q = 0; q < PER; ++q) {
-        const int i = tid + q * RD_THREADS;
-        w[q] = 0.0;
-        stale[q] = 0.0;
-        if (i < K) {
-            const float si = s[i];
-            double h;
-            if (use_rank) {
-                int better = 0;
-                for (int j = 0; j < K; ++j) {
-                    const float sj = s[j];
-                    better += (sj > si || (sj == si && j < i)) ? 1 : 0;
+    if (use_rank) {
+        for (int i = tid; i < n2; i += RD_THREADS) keys[i] = i < K ? rank_key(scores[i], i) : ~0ull;
+        __syncthreads();
+        for (int k = 2; k <= n2; k <<= 1) {
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                for (int t = tid; t < n2 / 2; t += RD_THREADS) {
+                    const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
+                    const uint64_t a = keys[lo], b = keys[hi];
+                    const bool ascending = (lo & k) == 0;
+                    if ((a > b) == ascending) { keys[lo] = b; keys[hi] = a; }
                 }
-                h = 1.0 / (double)(better + 1);
-            } else {
-                h = si > 0.0f ? (double)si : 0.0;
+                __syncthreads();
             }
-            w[q] = pow(h, inv_temperature);
-            stale[q] = (double)((long long)now - (long long)last_seen[i]);
-            wsum += w[q];
-            ssum += stale[q];
         }
+    }
+    // weights: by position in rank mode (position p holds the level of rank p + 1), by level
+    // otherwise; staleness by level
+    double wsum = 0.0, ssum = 0.0;
+    for (int i = tid; i < K; i += RD_THREADS) {
+        double h;
+        if (use_rank) {
+            h = 1.0 / (double)(i + 1);
+        } else {
+            const float si = scores[i];
+            h = si > 0.0f ? (double)si : 0.0;
+        }
+        wsum += pow(h, inv_temperature);
+        ssum += (double)((long long)now - (long long)last_seen[i]);
     }
     const double wtot = block_sum(wsum, red, tid);
     const double stot = block_sum(ssum, red, tid);
-#pragma unroll
-    for (int q = 0; q < PER; ++q) {
-        const int i = tid + q * RD_THREADS;
-        if (i < K) {
-            const double ps = wtot > 0.0 ? w[q] / wtot : 1.0 / (double)K;
-            const double p = stot > 0.0 ? (1.0 - rho) * ps + rho * (stale[q] / stot) : ps;
-            prob[i] = (float)p;
+    for (int p = tid; p < K; p += RD_THREADS) {
+        const int i = use_rank ? (int)(uint32_t)keys[p] : p;
+        double h;
+        if (use_rank) {
+            h = 1.0 / (double)(p + 1);
+        } else {
+            const float si = scores[i];
+            h = si > 0.0f ? (double)si : 0.0;
         }
+        const double ps = wtot > 0.0 ? pow(h, inv_temperature) / wtot : 1.0 / (double)K;
+        const double stale = (double)((long long)now - (long long)last_seen[i]);
+        prob[i] = (float)(stot > 0.0 ? (1.0 - rho) * ps + rho * (stale / stot) : ps);
     }
 }
 
@@ -85,9 +97,17 @@ extern "C" int replay_distribution(const float *d_scores, const int32_t *d_last_
     if (K < 1 || !(temperature > 0.0) || !(staleness_coef >= 0.0 && staleness_coef <= 1.0))
         return MAZE_EINVAL;
     if (K > RD_MAX_K) return MAZE_ESIZE;
-    const size_t shmem = 4 * (size_t)((K + 1) & ~1) + 8 * (RD_THREADS / 64);
+    int n2 = 2;
+    while (n2 < K) n2 <<= 1;
+    const size_t shmem = rank_prioritization ? 8 * (size_t)n2 : 0;
+    static size_t granted = 0;               // dynamic LDS above 64 KB needs an opt-in, once
+    if (shmem > 60 * 1024 && shmem > granted) {
+        MAZE_HIP_CHECK(hipFuncSetAttribute((const void *)k_replay_distribution,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem));
+        granted = shmem;
+    }
     hipLaunchKernelGGL(k_replay_distribution, dim3(1), dim3(RD_THREADS), shmem, (hipStream_t)stream,
-                       d_scores, d_last_seen, K, now, rank_prioritization ? 1 : 0, 1.0 / temperature,
+                       d_scores, d_last_seen, K, n2, now, rank_prioritization ? 1 : 0, 1.0 / temperature,
                        staleness_coef, d_prob);
     MAZE_HIP_CHECK(hipGetLastError());
     return MAZE_OK;

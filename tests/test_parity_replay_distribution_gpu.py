@@ -21,7 +21,7 @@ def check(s, seen, now, rank, beta, rho, what=""):
     assert abs(p.sum() - 1.0) < 1e-4
 
 
-@pytest.mark.parametrize("K", [1, 2, 63, 1000, 4000, 4097, 12288])
+@pytest.mark.parametrize("K", [1, 2, 63, 1000, 4000, 4097, 8192, 12288, 16384])
 @pytest.mark.parametrize("rank", [True, False])
 @pytest.mark.parametrize("beta,rho", [(0.3, 0.3), (0.1, 0.5), (1.0, 0.0), (0.5, 1.0)])
 def test_buffer_sizes(K, rank, beta, rho):
@@ -61,6 +61,6 @@ def test_error_paths():
     for beta, rho in ((0.0, 0.3), (-1.0, 0.3), (0.3, 1.5), (0.3, -0.1)):
         with pytest.raises(binding.MazeError):
             binding.replay_distribution(s, c, 0, True, beta, rho)
-    big = torch.zeros(12289, device="cuda:0")
+    big = torch.zeros(16385, device="cuda:0")
     with pytest.raises(binding.MazeError):
-        binding.replay_distribution(big, torch.zeros(12289, dtype=torch.int32, device="cuda:0"), 0, True, 0.3, 0.3)
+        binding.replay_distribution(big, torch.zeros(16385, dtype=torch.int32, device="cuda:0"), 0, True, 0.3, 0.3)
