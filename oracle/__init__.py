@@ -81,6 +81,14 @@ class MazeOracle:
             raise ValueError("view must be odd")
         self.N, self.H, self.W, self.view, self.max_steps = N, H, W, view, max_steps
         self.levels: Levels | None = None
+        self.encoding, self.occlusion = 0, 0
+
+    def set_obs_mode(self, encoding: int, occlusion: int) -> None:
+        """encoding 0 = one-hot (wall, goal, empty), 1 = (type, colour, state); occlusion
+        0 = the whole window, 1 = cells behind walls are unseen (Section 3, MiniGrid-based)."""
+        if self.view > 31:
+            raise ValueError("view too large for the variants")
+        self.encoding, self.occlusion = int(encoding), int(occlusion)
 
     def reset_to_levels(self, walls, agent_xy, agent_dir, goal_xy) -> None:
         N, H, W = self.N, self.H, self.W
@@ -95,8 +103,13 @@ class MazeOracle:
     def render_obs(self) -> np.ndarray:
         L, k = self.levels, self.view
         obs = np.empty((self.N, k, k, 3), np.int8)
-        _load().orc_maze_render(self.N, self.H, self.W, k, _p(L.walls), _p(L.goal_xy),
-                                _p(self.xy), _p(self.dir), _p(obs))
+        if self.encoding or self.occlusion:
+            _load().orc_maze_render_variant(self.N, self.H, self.W, k, self.encoding, self.occlusion,
+                                            _p(L.walls), _p(L.goal_xy), _p(self.xy), _p(self.dir),
+                                            _p(obs))
+        else:
+            _load().orc_maze_render(self.N, self.H, self.W, k, _p(L.walls), _p(L.goal_xy),
+                                    _p(self.xy), _p(self.dir), _p(obs))
         return obs
 
     def step(self, actions, n_steps: int = 1, want_obs: bool = True):
@@ -106,10 +119,20 @@ class MazeOracle:
         reward = np.empty((n_steps, N), np.float32)
         done = np.empty((n_steps, N), np.uint8)
         obs = np.empty((n_steps, N, k, k, 3), np.int8) if want_obs else None
-        _load().orc_maze_rollout(N, self.H, self.W, k, self.max_steps, n_steps,
-                                 _p(L.walls), _p(L.agent_xy), _p(L.agent_dir), _p(L.goal_xy),
-                                 _p(self.xy), _p(self.dir), _p(self.t),
-                                 _p(actions), _p(reward), _p(done), _p(obs))
+
+        def rollout(first, count, obs_out):
+            _load().orc_maze_rollout(N, self.H, self.W, k, self.max_steps, count,
+                                     _p(L.walls), _p(L.agent_xy), _p(L.agent_dir), _p(L.goal_xy),
+                                     _p(self.xy), _p(self.dir), _p(self.t),
+                                     _p(actions[first:first + count]), _p(reward[first:first + count]),
+                                     _p(done[first:first + count]), _p(obs_out))
+
+        if want_obs and (self.encoding or self.occlusion):
+            for s in range(n_steps):              # step, then observe in the chosen variant
+                rollout(s, 1, None)
+                obs[s] = self.render_obs()
+        else:
+            rollout(0, n_steps, obs)
         return reward, done, obs
 
     def get_state(self):

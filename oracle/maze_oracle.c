@@ -187,6 +187,96 @@ void orc_maze_rollout(int N, int H, int W, int k, int max_steps, int n_steps,
 }
 
 /* ---------------------------------------------------------------------------
+ * Observation variants (Section 3: the maze reproduces the MiniGrid mazes of
+ * prior work; MiniGrid's own observation hides what lies behind walls and
+ * describes a cell by (object type, colour, state)).
+ *
+ * occlusion = 1: a cell of the k x k view is seen if the agent's own cell is
+ * connected to it by a chain of seen cells that are not walls, where a seen
+ * non-wall cell passes sight on to its left and right neighbours in its view
+ * row and to the three cells of the next row ahead that touch it.  (Walls are
+ * seen but pass nothing on; a single pillar therefore hides nothing, a closed
+ * wall hides everything behind it.)  Rows are settled from the agent's row
+ * outwards.  An unseen cell has all three channels zero.
+ *
+ * encoding = 1: channels are (type, colour, state) with MiniGrid's published
+ * indices: unseen (0,0,0), empty (1,0,0), wall (2,5,0) -- grey --, goal
+ * (8,1,0) -- green.  encoding = 0: the one-hot (wall, goal, empty) channels.
+ * ------------------------------------------------------------------------- */
+enum { MAX_VIEW = 31 };
+
+static void view_cells(int H, int W, int k, const int8_t *walls, int gx, int gy,
+                       int x, int y, int dir, int cell[MAX_VIEW][MAX_VIEW])
+{
+    int rdir = (dir + 1) % 4;
+    for (int r = 0; r < k; ++r) {
+        for (int c = 0; c < k; ++c) {
+            int ahead = (k - 1) - r, side = c - k / 2;
+            int wx = x + ahead * DX[dir] + side * DX[rdir];
+            int wy = y + ahead * DY[dir] + side * DY[rdir];
+            if (is_wall(walls, H, W, wx, wy)) cell[r][c] = CELL_WALL;
+            else if (wx == gx && wy == gy) cell[r][c] = CELL_GOAL;
+            else cell[r][c] = CELL_EMPTY;
+        }
+    }
+}
+
+static void view_visibility(int k, int cell[MAX_VIEW][MAX_VIEW], int seen[MAX_VIEW][MAX_VIEW])
+{
+    for (int r = 0; r < k; ++r)
+        for (int c = 0; c < k; ++c) seen[r][c] = 0;
+    seen[k - 1][k / 2] = 1;                       /* the agent's own cell */
+    for (int r = k - 1; r >= 0; --r) {
+        /* the agent's cell passes sight on whatever it holds */
+        int changed = 1;
+        while (changed) {                         /* sideways, until the row is settled */
+            changed = 0;
+            for (int c = 0; c < k; ++c) {
+                int open = cell[r][c] != CELL_WALL || (r == k - 1 && c == k / 2);
+                if (!seen[r][c] || !open) continue;
+                if (c > 0 && !seen[r][c - 1]) { seen[r][c - 1] = 1; changed = 1; }
+                if (c + 1 < k && !seen[r][c + 1]) { seen[r][c + 1] = 1; changed = 1; }
+            }
+        }
+        if (r == 0) break;
+        for (int c = 0; c < k; ++c) {             /* on to the next row ahead */
+            int open = cell[r][c] != CELL_WALL || (r == k - 1 && c == k / 2);
+            if (!seen[r][c] || !open) continue;
+            for (int cc = c - 1; cc <= c + 1; ++cc)
+                if (cc >= 0 && cc < k) seen[r - 1][cc] = 1;
+        }
+    }
+}
+
+void orc_maze_render_variant(int N, int H, int W, int k, int encoding, int occlusion,
+                             const int8_t *walls, const int32_t *goal_xy,
+                             const int32_t *xy, const int8_t *dir, int8_t *obs /* [N,k,k,3] */)
+{
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        int cell[MAX_VIEW][MAX_VIEW], seen[MAX_VIEW][MAX_VIEW];
+        view_cells(H, W, k, walls + (size_t)n * H * W, goal_xy[2 * n], goal_xy[2 * n + 1],
+                   xy[2 * n], xy[2 * n + 1], dir[n], cell);
+        if (occlusion) view_visibility(k, cell, seen);
+        for (int r = 0; r < k; ++r) {
+            for (int c = 0; c < k; ++c) {
+                int8_t *o = obs + (((size_t)n * k + r) * k + c) * 3;
+                int vis = !occlusion || seen[r][c];
+                int kind = cell[r][c];
+                if (encoding == 0) {
+                    o[0] = vis && kind == CELL_WALL;
+                    o[1] = vis && kind == CELL_GOAL;
+                    o[2] = vis && kind == CELL_EMPTY;
+                } else {
+                    static const int8_t code[3][3] = { { 2, 5, 0 }, { 8, 1, 0 }, { 1, 0, 0 } };
+                    for (int ch = 0; ch < 3; ++ch) o[ch] = vis ? code[kind][ch] : 0;
+                }
+            }
+        }
+    }
+}
+
+/* ---------------------------------------------------------------------------
  * Teacher's design MDP (Section 2.2: the teacher's decision process is its own
  * environment whose final instance becomes the student's level).
  *
