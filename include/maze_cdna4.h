@@ -125,6 +125,21 @@ int maze_level_metrics(maze_ctx *ctx, int32_t *d_n_walls, int32_t *d_path_len, v
  * tests and measurements.                                                     */
 int maze_set_kernel_variant(maze_ctx *ctx, int variant);
 
+/* Observation variants (Section 3: the maze reproduces the MiniGrid mazes of prior
+ * work, whose observation hides what lies behind walls and describes a cell by
+ * object type, colour and state), for maze_step and maze_render_obs from the next
+ * call on.  Shape and index order of d_obs do not change.
+ *   encoding  0 (default): one-hot (wall, goal, empty)
+ *             1: (type, colour, state) with MiniGrid's indices: empty (1,0,0),
+ *                wall (2,5,0), goal (8,1,0), unseen (0,0,0)
+ *   occlusion 0 (default): every cell of the window is shown
+ *             1: a cell is seen if a chain of seen non-wall cells leads to it from
+ *                the agent's cell, each link going sideways within a view row or to
+ *                one of the three touching cells of the next row ahead; seen walls
+ *                pass nothing on; an unseen cell reads zero in all channels.
+ * Any non-default mode runs in the per-cell kernels.  MAZE_EINVAL for other values. */
+int maze_set_obs_mode(maze_ctx *ctx, int encoding, int occlusion);
+
 /* ------------------------------------------------------------------- teacher
  * The teacher's design MDP (Section 2.2): an empty H x W grid on which the
  * teacher places n_walls walls, then the agent, then the goal, one cell index

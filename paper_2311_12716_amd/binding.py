@@ -30,6 +30,7 @@ SIGNATURES = {
     "maze_get_levels": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_level_metrics": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_set_kernel_variant": (c_int, [c_void_p, c_int]),
+    "maze_set_obs_mode": (c_int, [c_void_p, c_int, c_int]),
     "editor_workspace_bytes": (c_int, [c_int, c_int, c_int, POINTER(c_size_t)]),
     "editor_create": (c_int, [POINTER(c_void_p), c_int, c_int, c_int, c_int, c_void_p, c_size_t]),
     "editor_destroy": (c_int, [c_void_p]),
@@ -119,6 +120,11 @@ class MazeEnv:
 
     def set_kernel_variant(self, variant: int):
         _check(load_library().maze_set_kernel_variant(self._h, variant), "maze_set_kernel_variant")
+
+    def set_obs_mode(self, encoding: int, occlusion: int):
+        """encoding 0 one-hot / 1 (type, colour, state); occlusion 0 off / 1 on."""
+        _check(load_library().maze_set_obs_mode(self._h, int(encoding), int(occlusion)),
+               "maze_set_obs_mode")
 
     def reset_to_levels(self, walls, agent_xy, agent_dir, goal_xy):
         N, H, W = self.N, self.H, self.W

@@ -41,6 +41,8 @@ struct StudentDev {
     uint32_t *goalrot;      // [N][4] goal position Xd | Yd << 8 in each frame
     void *grids;            // [N][4][SP] words (uint32_t or uint64_t)
     double reward_slope;    // 0.9 / max_steps
+    int obs_encoding;       // 0 one-hot (wall, goal, empty), 1 (type, colour, state)
+    int obs_occlusion;      // 0 whole window, 1 cells behind walls are unseen
 };
 
 struct maze_ctx {

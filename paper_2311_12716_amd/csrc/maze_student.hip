@@ -72,6 +72,8 @@ extern "C" int maze_create(maze_ctx **out, int N, int H, int W, int view, int ma
     c->dev = d;
     c->word64 = w64;
     c->variant = 0;
+    c->dev.obs_encoding = 0;
+    c->dev.obs_occlusion = 0;
     c->workspace_bytes = workspace_bytes;
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return MAZE_EHIP; }
     *out = c;
@@ -90,6 +92,15 @@ extern "C" int maze_set_kernel_variant(maze_ctx *ctx, int variant)
     if (!ctx) return MAZE_ENULL;
     if (variant < 0 || variant > 1) return MAZE_EINVAL;
     ctx->variant = variant;
+    return MAZE_OK;
+}
+
+extern "C" int maze_set_obs_mode(maze_ctx *ctx, int encoding, int occlusion)
+{
+    if (!ctx) return MAZE_ENULL;
+    if (encoding < 0 || encoding > 1 || occlusion < 0 || occlusion > 1) return MAZE_EINVAL;
+    ctx->dev.obs_encoding = encoding;
+    ctx->dev.obs_occlusion = occlusion;
     return MAZE_OK;
 }
 
@@ -209,16 +220,57 @@ __device__ __forceinline__ void render_cells(const StudentDev &p, const Word *__
     int xd = pose & 255, yd = (pose >> 8) & 255, d = (pose >> 16) & 3;
     int gxd = goal & 255, gyd = (goal >> 8) & 255;
     const Word *g = grid_n + d * p.SP;
-    for (int r = 0; r < k; ++r) {
-        int row = yd - (k - 1) + r;
-        Word w = g[row] >> (xd - h);
+    if (!p.obs_encoding && !p.obs_occlusion) {
+        for (int r = 0; r < k; ++r) {
+            int row = yd - (k - 1) + r;
+            Word w = g[row] >> (xd - h);
+            for (int c = 0; c < k; ++c) {
+                int wall = (int)((w >> c) & 1);
+                int isgoal = (!wall) && (row == gyd) && (xd - h + c == gxd);
+                o[0] = (int8_t)wall;
+                o[1] = (int8_t)isgoal;
+                o[2] = (int8_t)(!wall && !isgoal);
+                o += 3;
+            }
+        }
+        return;
+    }
+    // Variants.  Occlusion: view rows are settled from the agent's row outwards, each as a bit
+    // mask: the cells seen so far spread sideways through cells that are not walls (a seen wall
+    // spreads nothing), then every seen non-wall cell makes the three cells touching it in the
+    // next row ahead seen.  The agent's own cell spreads whatever it holds.
+    const uint32_t all = (1u << k) - 1;
+    uint32_t from_below = 1u << h;
+    for (int r = k - 1; r >= 0; --r) {
+        const int row = yd - (k - 1) + r;
+        const uint32_t wall = (uint32_t)(g[row] >> (xd - h)) & all;
+        uint32_t open = ~wall & all;
+        if (r == k - 1) open |= 1u << h;
+        uint32_t seen = all;
+        if (p.obs_occlusion) {
+            seen = from_below;
+            for (int it = 1; it < k; ++it) {
+                const uint32_t src = seen & open;
+                seen |= ((src << 1) | (src >> 1)) & all;
+            }
+            const uint32_t src = seen & open;
+            from_below = (src | (src << 1) | (src >> 1)) & all;
+        }
+        int8_t *q = o + (size_t)r * k * 3;
         for (int c = 0; c < k; ++c) {
-            int wall = (int)((w >> c) & 1);
-            int isgoal = (!wall) && (row == gyd) && (xd - h + c == gxd);
-            o[0] = (int8_t)wall;
-            o[1] = (int8_t)isgoal;
-            o[2] = (int8_t)(!wall && !isgoal);
-            o += 3;
+            const int vis = (seen >> c) & 1, is_wall = (wall >> c) & 1;
+            const int is_goal = !is_wall && row == gyd && xd - h + c == gxd;
+            if (p.obs_encoding == 0) {
+                q[0] = (int8_t)(vis & is_wall);
+                q[1] = (int8_t)(vis & is_goal);
+                q[2] = (int8_t)(vis & !is_wall & !is_goal);
+            } else {
+                // MiniGrid's indices: wall (2, grey 5), goal (8, green 1), empty (1, 0); unseen 0
+                q[0] = (int8_t)(vis ? (is_wall ? 2 : (is_goal ? 8 : 1)) : 0);
+                q[1] = (int8_t)(vis ? (is_wall ? 5 : (is_goal ? 1 : 0)) : 0);
+                q[2] = 0;
+            }
+            q += 3;
         }
     }
 }

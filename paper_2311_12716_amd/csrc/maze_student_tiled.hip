@@ -719,6 +719,7 @@ int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_ste
     const StudentDev &p = ctx->dev;
     *covered = 0;
     if (!d_obs) return 0;
+    if (p.obs_encoding || p.obs_occlusion) return 0;     // the variants run in the per-cell kernels
     const int K = p.k;
     if (K != 3 && K != 5 && K != 7) return 0;
     // 16-byte accesses: every time step's obs block, the obs buffer and each step's row of

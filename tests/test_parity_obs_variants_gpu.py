@@ -1,0 +1,77 @@
+"""GPU parity of the observation variants (occluded view, type/colour/state encoding)
+against the oracle, byte for byte, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_12716_amd import binding, workloads as wl
+from parity_util import (DEV, assert_rollout_equal, assert_state_equal, cpu_student, gpu_student, note,
+                         to_gpu)
+
+pytestmark = pytest.mark.gpu
+MODES = [(0, 1), (1, 0), (1, 1)]
+
+
+def run_variant(w, encoding, occlusion):
+    note(f"obs variant enc={encoding} occ={occlusion} {w.name}: N={w.N} {w.H}x{w.W} k={w.view}")
+    env, o = gpu_student(w), cpu_student(w)
+    env.set_obs_mode(encoding, occlusion)
+    o.set_obs_mode(encoding, occlusion)
+    assert (env.render_obs().cpu().numpy() == o.render_obs()).all(), "initial observation differs"
+    out = env.step(to_gpu(w.actions))
+    torch.cuda.synchronize()
+    ref = o.step(w.actions, w.T)
+    assert_rollout_equal(out, ref, w.name)
+    assert_state_equal(env, o)
+    return env, o
+
+
+@pytest.mark.parametrize("encoding,occlusion", MODES)
+def test_config_2_full_size(encoding, occlusion):
+    run_variant(wl.config(2, T=64), encoding, occlusion)
+
+
+@pytest.mark.parametrize("encoding,occlusion", MODES)
+def test_config_3_sampled_steps(encoding, occlusion):
+    # full batch of config 3, a short rollout: the oracle renders every step
+    run_variant(wl.config(3, T=6), encoding, occlusion)
+
+
+@pytest.mark.parametrize("encoding,occlusion", MODES)
+def test_perfect_mazes_view_7(encoding, occlusion):
+    run_variant(wl.config(5, N=512, T=40), encoding, occlusion)
+
+
+@pytest.mark.parametrize("H,W,k,nw", [(13, 13, 3, 30), (7, 19, 5, 40), (20, 9, 7, 50), (30, 30, 9, 200),
+                                      (1, 6, 3, 2), (40, 12, 5, 100)])
+def test_other_shapes(H, W, k, nw):
+    w = wl.student_random(f"variant-{H}x{W}-k{k}", 3 * H + W + k, N=257, H=H, W=W, view=k, T=30,
+                          n_walls=nw, max_steps=12)
+    for enc, occ in MODES:
+        run_variant(w, enc, occ)
+
+
+def test_levels_outside_the_preconditions():
+    w = wl.student_random("variant-odd", 97, N=384, H=13, W=13, view=5, T=40, n_walls=55, max_steps=20)
+    n = np.arange(w.N)
+    third = w.N // 3
+    w.walls[n[:third], w.goal_xy[:third, 1], w.goal_xy[:third, 0]] = 1
+    w.walls[n[third:2 * third], w.agent_xy[third:2 * third, 1], w.agent_xy[third:2 * third, 0]] = 1
+    w.goal_xy[2 * third:] = w.agent_xy[2 * third:]
+    for enc, occ in MODES:
+        run_variant(w, enc, occ)
+
+
+def test_switching_back_restores_the_default():
+    w = wl.config(2, T=16)
+    env, o = run_variant(w, 1, 1)
+    env.set_obs_mode(0, 0)
+    o.set_obs_mode(0, 0)
+    assert (env.render_obs().cpu().numpy() == o.render_obs()).all()
+    out = env.step(to_gpu(w.actions))
+    assert_rollout_equal(out, o.step(w.actions, w.T), "default again")
+    with pytest.raises(binding.MazeError):
+        env.set_obs_mode(2, 0)
+    with pytest.raises(binding.MazeError):
+        env.set_obs_mode(0, -1)
