@@ -179,6 +179,26 @@ def test_workgroup_size_choices(N):
     run_fused(w)
 
 
+@pytest.mark.parametrize("T", [2, 3, 7, 8, 9, 15, 16, 17, 23, 24, 25, 31, 32, 33, 47, 48, 49, 63, 64, 65, 97])
+def test_rollout_lengths_around_block_boundaries(T):
+    """Rollout lengths just below, at and above multiples of the kernel's step blocks and action
+    staging blocks, in a small batch (32 envs per workgroup) and one with 64 per workgroup."""
+    for N, k, S in ((96, 5, 13), (16384, 3, 9)):
+        w = wl.student_random(f"T{T}-N{N}", 7000 + T + N, N=N, H=S, W=S, view=k, T=T, n_walls=S * S // 4,
+                              max_steps=11)
+        note(w.name)
+        env, o = gpu_student(w), cpu_student(w)
+        half = T // 2
+        acts = to_gpu(w.actions)
+        out1 = env.step(acts[:half].contiguous()) if half else None
+        out2 = env.step(acts[half:].contiguous())
+        ref = o.step(w.actions, T)
+        if half:
+            assert_rollout_equal(out1, tuple(x[:half] if x is not None else None for x in ref), w.name)
+        assert_rollout_equal(out2, tuple(x[half:] if x is not None else None for x in ref), w.name)
+        assert_state_equal(env, o)
+
+
 def test_unaligned_buffers_take_the_per_cell_path():
     """Views into larger tensors whose addresses are not 16-byte aligned still give exact results."""
     w = wl.student_random("unaligned", 66, N=640, T=40, n_walls=50, max_steps=30)
