@@ -3,14 +3,15 @@
 // A workgroup owns EPW consecutive envs for the whole rollout: 128 when the batch is
 // large enough to fill the GPU that way (128 * 3k^2 bytes per step is a whole number
 // of 128-byte lines, so no line of the output is shared between workgroups), 64 or
-// 32 for smaller batches or grids whose LDS copy would not fit.  Per step one lane per env advances the env (state in
-// registers, wall rows from LDS) and its observation is built as a BIT STREAM --
-// bit i of the stream is byte i of the env's k*k*3 observation, which is 0 or 1 --
-// and left in LDS.  The EPW streams, concatenated, are exactly the EPW*3k^2
-// contiguous output bytes of this time step, so other lanes then take 16 consecutive stream bits each (they may
-// straddle two envs), expand each bit to a byte and write 16 contiguous bytes;
-// consecutive lanes take consecutive pieces, so one store instruction of a wave
-// writes 1 KB of contiguous, aligned output.
+// 32 for smaller batches or grids whose LDS copy would not fit.  Per step one lane
+// per env advances the env (state in registers, wall rows from LDS) and its
+// observation is built as a BIT STREAM -- bit i of the stream is byte i of the env's
+// k*k*3 observation, which is 0 or 1 -- and left in LDS.  The EPW streams,
+// concatenated, are exactly the EPW*3k^2 contiguous output bytes of this time step,
+// so other lanes then take 16 consecutive stream bits each (they may straddle two
+// envs), expand each bit to a byte and write 16 contiguous bytes; consecutive lanes
+// take consecutive pieces, so one store instruction of a wave writes 1 KB of
+// contiguous, aligned output.
 //
 // The per-step work is a four-stage pipeline over the waves of the workgroup,
 // advanced by one barrier per block of SPB steps:
