@@ -215,6 +215,21 @@ def main():
         rows["per_step_with_obs_graph16_c3"] = {"ms": ms / 16, "env-steps/s": 16 * N / ms * 1e3,
                                                 "note": "16 single steps per captured graph replay"}
         del graph
+        # closed-loop stepping at the batch sizes of the paper's speed table (Section 3, steps
+        # per second at 1 / 32 / 256 / 1024 parallel envs): one maze_step(n=1) with obs per step
+        small = {}
+        for Ns in (1, 32, 256, 1024):
+            ws = wl.student_random(f"table-{Ns}", 900 + Ns, N=Ns, T=4, n_walls=50)
+            es = binding.MazeEnv(Ns, ws.H, ws.W, ws.view, ws.max_steps, device=dev)
+            es.reset_to_levels(g(ws.walls), g(ws.agent_xy), g(ws.agent_dir), g(ws.goal_xy))
+            a_s = g(ws.actions[:1])
+            r_s = torch.empty((1, Ns), dtype=torch.float32, device=dev)
+            d_s = torch.empty((1, Ns), dtype=torch.uint8, device=dev)
+            o_s = torch.empty((1, Ns, 5, 5, 3), dtype=torch.int8, device=dev)
+            ms, mn = time_calls(torch, lambda: es.step(a_s, r_s, d_s, o_s), 200, warmup=20)
+            small[str(Ns)] = {"ms": ms, "env-steps/s": Ns / ms * 1e3}
+            del es
+        rows["closed_loop_single_steps_by_batch"] = small
         # GAE on this rollout's outputs
         values = torch.rand((T + 1, N), dtype=torch.float32, device=dev)
         adv = torch.empty((T, N), dtype=torch.float32, device=dev)
