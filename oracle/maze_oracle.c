@@ -20,7 +20,12 @@
  * Parity pins (tests/, "not gpu"): BFS shortest paths on hand-built mazes,
  * scripted levels with known step counts and rewards, rotation / turn
  * invariants, hand-derived observation crops, GAE closed forms, editor
- * scripted cases.
+ * scripted cases; level metrics against closed forms, scipy's graph routines
+ * and the matrix all-pairs recursion; the random generator against its
+ * published known-answer vectors, generated and mutated levels by invariants
+ * and statistics; replay scores by closed forms and against GAE at lambda = 1;
+ * observation variants by hand-derived visibility masks and graph
+ * reachability.  No function here is without a pin.
  */
 #include <stdint.h>
 #include <stddef.h>
