@@ -199,6 +199,21 @@ def test_rollout_lengths_around_block_boundaries(T):
         assert_state_equal(env, o)
 
 
+def test_outputs_larger_than_4_gib():
+    """262144 envs x 256 steps: 5.0e9 obs bytes, so every offset needs 64 bits (eight times config 3)."""
+    w = wl.student_random("big", 31337, N=262144, T=256, n_walls=50)
+    note(w.name)
+    env, o = gpu_student(w), cpu_student(w)
+    r, d, obs = env.step(to_gpu(w.actions))
+    torch.cuda.synchronize()
+    orr, od, oobs = o.step(w.actions, w.T)
+    assert (d.cpu().numpy() == od).all()
+    assert np.abs(r.cpu().numpy().astype(np.float64) - orr).max() <= TOL
+    for t0 in range(0, w.T, 32):                       # compare in slabs to bound host memory
+        assert (obs[t0:t0 + 32].cpu().numpy() == oobs[t0:t0 + 32]).all(), f"obs differ in steps {t0}.."
+    assert_state_equal(env, o)
+
+
 def test_unaligned_buffers_take_the_per_cell_path():
     """Views into larger tensors whose addresses are not 16-byte aligned still give exact results."""
     w = wl.student_random("unaligned", 66, N=640, T=40, n_walls=50, max_steps=30)
