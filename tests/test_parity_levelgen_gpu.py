@@ -78,6 +78,49 @@ def test_set_levels_and_hand_off_to_the_student():
     assert (nw.cpu().numpy() == onw).all() and (pl.cpu().numpy() == opl).all()
 
 
+def test_double_and_triple_batches_are_slices_of_one_student_batch():
+    """The parallel replay variants of Section 4 step new, replayed and mutated levels in one env
+    batch of 2N or 3N: each part's levels are written into its slice of the level arrays."""
+    N, H, W, nw = 2048, 13, 13, 50
+    dev = DEV
+    walls = torch.empty((3 * N, H, W), dtype=torch.int8, device=dev)
+    axy = torch.empty((3 * N, 2), dtype=torch.int32, device=dev)
+    adir = torch.empty((3 * N,), dtype=torch.int8, device=dev)
+    gxy = torch.empty((3 * N, 2), dtype=torch.int32, device=dev)
+    lib = binding.load_library()
+    ed = binding.EditorEnv(N, H, W, nw, device=dev)
+    o = oracle.EditorOracle(N, H, W, nw)
+    parts = []
+
+    def take(part):
+        sl = slice(part * N, (part + 1) * N)
+        rc = lib.editor_get_levels(ed._h, walls[sl].data_ptr(), axy[sl].data_ptr(), adir[sl].data_ptr(),
+                                   gxy[sl].data_ptr(), torch.cuda.current_stream().cuda_stream)
+        assert rc == 0
+        parts.append(o.get_levels())
+
+    ed.random_levels(11, 0); o.random_levels(11, 0); take(0)               # new levels
+    ed.random_levels(11, 5000); o.random_levels(11, 5000); take(1)         # stands in for replayed ones
+    ed.mutate_levels(12, 5000, 20); o.mutate(12, 5000, 20); take(2)        # their mutations
+    torch.cuda.synchronize()
+    ref_walls = np.concatenate([p.walls for p in parts])
+    ref_axy = np.concatenate([p.agent_xy for p in parts])
+    ref_adir = np.concatenate([p.agent_dir for p in parts])
+    ref_gxy = np.concatenate([p.goal_xy for p in parts])
+    assert (walls.cpu().numpy() == ref_walls).all() and (axy.cpu().numpy() == ref_axy).all()
+    assert (adir.cpu().numpy() == ref_adir).all() and (gxy.cpu().numpy() == ref_gxy).all()
+    T = 24
+    actions = np.random.default_rng(4).integers(0, 3, size=(T, 3 * N), dtype=np.int8)
+    env = binding.MazeEnv(3 * N, H, W, 5, 250, device=dev)
+    env.reset_to_levels(walls, axy, adir, gxy)
+    r, d, obs = env.step(to_gpu(actions))
+    om = oracle.MazeOracle(3 * N, H, W, 5, 250)
+    om.reset_to_levels(ref_walls, ref_axy, ref_adir, ref_gxy)
+    orr, od, oobs = om.step(actions, T)
+    assert (obs.cpu().numpy() == oobs).all() and (d.cpu().numpy() == od).all()
+    assert np.abs(r.cpu().numpy().astype(np.float64) - orr).max() <= 1e-6
+
+
 def test_set_levels_clamps_coordinates():
     N, H, W = 70, 6, 9
     rng = np.random.default_rng(3)
