@@ -405,8 +405,8 @@ __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word>
 
 template <int K, typename Word, int EPW, bool GRID_LDS, bool SQUARE>
 __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
-    StudentDev p, const int8_t *__restrict__ actions, int n_steps, float *__restrict__ reward,
-    uint8_t *__restrict__ done, int8_t *__restrict__ obs)
+    StudentDev p, int n_begin, const int8_t *__restrict__ actions, int n_steps,
+    float *__restrict__ reward, uint8_t *__restrict__ done, int8_t *__restrict__ obs)
 {
     using V = View<K, EPW>;
     using L = Lds<K, Word, EPW>;
@@ -417,7 +417,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     extern __shared__ uint32_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int env0 = blockIdx.x * EPW;
+    const int env0 = n_begin + blockIdx.x * EPW;     // n_begin: a multiple of 32 (16-byte pieces)
     const int SP = p.SP, N = p.N;
 
     fill_lut<K>(lds + L::LUT, tid, NT);
@@ -642,31 +642,36 @@ bool allow_large_lds(Kernel kernel, size_t bytes, size_t *granted)
     return true;
 }
 
+// Runs the rollout kernel on envs [n_begin, n_begin + EPW * (n_envs / EPW)); returns how many.
 template <int K, typename Word, int EPW>
-int launch_rollout(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
-                   uint8_t *d_done, int8_t *d_obs, hipStream_t st)
+int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d_actions, int n_steps,
+                   float *d_reward, uint8_t *d_done, int8_t *d_obs, hipStream_t st)
 {
     using V = View<K, EPW>;
     using L = Lds<K, Word, EPW>;
     const StudentDev &p = ctx->dev;
+    if (n_envs < EPW) return 0;
     const bool grid_lds = L::bytes(p.SP, true) <= LDS_PER_CU - 1024;
     const size_t shmem = L::bytes(p.SP, grid_lds);
-    const dim3 grid(p.N / EPW), block(64 * V::WAVES);
+    const dim3 grid(n_envs / EPW), block(64 * V::WAVES);
     const bool square = p.HP == p.WP;
     static size_t granted[2] = {0, 0};
     if (grid_lds && square) {
         auto kern = k_student_rollout<K, Word, EPW, true, true>;
         if (!allow_large_lds(kern, shmem, &granted[0])) return 0;
-        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, d_actions, n_steps, d_reward, d_done, d_obs);
+        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, d_actions, n_steps, d_reward, d_done,
+                           d_obs);
     } else if (grid_lds) {
         auto kern = k_student_rollout<K, Word, EPW, true, false>;
         if (!allow_large_lds(kern, shmem, &granted[1])) return 0;
-        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, d_actions, n_steps, d_reward, d_done, d_obs);
+        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, d_actions, n_steps, d_reward, d_done,
+                           d_obs);
     } else {
         auto kern = k_student_rollout<K, Word, EPW, false, false>;
-        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, d_actions, n_steps, d_reward, d_done, d_obs);
+        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, d_actions, n_steps, d_reward, d_done,
+                           d_obs);
     }
-    return EPW * (p.N / EPW);
+    return EPW * (n_envs / EPW);
 }
 
 // Envs per workgroup: the largest of 128 / 64 / 32 whose grids fit in LDS and that still
@@ -689,23 +694,30 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
                                d_actions, d_reward, d_done, d_obs);
         return REPW * (p.N / REPW);
     }
+    int covered = 0;
 #ifdef MAZE_FORCE_EPW
-    if (p.N >= MAZE_FORCE_EPW)
-        return launch_rollout<K, Word, MAZE_FORCE_EPW>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
-#endif
+    covered = launch_rollout<K, Word, MAZE_FORCE_EPW>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
+#else
     const int cus = 256;
     const bool fit128 = Lds<K, Word, 128>::bytes(p.SP, true) <= LDS_PER_CU - 1024;
     const bool fit64 = Lds<K, Word, 64>::bytes(p.SP, true) <= LDS_PER_CU - 1024;
     const bool fit32 = Lds<K, Word, 32>::bytes(p.SP, true) <= LDS_PER_CU - 1024;
     if (p.N >= 128 * cus && fit128)
-        return launch_rollout<K, Word, 128>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
-    if (p.N >= 64 * cus && fit64)
-        return launch_rollout<K, Word, 64>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
-    if (p.N >= 32 && (fit32 || !fit64))
-        return launch_rollout<K, Word, 32>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
-    if (p.N >= 64)
-        return launch_rollout<K, Word, 64>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
-    return 0;
+        covered = launch_rollout<K, Word, 128>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
+    else if (p.N >= 64 * cus && fit64)
+        covered = launch_rollout<K, Word, 64>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
+    else if (fit32 || !fit64)
+        covered = launch_rollout<K, Word, 32>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
+    else
+        covered = launch_rollout<K, Word, 64>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
+#endif
+    // the envs left over by a large workgroup size go to workgroups of 32 (a second, small
+    // launch on the same stream); what is left after that (< 32 envs) to the per-cell kernel.
+    // `covered` is a multiple of 32 envs = a whole number of 16-byte pieces of obs.
+    if (covered > 0 && p.N - covered >= 32)
+        covered += launch_rollout<K, Word, 32>(ctx, covered, p.N - covered, d_actions, n_steps, d_reward,
+                                               d_done, d_obs, st);
+    return covered;
 }
 
 }  // namespace

@@ -171,7 +171,7 @@ def test_chunked_rollout_equals_one_launch():
     assert_state_equal(env, o)
 
 
-@pytest.mark.parametrize("N", [128, 256 + 32, 8192 + 64 + 5, 16384, 32768 + 128 + 40])
+@pytest.mark.parametrize("N", [128, 256 + 32, 8192 + 64 + 5, 16384, 16384 + 32 + 16, 32768 + 96, 32768 + 128 + 40])
 def test_workgroup_size_choices(N):
     """Batch sizes that make the launcher pick 32, 64 or 128 envs per workgroup, with tails."""
     w = wl.student_random(f"epw{N}", 4000 + N, N=N, T=37, n_walls=50, max_steps=25)
