@@ -289,8 +289,17 @@ __global__ void k_student_percell(StudentDev p, int n_begin, const int8_t *__res
     uint32_t gr[4];
     for (int f = 0; f < 4; ++f) gr[f] = p.goalrot[4 * n + f];
     const size_t obs_env = (size_t)p.k * p.k * 3;
+    // actions are fetched four steps ahead: the loop otherwise waits a full memory round
+    // trip per step for one byte
+    constexpr int AHEAD = 4;
+    int a_q[AHEAD];
+#pragma unroll
+    for (int j = 0; j < AHEAD; ++j) a_q[j] = actions[(size_t)min(j, n_steps - 1) * p.N + n];
     for (int s = 0; s < n_steps; ++s) {
-        int a = actions[(size_t)s * p.N + n];
+        const int a = a_q[0];
+#pragma unroll
+        for (int j = 0; j + 1 < AHEAD; ++j) a_q[j] = a_q[j + 1];
+        a_q[AHEAD - 1] = actions[(size_t)min(s + AHEAD, n_steps - 1) * p.N + n];
         int xd = pose & 255, yd = (pose >> 8) & 255, d = (pose >> 16) & 3;
         bool blocked = (grid_n[d * p.SP + yd - 1] >> xd) & 1;
         pose = student_move(p, pose, a, blocked);
