@@ -105,14 +105,22 @@ extern "C" int maze_set_obs_mode(maze_ctx *ctx, int encoding, int occlusion)
 }
 
 // ------------------------------------------------------------- level packing
-// One wavefront per env.  The H*W wall bytes are turned into two bitmaps with wave
-// ballots -- row-major (bit y*W + x) and column-major (bit x*H + y) -- 64 cells per
-// ballot, kept in the wave's slice of LDS.  Every row of the four heading frames is
-// then one field of one of the bitmaps (reversed for the two frames that look
-// against the axis), shifted into the ring of border walls.  Lane 0 also packs the
-// start pose and the goal's position in the four frames.
-constexpr int PACK_WAVES = 4;                 // waves (= envs) per workgroup
-constexpr int PACK_BM_DWORDS = 4096 / 32 + 4;  // bitmap of up to 64x64 cells + zero tail
+// G lanes per env (16, 32 or 64: small grids share a wave, so that fewer, fuller waves
+// are launched).  The H*W wall bytes of an env are turned into two bitmaps with wave
+// ballots -- row-major (bit y*W + x) and column-major (bit x*H + y) -- G cells of every
+// env of the wave per ballot, kept in the env's slice of LDS.  Every row of the four
+// heading frames is then one field of one of the bitmaps (reversed for the two frames
+// that look against the axis), shifted into the ring of border walls.  Five lanes per
+// env also pack the start pose and the goal's position in the four frames.
+constexpr int PACK_WAVES = 4;                 // waves per workgroup
+
+// floor(n / d) for n < 2^16, d < 2^16 as one multiply: magic = ceil(2^32 / d) (0 stands for d = 1).
+__device__ __forceinline__ int div_magic(int n, uint32_t magic)
+{
+    return magic ? (int)__umulhi((uint32_t)n, magic) : n;
+}
+
+static uint32_t magic_of(int d) { return d == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); }
 
 __device__ __forceinline__ uint64_t bitmap_field(const uint32_t *bm, int offset, int len)
 {
@@ -124,69 +132,131 @@ __device__ __forceinline__ uint64_t bitmap_field(const uint32_t *bm, int offset,
     return len >= 64 ? v : (v & (((uint64_t)1 << len) - 1));
 }
 
-template <typename Word>
-__global__ __launch_bounds__(64 * PACK_WAVES) void k_pack_levels(
-    StudentDev p, const int8_t *__restrict__ walls, const int32_t *__restrict__ agent_xy,
-    const int8_t *__restrict__ agent_dir, const int32_t *__restrict__ goal_xy)
+// G-bit piece number c of a bitmap
+template <int G>
+__device__ __forceinline__ void store_piece(uint32_t *bm, int c, uint64_t piece)
 {
-    __shared__ uint32_t lds[PACK_WAVES][2][PACK_BM_DWORDS];
+    if (G == 16) ((uint16_t *)bm)[c] = (uint16_t)piece;
+    else if (G == 32) bm[c] = (uint32_t)piece;
+    else { bm[2 * c] = (uint32_t)piece; bm[2 * c + 1] = (uint32_t)(piece >> 32); }
+}
+
+// MAXC = largest H*W this instantiation takes; a bitmap has MAXC/32 dwords + 4 of zero tail.
+template <typename Word, int G, int MAXC>
+__global__ __launch_bounds__(64 * PACK_WAVES) void k_pack_levels(
+    StudentDev p, uint32_t magic_h, uint32_t magic_sp, const int8_t *__restrict__ walls,
+    const int32_t *__restrict__ agent_xy, const int8_t *__restrict__ agent_dir,
+    const int32_t *__restrict__ goal_xy)
+{
+    constexpr int EPV = 64 / G;                  // envs per wave
+    constexpr int BM = MAXC / 32 + 4;
+    __shared__ uint32_t lds[PACK_WAVES * EPV][2][BM];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n = blockIdx.x * PACK_WAVES + wave;
-    if (n >= p.N) return;                        // whole wave leaves together
-    uint32_t *bm_rm = lds[wave][0], *bm_cm = lds[wave][1];
+    const int sub = lane / G, l = lane - sub * G;
+    const int n_raw = (blockIdx.x * PACK_WAVES + wave) * EPV + sub;
+    const bool live = n_raw < p.N;
+    const int n = live ? n_raw : p.N - 1;        // idle lanes repeat the last env, store nothing
+    uint32_t *bm_rm = lds[wave * EPV + sub][0], *bm_cm = lds[wave * EPV + sub][1];
+    // the five pose lanes request their inputs now: the round trip overlaps the wall bytes'
+    const int32_t *pos_src = l < 4 ? goal_xy : agent_xy;
+    const int pos_x = l < 5 ? pos_src[2 * n] : 0, pos_y = l < 5 ? pos_src[2 * n + 1] : 0;
+    const int start_dir = agent_dir[n] & 3;
     const int cells = p.H * p.W;
     const int8_t *g = walls + (size_t)n * cells;
-    const int chunks = (cells + 63) >> 6;
-    for (int c = 0; c <= chunks; ++c) {          // one extra chunk of zeros as the tail
-        const int idx = c * 64 + lane;
-        const bool valid = idx < cells;
-        const int x = valid ? idx / p.H : 0, y = valid ? idx - x * p.H : 0;
-        const bool rm = valid && g[idx] != 0;
-        const bool cm = valid && g[y * p.W + x] != 0;
-        const uint64_t m_rm = __ballot(rm), m_cm = __ballot(cm);
-        if (lane == 0) {
-            bm_rm[2 * c] = (uint32_t)m_rm; bm_rm[2 * c + 1] = (uint32_t)(m_rm >> 32);
-            bm_cm[2 * c] = (uint32_t)m_cm; bm_cm[2 * c + 1] = (uint32_t)(m_cm >> 32);
+    for (int i = l; i < 2 * BM; i += G) bm_rm[i] = 0;        // both bitmaps (they are adjacent)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int chunks = (cells + G - 1) / G;
+    const uint64_t sub_mask = G == 64 ? ~(uint64_t)0 : (((uint64_t)1 << G) - 1);
+    // UNR chunks at a time, all their loads issued before the first ballot (one memory round
+    // trip per group; measured: 16 at a time is slower than 4)
+    constexpr int UNR = 4;
+    for (int c0 = 0; c0 < chunks; c0 += UNR) {
+        bool rm[UNR], cm[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int idx = (c0 + u) * G + l;
+            const bool valid = idx < cells;
+            const int x = valid ? div_magic(idx, magic_h) : 0, y = valid ? idx - x * p.H : 0;
+            rm[u] = valid && g[valid ? idx : 0] != 0;
+            cm[u] = valid && g[y * p.W + x] != 0;
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int c = c0 + u;
+            const uint64_t m_rm = (__ballot(rm[u]) >> (sub * G)) & sub_mask;
+            const uint64_t m_cm = (__ballot(cm[u]) >> (sub * G)) & sub_mask;
+            if (l == 0 && c < chunks) {
+                store_piece<G>(bm_rm, c, m_rm);
+                store_piece<G>(bm_cm, c, m_cm);
+            }
         }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     Word *out = (Word *)p.grids + (size_t)n * 4 * p.SP;
-    for (int task = lane; task < 4 * p.SP; task += 64) {
-        const int d = task / p.SP, row = task - d * p.SP;
+    for (int task = l; task < 4 * p.SP; task += G) {
+        const int d = div_magic(task, magic_sp), row = task - d * p.SP;
         const int rows = (d & 1) ? p.HP : p.WP;  // shape of frame d
         const int len = (d & 1) ? p.W : p.H;     // interior cells per row of frame d
         uint64_t word = ~(uint64_t)0;            // border rows and rows beyond the frame: solid
         const int r = row - p.P;                 // interior line of the frame
         if (row < rows && r >= 0 && r < rows - 2 * p.P) {
-            uint64_t f;
-            if (d == 3) f = bitmap_field(bm_rm, r * p.W, p.W);
-            else if (d == 1) f = __brevll(bitmap_field(bm_rm, (p.H - 1 - r) * p.W, p.W)) >> (64 - p.W);
-            else if (d == 0) f = bitmap_field(bm_cm, (p.W - 1 - r) * p.H, p.H);
-            else f = __brevll(bitmap_field(bm_cm, r * p.H, p.H)) >> (64 - p.H);
+            // frames 3 and 1 read lines of the row-major bitmap (W cells), frames 0 and 2 lines
+            // of the column-major one (H cells); frames 1 and 2 run against the axis (reversed
+            // bits), frames 1 and 0 take the lines in reverse order.  One field read per lane.
+            const bool col_major = !(d & 1);
+            const uint32_t *bm = col_major ? bm_cm : bm_rm;
+            const int lines = col_major ? p.W : p.H;
+            const int line = (d == 1 || d == 0) ? lines - 1 - r : r;
+            uint64_t f = bitmap_field(bm, line * len, len);
+            const uint64_t rev = __brevll(f) >> (64 - len);
+            f = (d == 1 || d == 2) ? rev : f;
             const uint64_t field_mask = (((uint64_t)1 << len) - 1) << p.P;
             word = (f << p.P) | ~field_mask;
         }
-        out[task] = (Word)word;
+        if (live) out[task] = (Word)word;
     }
-    if (lane == 0) {
-        int ax = min(max(agent_xy[2 * n], 0), p.W - 1) + p.P;
-        int ay = min(max(agent_xy[2 * n + 1], 0), p.H - 1) + p.P;
-        int gx = min(max(goal_xy[2 * n], 0), p.W - 1) + p.P;
-        int gy = min(max(goal_xy[2 * n + 1], 0), p.H - 1) + p.P;
-        int d = agent_dir[n] & 3;
+    if (l < 5 && live) {
+        const int X = min(max(pos_x, 0), p.W - 1) + p.P;
+        const int Y = min(max(pos_y, 0), p.H - 1) + p.P;
+        const int d = l < 4 ? l : start_dir;
         int xd, yd;
-        padded_to_frame(p, d, ax, ay, xd, yd);
-        uint32_t s = (uint32_t)xd | ((uint32_t)yd << 8) | ((uint32_t)d << 16);
-        p.start[n] = s;
-        p.pose[n] = s;
-        p.tcount[n] = 0;
-        for (int f = 0; f < 4; ++f) {
-            padded_to_frame(p, f, gx, gy, xd, yd);
-            p.goalrot[4 * n + f] = (uint32_t)xd | ((uint32_t)yd << 8);
+        padded_to_frame(p, d, X, Y, xd, yd);
+        const uint32_t v = (uint32_t)xd | ((uint32_t)yd << 8);
+        if (l < 4) {
+            p.goalrot[4 * n + l] = v;
+        } else {
+            const uint32_t s = v | ((uint32_t)d << 16);
+            p.start[n] = s;
+            p.pose[n] = s;
+            p.tcount[n] = 0;
         }
     }
+}
+
+template <typename Word>
+static void launch_pack(const StudentDev &p, const int8_t *d_walls, const int32_t *d_agent_xy,
+                        const int8_t *d_agent_dir, const int32_t *d_goal_xy, hipStream_t st)
+{
+    const int cells = p.H * p.W;
+    const dim3 block(64 * PACK_WAVES);
+    const uint32_t mh = magic_of(p.H), msp = magic_of(p.SP);
+    auto grid_for = [&](int envs_per_wave) {
+        const int per_block = PACK_WAVES * envs_per_wave;
+        return dim3((p.N + per_block - 1) / per_block);
+    };
+    if (cells <= 256)
+        hipLaunchKernelGGL((k_pack_levels<Word, 16, 256>), grid_for(4), block, 0, st, p, mh, msp, d_walls,
+                           d_agent_xy, d_agent_dir, d_goal_xy);
+    else if (cells <= 1024)
+        hipLaunchKernelGGL((k_pack_levels<Word, 32, 1024>), grid_for(2), block, 0, st, p, mh, msp, d_walls,
+                           d_agent_xy, d_agent_dir, d_goal_xy);
+    else
+        hipLaunchKernelGGL((k_pack_levels<Word, 64, 4096>), grid_for(1), block, 0, st, p, mh, msp, d_walls,
+                           d_agent_xy, d_agent_dir, d_goal_xy);
 }
 
 extern "C" int maze_reset_to_levels(maze_ctx *ctx, const int8_t *d_walls,
@@ -196,13 +266,10 @@ extern "C" int maze_reset_to_levels(maze_ctx *ctx, const int8_t *d_walls,
     if (!ctx || !d_walls || !d_agent_xy || !d_agent_dir || !d_goal_xy) return MAZE_ENULL;
     hipStream_t st = (hipStream_t)stream;
     const StudentDev &p = ctx->dev;
-    dim3 grid((p.N + PACK_WAVES - 1) / PACK_WAVES), block(64 * PACK_WAVES);
     if (ctx->word64)
-        hipLaunchKernelGGL(k_pack_levels<uint64_t>, grid, block, 0, st, p, d_walls, d_agent_xy,
-                           d_agent_dir, d_goal_xy);
+        launch_pack<uint64_t>(p, d_walls, d_agent_xy, d_agent_dir, d_goal_xy, st);
     else
-        hipLaunchKernelGGL(k_pack_levels<uint32_t>, grid, block, 0, st, p, d_walls, d_agent_xy,
-                           d_agent_dir, d_goal_xy);
+        launch_pack<uint32_t>(p, d_walls, d_agent_xy, d_agent_dir, d_goal_xy, st);
     MAZE_HIP_CHECK(hipGetLastError());
     return MAZE_OK;
 }
