@@ -100,11 +100,14 @@ extern "C" int replay_distribution(const float *d_scores, const int32_t *d_last_
     int n2 = 2;
     while (n2 < K) n2 <<= 1;
     const size_t shmem = rank_prioritization ? 8 * (size_t)n2 : 0;
-    static size_t granted = 0;               // dynamic LDS above 64 KB needs an opt-in, once
-    if (shmem > 60 * 1024 && shmem > granted) {
+    // dynamic LDS above 64 KB needs an opt-in, once per device
+    static size_t granted[16] = {};
+    int device = 0;
+    MAZE_HIP_CHECK(hipGetDevice(&device));
+    if (shmem > 60 * 1024 && shmem > granted[device & 15]) {
         MAZE_HIP_CHECK(hipFuncSetAttribute((const void *)k_replay_distribution,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem));
-        granted = shmem;
+        granted[device & 15] = shmem;
     }
     hipLaunchKernelGGL(k_replay_distribution, dim3(1), dim3(RD_THREADS), shmem, (hipStream_t)stream,
                        d_scores, d_last_seen, K, n2, now, rank_prioritization ? 1 : 0, 1.0 / temperature,

@@ -655,15 +655,19 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
     const size_t shmem = L::bytes(p.SP, grid_lds);
     const dim3 grid(n_envs / EPW), block(64 * V::WAVES);
     const bool square = p.HP == p.WP;
-    static size_t granted[2] = {0, 0};
+    // largest LDS size granted so far, per kernel flavour and device (the attribute belongs to
+    // the kernel on one device); a race between host threads only repeats the call
+    static size_t granted_all[2][16] = {};
+    size_t *granted = &granted_all[0][ctx->device & 15];
+    constexpr int FLAVOUR_STRIDE = 16;
     if (grid_lds && square) {
         auto kern = k_student_rollout<K, Word, EPW, true, true>;
-        if (!allow_large_lds(kern, shmem, &granted[0])) return 0;
+        if (!allow_large_lds(kern, shmem, granted)) return 0;
         hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, d_actions, n_steps, d_reward, d_done,
                            d_obs);
     } else if (grid_lds) {
         auto kern = k_student_rollout<K, Word, EPW, true, false>;
-        if (!allow_large_lds(kern, shmem, &granted[1])) return 0;
+        if (!allow_large_lds(kern, shmem, granted + FLAVOUR_STRIDE)) return 0;
         hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, d_actions, n_steps, d_reward, d_done,
                            d_obs);
     } else {
