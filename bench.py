@@ -194,12 +194,12 @@ def main():
         ms, mn = time_calls(torch, lambda: env.step(a1, r1, d1, o1), 200, warmup=20)
         rows["per_step_with_obs_c3"] = {"ms": ms, "env-steps/s": N / ms * 1e3,
                                         "note": "maze_step(n=1) writing obs: one launch per step"}
-        # observation variants (occluded view, type/colour/state bytes): per-cell kernels
+        # observation variants (occluded view, type/colour/state bytes)
         env.set_obs_mode(1, 1)
         ms, mn = time_calls(torch, lambda: env.step(actions, reward, done, obs), 5, warmup=1)
         rows["student_rollout_c3_occluded_typed_obs"] = {
             "ms": ms, "env-steps/s": N * T / ms * 1e3, "GB/s": 81.0 * N * T / ms / 1e6,
-            "note": "maze_set_obs_mode(1, 1): one lane per env, obs written byte by byte"}
+            "note": "maze_set_obs_mode(1, 1): occlusion in the records stage, typed bytes in the store stage"}
         env.set_obs_mode(0, 0)
         # the same single step replayed from a captured HIP graph (what a policy loop can do)
         side = torch.cuda.Stream()

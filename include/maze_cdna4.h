@@ -137,7 +137,7 @@ int maze_set_kernel_variant(maze_ctx *ctx, int variant);
  *                the agent's cell, each link going sideways within a view row or to
  *                one of the three touching cells of the next row ahead; seen walls
  *                pass nothing on; an unseen cell reads zero in all channels.
- * Any non-default mode runs in the per-cell kernels.  MAZE_EINVAL for other values. */
+ * MAZE_EINVAL for other values.                                                 */
 int maze_set_obs_mode(maze_ctx *ctx, int encoding, int occlusion);
 
 /* ------------------------------------------------------------------- teacher

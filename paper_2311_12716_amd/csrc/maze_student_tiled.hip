@@ -163,10 +163,27 @@ __device__ __forceinline__ void record_lookup(const uint32_t *lut, const uint32_
         piece[r] = lut[(vw[r / V::RPD] >> (K * (r % V::RPD))) & (V::LUTN - 1)];
 }
 
+// Occluded view: an unseen cell's three stream bits are cleared.  The row table entry of a
+// mask has bit 3c set for every 1 of the mask (the wall pattern 001b); times 7 gives 111b.
+template <int K>
+__device__ __forceinline__ void mask_unseen(const uint32_t *lut, const uint32_t (&seenw)[View<K, 64>::WV],
+                                            uint32_t (&piece)[K])
+{
+    using V = View<K, 64>;
+    constexpr uint32_t first_of_three = 0x49249249u & ((1u << V::ROWBITS) - 1);
+#pragma unroll
+    for (int r = 0; r < K; ++r) {
+        const uint32_t seen = (seenw[r / V::RPD] >> (K * (r % V::RPD))) & (V::LUTN - 1);
+        piece[r] &= (lut[seen] & first_of_three) * 7u;
+    }
+}
+
+// seenw: the seen cells (occluded view) packed like vw, or nullptr when every cell is shown.
 template <int K>
 __device__ __forceinline__ void record_finish(const uint32_t (&piece)[K],
                                               const uint32_t (&vw)[View<K, 64>::WV], int gf, int gc,
-                                              uint32_t (&D)[View<K, 64>::ND], uint32_t *rec)
+                                              uint32_t (&D)[View<K, 64>::ND], uint32_t *rec,
+                                              const uint32_t *seenw = nullptr)
 {
     using V = View<K, 64>;
 #pragma unroll
@@ -186,6 +203,11 @@ __device__ __forceinline__ void record_finish(const uint32_t (&piece)[K],
     const uint32_t gword = (V::WV == 1 || grow < V::RPD) ? vw_first : vw_last;
     const int gshift = K * (grow < V::RPD ? grow : grow - V::RPD) + c;
     inview = inview & !((gword >> (gshift & 31)) & 1);
+    if (seenw) {                                   // an unseen goal is not shown
+        const uint32_t sw_first = seenw[0], sw_last = seenw[V::WV - 1];
+        const uint32_t sword = (V::WV == 1 || grow < V::RPD) ? sw_first : sw_last;
+        inview = inview & ((sword >> (gshift & 31)) & 1);
+    }
     const int bit = inview ? 3 * (grow * K + c) + 1 : 0;
     const uint64_t flip = inview ? (uint64_t)3 << (bit & 31) : 0;
     const int fq = bit >> 5;
@@ -219,6 +241,9 @@ struct Window {
     int rem;        // bits taken from env e0 when fewer than 16, else 0 (then addr1 reads zero)
     int active;     // window exists (the last round is partial)
     uint32_t out;   // byte offset of the window's 16 output bytes in the workgroup's block
+    // typed encoding only: which of the window's 16 bytes are a cell's first (type) and second
+    // (colour) byte; a cell is three bytes and every env starts a new cell
+    uint32_t type_pos, colour_pos;
 };
 
 template <int K, int EPW>
@@ -239,6 +264,10 @@ __device__ __forceinline__ Window make_window(int lane, int round)
     w.rem = rem < 16 ? rem : 0;
     w.addr1 = rem < 16 ? rec0 + V::REC : rec0 + V::ND;
     w.out = 16u * mm;
+    const int phase = bitpos % 3;                // stream bit 16*mm is byte `phase` of its cell
+    const uint32_t every_third = 0x9249u;        // bits 0, 3, 6, 9, 12, 15
+    w.type_pos = phase == 0 ? every_third : (phase == 1 ? 0x4924u : 0x2492u);
+    w.colour_pos = phase == 0 ? 0x2492u : (phase == 1 ? every_third : 0x4924u);
     return w;
 }
 
@@ -253,6 +282,66 @@ __device__ __forceinline__ void consume_window(const uint32_t *recs, const Windo
     a.x = expand_nibble(bits & 15);          a.y = expand_nibble((bits >> 4) & 15);
     a.z = expand_nibble((bits >> 8) & 15);   a.w = expand_nibble((bits >> 12) & 15);
     *(uint4 *)(block + w.out) = a;
+}
+
+// The same window written in the (type, colour, state) encoding.  The one-hot stream holds,
+// per cell, the bits (wall, goal, empty); the typed bytes are
+//     type = 1*empty + 2*wall + 8*goal,  colour = 5*wall + 1*goal,  state = 0,
+// so bit planes 0..3 of the output bytes are picked from the stream bits of the same cell
+// one or two positions away, masked to the type / colour positions, expanded like the
+// plain stream and combined.  A cell never straddles two envs, so the bits needed beyond
+// the window come from the same records.
+__device__ __forceinline__ void consume_window_typed(const uint32_t *recs, const Window &w, int8_t *block)
+{
+    const uint32_t lo = recs[w.addr0], hi = recs[w.addr0 + 1], nx = recs[w.addr1];
+    const uint32_t prev = recs[w.addr0 > 0 ? w.addr0 - 1 : 0];
+    const uint32_t bits = __builtin_amdgcn_alignbit(hi, lo, w.sh) | (nx << w.rem);   // stream bits p, p+1, ...
+    const uint32_t below = w.sh ? (lo >> (w.sh - 1)) & 1u : prev >> 31;               // stream bit p-1
+    const uint32_t x = bits & 0xFFFFu, up1 = (bits >> 1) & 0xFFFFu, up2 = (bits >> 2) & 0xFFFFu;
+    const uint32_t down1 = ((bits << 1) | below) & 0xFFFFu;
+    const uint32_t p0 = (up2 & w.type_pos) | ((down1 | x) & w.colour_pos);   // empty -> 1; wall or goal -> colour bit 0
+    const uint32_t p1 = x & w.type_pos;                                      // wall -> type 2
+    const uint32_t p2 = down1 & w.colour_pos;                                // wall -> colour 4 (+1 = grey 5)
+    const uint32_t p3 = up1 & w.type_pos;                                    // goal -> type 8
+    uint32_t out[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int sh = 4 * q;
+        out[q] = expand_nibble((p0 >> sh) & 15) | (expand_nibble((p1 >> sh) & 15) << 1) |
+                 (expand_nibble((p2 >> sh) & 15) << 2) | (expand_nibble((p3 >> sh) & 15) << 3);
+    }
+    *(uint4 *)(block + w.out) = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
+// Which cells of the view are seen (occluded view): rows are settled from the agent's row
+// outwards as K-bit masks.  Seen cells spread sideways through cells that are not walls (a
+// seen wall spreads nothing), then every seen non-wall cell makes the three cells touching
+// it in the next row ahead seen.  The agent's own cell spreads whatever it holds.  Returns
+// the masks packed like the view bits (row r at bit K*(r % RPD) of dword r / RPD).
+template <int K>
+__device__ __forceinline__ void visible_cells(const uint32_t (&vw)[View<K, 64>::WV],
+                                              uint32_t (&seenw)[View<K, 64>::WV])
+{
+    using V = View<K, 64>;
+    constexpr uint32_t all = (1u << K) - 1;
+#pragma unroll
+    for (int q = 0; q < V::WV; ++q) seenw[q] = 0;
+    uint32_t from_below = 1u << (K / 2);
+#pragma unroll
+    for (int r = K - 1; r >= 0; --r) {
+        const uint32_t wall = (vw[r / V::RPD] >> (K * (r % V::RPD))) & all;
+        uint32_t open = ~wall & all;
+        if (r == K - 1) open |= 1u << (K / 2);
+        uint32_t seen = from_below;
+#pragma unroll
+        for (int it = 1; it < K; ++it) {
+            const uint32_t src = seen & open;
+            seen |= ((src << 1) | (src >> 1)) & all;
+        }
+        const uint32_t src = seen & open;
+        from_below = (src | (src << 1) | (src >> 1)) & all;
+        seenw[r / V::RPD] |= seen << (K * (r % V::RPD));
+    }
 }
 
 template <int K>
@@ -403,7 +492,9 @@ __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word>
         }                                                                                  \
     }
 
-template <int K, typename Word, int EPW, bool GRID_LDS, bool SQUARE>
+// MODE 0: the default observation.  MODE 1: the observation variants (p.obs_occlusion: unseen
+// cells cleared in the records stage; p.obs_encoding: typed bytes in the stores stage).
+template <int K, typename Word, int EPW, bool GRID_LDS, bool SQUARE, int MODE = 0>
 __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     StudentDev p, int n_begin, const int8_t *__restrict__ actions, int n_steps,
     float *__restrict__ reward, uint8_t *__restrict__ done, int8_t *__restrict__ obs)
@@ -543,6 +634,13 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                     _Pragma("unroll") for (int w = 0; w < UGR; ++w) if (MAZE_STEP_ON(u0 + w)) {
                         uint32_t D[V::ND];
                         uint32_t *rec = lds + L::REC + (par * SPB + u0 + w) * L::REC_SIZE + e * V::REC;
+                        if (MODE == 1 && p.obs_occlusion) {
+                            uint32_t seenw[V::WV];
+                            visible_cells<K>(vw[w], seenw);
+                            mask_unseen<K>(lds + L::LUT, seenw, piece[w]);
+                            record_finish<K>(piece[w], vw[w], (int)(int16_t)(g[w] & 0xFFFF),
+                                             (int)g[w] >> 16, D, rec, seenw);
+                        } else
                         record_finish<K>(piece[w], vw[w], (int)(int16_t)(g[w] & 0xFFFF), (int)g[w] >> 16,
                                          D, rec);
                         const uint32_t tr = out[w] & 0x7FFFFFFFu;
@@ -570,8 +668,11 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         MAZE_FOR_EACH_BLOCK(
             _Pragma("unroll") for (int u = 0; u < SPB; ++u) if (MAZE_STEP_ON(u)) {
                 const uint32_t *rec = lds + L::REC + (par * SPB + u) * L::REC_SIZE;
-                _Pragma("unroll") for (int j = 0; j < MYR; ++j)
-                    if (win[j].active) consume_window(rec, win[j], out_block + u * step_obs);
+                _Pragma("unroll") for (int j = 0; j < MYR; ++j) {
+                    if (!win[j].active) continue;
+                    if (MODE == 1 && p.obs_encoding) consume_window_typed(rec, win[j], out_block + u * step_obs);
+                    else consume_window(rec, win[j], out_block + u * step_obs);
+                }
             }
             out_block += SPB * step_obs;)
     }
@@ -643,7 +744,7 @@ bool allow_large_lds(Kernel kernel, size_t bytes, size_t *granted)
 }
 
 // Runs the rollout kernel on envs [n_begin, n_begin + EPW * (n_envs / EPW)); returns how many.
-template <int K, typename Word, int EPW>
+template <int K, typename Word, int EPW, int MODE = 0>
 int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d_actions, int n_steps,
                    float *d_reward, uint8_t *d_done, int8_t *d_obs, hipStream_t st)
 {
@@ -654,24 +755,24 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
     const bool grid_lds = L::bytes(p.SP, true) <= LDS_PER_CU - 1024;
     const size_t shmem = L::bytes(p.SP, grid_lds);
     const dim3 grid(n_envs / EPW), block(64 * V::WAVES);
-    const bool square = p.HP == p.WP;
+    const bool square = p.HP == p.WP && MODE == 0;       // the variants skip the square-grid flavour
     // largest LDS size granted so far, per kernel flavour and device (the attribute belongs to
     // the kernel on one device); a race between host threads only repeats the call
     static size_t granted_all[2][16] = {};
     size_t *granted = &granted_all[0][ctx->device & 15];
     constexpr int FLAVOUR_STRIDE = 16;
     if (grid_lds && square) {
-        auto kern = k_student_rollout<K, Word, EPW, true, true>;
+        auto kern = k_student_rollout<K, Word, EPW, true, MODE == 0, MODE>;
         if (!allow_large_lds(kern, shmem, granted)) return 0;
         hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, d_actions, n_steps, d_reward, d_done,
                            d_obs);
     } else if (grid_lds) {
-        auto kern = k_student_rollout<K, Word, EPW, true, false>;
+        auto kern = k_student_rollout<K, Word, EPW, true, false, MODE>;
         if (!allow_large_lds(kern, shmem, granted + FLAVOUR_STRIDE)) return 0;
         hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, d_actions, n_steps, d_reward, d_done,
                            d_obs);
     } else {
-        auto kern = k_student_rollout<K, Word, EPW, false, false>;
+        auto kern = k_student_rollout<K, Word, EPW, false, false, MODE>;
         hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, d_actions, n_steps, d_reward, d_done,
                            d_obs);
     }
@@ -698,6 +799,8 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
                                d_actions, d_reward, d_done, d_obs);
         return REPW * (p.N / REPW);
     }
+    if (p.obs_encoding || p.obs_occlusion)       // observation variants: one flavour, 64 envs per workgroup
+        return launch_rollout<K, Word, 64, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
     int covered = 0;
 #ifdef MAZE_FORCE_EPW
     covered = launch_rollout<K, Word, MAZE_FORCE_EPW>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
@@ -736,7 +839,8 @@ int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_ste
     const StudentDev &p = ctx->dev;
     *covered = 0;
     if (!d_obs) return 0;
-    if (p.obs_encoding || p.obs_occlusion) return 0;     // the variants run in the per-cell kernels
+    // single steps and renders of the observation variants run in the per-cell kernels
+    if ((p.obs_encoding || p.obs_occlusion) && n_steps <= 1) return 0;
     const int K = p.k;
     if (K != 3 && K != 5 && K != 7) return 0;
     // 16-byte accesses: every time step's obs block, the obs buffer and each step's row of
