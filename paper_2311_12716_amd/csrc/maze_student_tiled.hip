@@ -684,7 +684,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
 // rows from the packed grids in L2), then produce the records and expand them.
 constexpr int REPW = 64;
 
-template <int K, typename Word, bool DO_STEP>
+template <int K, typename Word, bool DO_STEP, int MODE = 0>
 __global__ __launch_bounds__(REPW) void k_step_render_tiled(
     StudentDev p, const int8_t *__restrict__ actions, float *__restrict__ reward,
     uint8_t *__restrict__ done, int8_t *__restrict__ obs)
@@ -719,13 +719,24 @@ __global__ __launch_bounds__(REPW) void k_step_render_tiled(
     uint32_t vw[V::WV];
     pack_view<K, Word>(rows, xd, vw);
     const uint32_t g = p.goalrot[4 * (size_t)n + d];
-    produce_record<K>(lds + L::LUT, lds + L::REC + lane * V::REC, vw, yd - (int)(g >> 8),
-                      (int)(g & 255) - xd);
+    uint32_t *rec = lds + L::REC + lane * V::REC;
+    if (MODE == 1 && p.obs_occlusion) {
+        uint32_t piece[K], D[V::ND], seenw[V::WV];
+        record_lookup<K>(lds + L::LUT, vw, piece);
+        visible_cells<K>(vw, seenw);
+        mask_unseen<K>(lds + L::LUT, seenw, piece);
+        record_finish<K>(piece, vw, yd - (int)(g >> 8), (int)(g & 255) - xd, D, rec, seenw);
+        rec[V::ND] = 0;
+    } else {
+        produce_record<K>(lds + L::LUT, rec, vw, yd - (int)(g >> 8), (int)(g & 255) - xd);
+    }
     __syncthreads();
     int8_t *block = obs + (size_t)env0 * V::SB;
     for (int j = 0; j < V::ROUNDS; ++j) {
         Window w = make_window<K, REPW>(lane, j);
-        if (w.active) consume_window(lds + L::REC, w, block);
+        if (!w.active) continue;
+        if (MODE == 1 && p.obs_encoding) consume_window_typed(lds + L::REC, w, block);
+        else consume_window(lds + L::REC, w, block);
     }
 }
 
@@ -791,11 +802,18 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
         if (p.N < REPW) return 0;
         const size_t shmem_render = Lds<K, Word, REPW>::bytes(p.SP, false);
         const dim3 grid(p.N / REPW), block(REPW);
-        if (n_steps == 0)
+        const bool variant = p.obs_encoding || p.obs_occlusion;
+        if (n_steps == 0 && !variant)
             hipLaunchKernelGGL((k_step_render_tiled<K, Word, false>), grid, block, shmem_render, st, p,
                                d_actions, d_reward, d_done, d_obs);
-        else
+        else if (n_steps == 0)
+            hipLaunchKernelGGL((k_step_render_tiled<K, Word, false, 1>), grid, block, shmem_render, st, p,
+                               d_actions, d_reward, d_done, d_obs);
+        else if (!variant)
             hipLaunchKernelGGL((k_step_render_tiled<K, Word, true>), grid, block, shmem_render, st, p,
+                               d_actions, d_reward, d_done, d_obs);
+        else
+            hipLaunchKernelGGL((k_step_render_tiled<K, Word, true, 1>), grid, block, shmem_render, st, p,
                                d_actions, d_reward, d_done, d_obs);
         return REPW * (p.N / REPW);
     }
@@ -839,8 +857,6 @@ int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_ste
     const StudentDev &p = ctx->dev;
     *covered = 0;
     if (!d_obs) return 0;
-    // single steps and renders of the observation variants run in the per-cell kernels
-    if ((p.obs_encoding || p.obs_occlusion) && n_steps <= 1) return 0;
     const int K = p.k;
     if (K != 3 && K != 5 && K != 7) return 0;
     // 16-byte accesses: every time step's obs block, the obs buffer and each step's row of

@@ -53,6 +53,20 @@ def test_other_shapes(H, W, k, nw):
         run_variant(w, enc, occ)
 
 
+@pytest.mark.parametrize("encoding,occlusion", MODES)
+def test_single_steps_in_a_policy_loop(encoding, occlusion):
+    w = wl.config(2, T=24)
+    env, o = gpu_student(w), cpu_student(w)
+    env.set_obs_mode(encoding, occlusion)
+    o.set_obs_mode(encoding, occlusion)
+    acts = to_gpu(w.actions)
+    for t in range(w.T):
+        out = env.step(acts[t:t + 1])
+        assert_rollout_equal(out, o.step(w.actions[t:t + 1], 1), f"step {t}")
+    assert (env.render_obs().cpu().numpy() == o.render_obs()).all()
+    assert_state_equal(env, o)
+
+
 def test_levels_outside_the_preconditions():
     w = wl.student_random("variant-odd", 97, N=384, H=13, W=13, view=5, T=40, n_walls=55, max_steps=20)
     n = np.arange(w.N)
