@@ -277,6 +277,19 @@ def main():
         ms, mn = time_calls(torch, lambda: ed.mutate_levels(2, 0, 20), 20)
         rows["editor_mutate_levels_c4_20edits"] = {"ms": ms, "levels/s": ew.N / ms * 1e3}
         del eobs, et, edn, ed
+        # configs 1 and 2: small batches (latency-bound)
+        for ci in (1, 2):
+            wc = wl.config(ci)
+            ec = binding.MazeEnv(wc.N, wc.H, wc.W, wc.view, wc.max_steps, device=dev)
+            ec.reset_to_levels(g(wc.walls), g(wc.agent_xy), g(wc.agent_dir), g(wc.goal_xy))
+            ac = g(wc.actions)
+            rc_ = torch.empty((wc.T, wc.N), dtype=torch.float32, device=dev)
+            dc = torch.empty((wc.T, wc.N), dtype=torch.uint8, device=dev)
+            oc = torch.empty((wc.T, wc.N, 5, 5, 3), dtype=torch.int8, device=dev)
+            ms, mn = time_calls(torch, lambda: ec.step(ac, rc_, dc, oc), 20)
+            rows[f"student_rollout_c{ci}"] = {"ms": ms, "env-steps/s": wc.N * wc.T / ms * 1e3,
+                                              "GB/s": 81.0 * wc.N * wc.T / ms / 1e6}
+            del ec, oc
         # config 5: 51x51 perfect mazes, view 7
         w5 = wl.config(5)
         env5 = binding.MazeEnv(w5.N, w5.H, w5.W, w5.view, w5.max_steps, device=dev)
