@@ -4,6 +4,7 @@ from __future__ import annotations
 import glob
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -13,12 +14,13 @@ HEADERS = sorted(glob.glob(os.path.join(HERE, "csrc", "*.h"))) + \
     [os.path.join(ROOT, "include", "maze_cdna4.h")]
 
 HIPCC_FLAGS = [
-    "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
+    "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
     "-ffp-contract=off",
     # packed-FP32 instructions are kept out of the generated code on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I" + os.path.join(ROOT, "include"),
 ]
+OBJ_DIR = os.path.join(HERE, "csrc", "_build")
 
 
 def is_stale() -> bool:
@@ -28,20 +30,37 @@ def is_stale() -> bool:
     return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
 
 
-def build_library(force: bool = True, verbose: bool = False) -> str:
-    if not force and not is_stale():
-        return LIB
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + f".tmp{os.getpid()}"
-    cmd = [hipcc] + HIPCC_FLAGS + SOURCES + ["-o", tmp]
+def _run(cmd, verbose):
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:
         print(" ".join(cmd))
         print(res.stdout)
         print("\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l))
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed building libmaze_cdna4.so")
-    os.replace(tmp, LIB)
+    return res.returncode
+
+
+def build_library(force: bool = True, verbose: bool = False) -> str:
+    """Compile every csrc/*.hip to an object (side by side) and link them."""
+    if not force and not is_stale():
+        return LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    objs = [os.path.join(OBJ_DIR, os.path.basename(s)[:-4] + f".{os.getpid()}.o") for s in SOURCES]
+    jobs = min(len(SOURCES), max(1, min(16, os.cpu_count() or 1)))
+    try:
+        with ThreadPoolExecutor(jobs) as pool:
+            codes = list(pool.map(lambda so: _run([hipcc] + HIPCC_FLAGS + ["-c", so[0], "-o", so[1]], verbose),
+                                  zip(SOURCES, objs)))
+        if any(codes):
+            raise RuntimeError("hipcc failed compiling libmaze_cdna4.so")
+        tmp = LIB + f".tmp{os.getpid()}"
+        if _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", tmp], verbose):
+            raise RuntimeError("hipcc failed linking libmaze_cdna4.so")
+        os.replace(tmp, LIB)
+    finally:
+        for o in objs:
+            if os.path.exists(o):
+                os.remove(o)
     return LIB
 
 

@@ -37,6 +37,30 @@ __device__ __forceinline__ void lds_clear_bit(uint32_t *rec, int bit)
     atomicAnd(&rec[bit >> 5], ~(1u << (bit & 31)));
 }
 
+// The first `valid` (< 16) bytes of a piece: 8, 4, 2 and 1 bytes as the bits of `valid` say.
+__device__ __forceinline__ void store_tail(int8_t *dst, const uint4 &v, int valid)
+{
+    uint64_t cur = ((uint64_t)v.y << 32) | v.x;
+    if (valid & 8) {
+        __builtin_memcpy(dst, &cur, 8);
+        dst += 8;
+        cur = ((uint64_t)v.w << 32) | v.z;
+    }
+    if (valid & 4) {
+        const uint32_t w = (uint32_t)cur;
+        __builtin_memcpy(dst, &w, 4);
+        dst += 4;
+        cur >>= 32;
+    }
+    if (valid & 2) {
+        const uint16_t h = (uint16_t)cur;
+        __builtin_memcpy(dst, &h, 2);
+        dst += 2;
+        cur >>= 16;
+    }
+    if (valid & 1) *dst = (int8_t)cur;
+}
+
 __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
     EditorDev p, const int32_t *__restrict__ actions, int n_steps, int8_t *__restrict__ obs,
     int32_t *__restrict__ t_out, uint8_t *__restrict__ done)
@@ -47,17 +71,20 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
     const int env0 = blockIdx.x * EPW;
     const int SW = p.SW, REC = SW + 1;
     const int SB = 3 * p.cells;                  // stream bits = obs bytes per env
+    const int count = min(EPW, p.N - env0);      // envs of this workgroup (the last one may be partly filled)
 
-    // stage the streams (and zero the pad dwords)
+    // stage the streams (and zero the pad dwords; streams of absent envs read as empty)
     for (int i = tid; i < EPW * REC; i += 64 * NWAVES) {
         int e = i / REC, o = i - e * REC;
-        lds[i] = (o < SW) ? p.stream[(size_t)(env0 + e) * SW + o] : 0u;
+        lds[i] = (o < SW && e < count) ? p.stream[(size_t)(env0 + e) * SW + o] : 0u;
     }
     __syncthreads();
 
     if (wave < NE) {
         // ==================================================================== edit
-        const int e = wave * 64 + lane, n = env0 + e;
+        const int e = wave * 64 + lane;
+        const bool present = e < count;
+        const int n = env0 + (present ? e : 0);  // absent lanes repeat env 0's reads, write nothing
         uint32_t *rec = lds + e * REC;
         int32_t t = p.t[n], ac = p.agent_cell[n], gc = p.goal_cell[n];
         const int32_t *act = actions + n;
@@ -79,20 +106,23 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
                 lds_set_bit(rec, 3 * j + 1);
             }
             if (t < p.n_walls + 2) t += 1;
-            if (t_out) t_out[(size_t)s * p.N + n] = t;
-            if (done) done[(size_t)s * p.N + n] = (t == p.n_walls + 2) ? 1 : 0;
+            if (t_out && present) t_out[(size_t)s * p.N + n] = t;
+            if (done && present) done[(size_t)s * p.N + n] = (t == p.n_walls + 2) ? 1 : 0;
             __syncthreads();                     // edits of step s visible
             __syncthreads();                     // stores of step s have read the streams
         }
         // write the state back
-        p.t[n] = t;
-        p.agent_cell[n] = ac;
-        p.goal_cell[n] = gc;
-        for (int o = 0; o < SW; ++o) p.stream[(size_t)n * SW + o] = rec[o];
+        if (present) {
+            p.t[n] = t;
+            p.agent_cell[n] = ac;
+            p.goal_cell[n] = gc;
+            for (int o = 0; o < SW; ++o) p.stream[(size_t)n * SW + o] = rec[o];
+        }
     } else {
         // =================================================================== store
         const int c = wave - NE;
-        const int nwin = EPW * SB / 16;          // 16-bit windows per step (EPW*SB is a multiple of 16)
+        const int block_bytes = count * SB;      // obs bytes of the workgroup per step
+        const int nwin = (block_bytes + 15) / 16;  // 16-bit windows per step (the last may be cut)
         // window m = c*64 + lane, then every NS*64 windows; its position is kept as
         // (env e0, bit s inside the env) and advanced without divisions
         const int adv_bits = 16 * NS * 64;
@@ -114,7 +144,9 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
                 uint4 v;
                 v.x = expand_nibble(bits & 15);          v.y = expand_nibble((bits >> 4) & 15);
                 v.z = expand_nibble((bits >> 8) & 15);   v.w = expand_nibble((bits >> 12) & 15);
-                *(uint4 *)(out_block + 16 * (size_t)m) = v;
+                const int valid = block_bytes - 16 * m;
+                if (valid >= 16) __builtin_memcpy(out_block + 16 * (size_t)m, &v, 16);   // any alignment: one dwordx4 store
+                else store_tail(out_block + 16 * (size_t)m, v, valid);
                 bs += adv_r;
                 e0 += adv_q;
                 if (bs >= SB) { bs -= SB; e0 += 1; }
@@ -127,8 +159,8 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
 
 }  // namespace
 
-// Returns 1 if the tiled kernel was launched on the first *covered envs (a multiple of
-// EPW; the caller runs the per-cell kernel on the rest), 0 if the shape is not covered.
+// Returns 1 if the tiled kernel was launched (on all envs: *covered = N; the last workgroup
+// may be partly filled), 0 if the shape is not covered (the caller runs the per-cell kernel).
 int editor_tiled_launch(const editor_ctx *ctx, const int32_t *d_actions, int n_steps,
                         int8_t *d_obs, int32_t *d_t, uint8_t *d_done, int *covered, hipStream_t st)
 {
@@ -137,12 +169,10 @@ int editor_tiled_launch(const editor_ctx *ctx, const int32_t *d_actions, int n_s
     if (!d_obs) return 0;
     size_t shmem = 4 * (size_t)EPW * (p.SW + 1);
     if (shmem > 60 * 1024) return 0;
-    // 16-byte stores: each step's obs block and the buffer must be 16-byte aligned
-    if ((((size_t)p.N * 3 * p.cells) & 15) != 0 || ((uintptr_t)d_obs & 15) != 0) return 0;
-    int groups = p.N / EPW;
-    if (groups == 0) return 0;
+    if (3 * p.cells < 16) return 0;              // a 16-bit window must not span more than two envs
+    const int groups = (p.N + EPW - 1) / EPW;
     hipLaunchKernelGGL(k_editor_tiled, dim3(groups), dim3(64 * NWAVES), shmem, st, p, d_actions,
                        n_steps, d_obs, d_t, d_done);
-    *covered = groups * EPW;
+    *covered = p.N;
     return 1;
 }

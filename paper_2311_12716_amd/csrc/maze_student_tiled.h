@@ -1,0 +1,942 @@
+// Tiled store-layout kernels of the student env (templates; included by one translation
+// unit per view size, which instantiates them).
+//
+// A workgroup owns EPW consecutive envs for the whole rollout: 128 when the batch is
+// large enough to fill the GPU that way (128 * 3k^2 bytes per step is a whole number
+// of 128-byte lines, so no line of the output is shared between workgroups), 64 or
+// 32 for smaller batches or grids whose LDS copy would not fit.  Per step one lane
+// per env advances the env (state in registers, wall rows from LDS) and its
+// observation is built as a BIT STREAM -- bit i of the stream is byte i of the env's
+// k*k*3 observation, which is 0 or 1 -- and left in LDS.  The EPW streams,
+// concatenated, are exactly the EPW*3k^2 contiguous output bytes of this time step,
+// so other lanes then take 16 consecutive stream bits each (they may straddle two
+// envs), expand each bit to a byte and write 16 contiguous bytes; consecutive lanes
+// take consecutive pieces, so one store instruction of a wave writes 1 KB of
+// contiguous, aligned output.
+//
+// The per-step work is a four-stage pipeline over the waves of the workgroup,
+// advanced by one barrier per block of SPB steps:
+//   first  ("dynamics") block b  : action, move (one wall word: the row ahead),
+//                                  goal/done/reset; publish pose, goal offset, outcome
+//   next   ("views")    block b-1: K wall rows of the view -> K x K view bits
+//   next   ("records")  block b-2: view bits -> stream record (row lookup table),
+//                                  goal cell patched in; store reward and done
+//   rest   ("stores")   block b-3: expand records to bytes, store obs
+// (one dynamics, one views and one records wave per 64 envs; every stage has at most
+// two dependent LDS round trips)
+// Only the dynamics wave carries a dependency from step to step, so the time per
+// step is that wave's short chain; the store waves never load from global memory
+// and the dynamics wave touches it once every 16 steps (actions, staged in LDS).
+#pragma once
+
+#include "maze_internal.h"
+#include "maze_student_device.h"
+
+// Compile-time knobs (overridable for measurements).
+#ifndef MAZE_SPB
+#define MAZE_SPB 8
+#endif
+#ifndef MAZE_STORE_WAVES
+#define MAZE_STORE_WAVES 10
+#endif
+
+namespace {
+
+constexpr int SPB = MAZE_SPB;   // steps per barrier: every stage handles SPB steps between barriers
+// Steps a stage handles together (all reads, then all writes): the largest power of two
+// that divides SPB and keeps the group's registers within `budget` dwords.
+constexpr int step_group(int dwords_per_step, int budget)
+{
+    int g = 1;
+    while (2 * g <= SPB && SPB % (2 * g) == 0 && 2 * g * dwords_per_step <= budget) g *= 2;
+    return g;
+}
+
+// Compile-time shape of a workgroup: view size K, EPW envs.
+template <int K, int EPW>
+struct View {
+    static constexpr int CELLS = K * K;
+    static constexpr int SB = 3 * CELLS;           // stream bits (= obs bytes) per env
+    static constexpr int ND = (SB + 31) / 32;      // data dwords per env record
+    static constexpr int REC = ND + 1;             // record = data dwords + one zero dword
+    static constexpr int LUTN = 1 << K;            // row pattern -> 3K stream bits
+    static constexpr int ROWBITS = 3 * K;
+    static constexpr int RPD = 32 / K;             // view rows packed per dword
+    static constexpr int WV = (K + RPD - 1) / RPD; // dwords of packed view bits
+    static constexpr int LA = EPW < 64 ? EPW : 64; // envs (= active lanes) of a dynamics / records wave
+    static constexpr int NDYN = EPW / LA;          // dynamics waves (and records waves)
+    static constexpr int NWIN = EPW * SB / 16;     // 16-bit windows per workgroup step
+    static constexpr int ROUNDS = (NWIN + 63) / 64;
+    static constexpr int NC = ROUNDS < MAZE_STORE_WAVES ? ROUNDS : MAZE_STORE_WAVES;   // store waves
+    static constexpr int WAVES = 3 * NDYN + NC;
+    // actions: one 16-byte load per lane covers 16 envs of one step, so a dynamics wave
+    // stages ACT_BLOCK steps of its LA envs per load
+    static constexpr int ACT_LPR = LA / 16;
+    static constexpr int ACT_BLOCK = 64 / ACT_LPR;
+    static_assert((EPW * SB) % 16 == 0, "a step's chunk must be a whole number of 16-byte pieces");
+};
+
+// 16-byte global accesses at addresses of any alignment (a batch size or a buffer offset that
+// is not a multiple of 16 shifts every step's block): a plain 16-byte copy, which compiles to
+// one dwordx4 instruction on this target whatever the alignment.
+__device__ __forceinline__ void store16(int8_t *dst, const uint4 &v) { __builtin_memcpy(dst, &v, 16); }
+__device__ __forceinline__ uint4 load16(const int8_t *src)
+{
+    uint4 v;
+    __builtin_memcpy(&v, src, 16);
+    return v;
+}
+
+// The same for a piece of which only the first `valid` (< 16) bytes exist (the last, partly
+// filled workgroup of a batch).
+__device__ __forceinline__ void store_bytes(int8_t *dst, const uint4 &v, int valid)
+{
+    // 8, 4, 2 and 1 bytes as the bits of `valid` say: at most four stores
+    uint64_t cur = ((uint64_t)v.y << 32) | v.x;
+    if (valid & 8) {
+        __builtin_memcpy(dst, &cur, 8);
+        dst += 8;
+        cur = ((uint64_t)v.w << 32) | v.z;
+    }
+    if (valid & 4) {
+        const uint32_t w = (uint32_t)cur;
+        __builtin_memcpy(dst, &w, 4);
+        dst += 4;
+        cur >>= 32;
+    }
+    if (valid & 2) {
+        const uint16_t h = (uint16_t)cur;
+        __builtin_memcpy(dst, &h, 2);
+        dst += 2;
+        cur >>= 16;
+    }
+    if (valid & 1) *dst = (int8_t)cur;
+}
+__device__ __forceinline__ uint4 load_bytes(const int8_t *src, int valid)
+{
+    uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int b = 0; b < 16; ++b)
+        if (b < valid) w[b >> 2] |= (uint32_t)(uint8_t)src[b] << (8 * (b & 3));
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// 16 action bytes of one step (row clamped to the last step), from a lane's first column on.
+template <bool PARTIAL>
+__device__ __forceinline__ uint4 load_actions(const int8_t *act_lane, int row, int last, int N, int valid)
+{
+    const int8_t *src = act_lane + (size_t)min(row, last) * N;
+    return (!PARTIAL || valid >= 16) ? load16(src) : load_bytes(src, valid);
+}
+
+// 4 stream bits -> 4 bytes (bit j -> byte j).  The four shifted copies do not
+// overlap, so the multiply carries nothing.
+__device__ __forceinline__ uint32_t expand_nibble(uint32_t nib)
+{
+    return (nib * 0x00204081u) & 0x01010101u;
+}
+
+template <typename Word> struct WordOps;
+template <> struct WordOps<uint32_t> { static constexpr int DW = 1; };
+template <> struct WordOps<uint64_t> { static constexpr int DW = 2; };
+
+// Per-workgroup LDS carve-up (dword offsets).  ST and REC hold SPB steps each and
+// are double buffered by block parity (a block = the SPB steps between two barriers).
+template <int K, typename Word, int EPW>
+struct Lds {
+    using V = View<K, EPW>;
+    static constexpr int LUT = 0;                                  // [LUTN]
+    static constexpr int ACT = LUT + V::LUTN;                      // [2][ACT_BLOCK][EPW] action bytes
+    static constexpr int ACT_ROW = EPW;                            // bytes per step
+    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][3][EPW] pose, goal offset, out
+    static constexpr int ST_SIZE = 3 * EPW;
+    static constexpr int VW = ST + 2 * SPB * ST_SIZE;              // [2][SPB][WV+2][EPW] view bits, goal, out
+    static constexpr int VW_SIZE = (V::WV + 2) * EPW;
+    static constexpr int REC = VW + 2 * SPB * VW_SIZE;             // [2][SPB][EPW*REC] stream records
+    static constexpr int REC_SIZE = EPW * V::REC;
+    static constexpr int GRID0 = REC + 2 * SPB * REC_SIZE;         // [EPW][grid_stride]
+    __host__ __device__ static int grid_stride(int SP)             // dwords per env, odd
+    {
+        return (4 * SP * WordOps<Word>::DW) | 1;
+    }
+    __host__ static size_t bytes(int SP, bool grid_in_lds)
+    {
+        return 4 * (size_t)(GRID0 + (grid_in_lds ? EPW * grid_stride(SP) : 0));
+    }
+};
+
+// The K wall words of an env's view (row 0 farthest).  From LDS or, for grids too
+// large to stage, from the packed grids in global memory.
+template <int K, typename Word, bool GRID_LDS>
+__device__ __forceinline__ void load_view_rows(const uint32_t *lds_env, const Word *glob_env, int SP,
+                                               int d, int yd, Word (&rows)[K])
+{
+    int first = d * SP + yd - (K - 1);
+    if (GRID_LDS) {
+        if (sizeof(Word) == 4) {
+#pragma unroll
+            for (int r = 0; r < K; ++r) rows[r] = (Word)lds_env[first + r];
+        } else {
+#pragma unroll
+            for (int r = 0; r < K; ++r) {
+                uint32_t lo = lds_env[2 * (first + r)], hi = lds_env[2 * (first + r) + 1];
+                rows[r] = (Word)(((uint64_t)hi << 32) | lo);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < K; ++r) rows[r] = glob_env[first + r];
+    }
+}
+
+// K x K view bits (row r, column c -> bit K*(r % RPD) + c of dword r / RPD).
+template <int K, typename Word>
+__device__ __forceinline__ void pack_view(const Word (&rows)[K], int xd, uint32_t (&vw)[View<K, 64>::WV])
+{
+    using V = View<K, 64>;
+    const int sh = xd - K / 2;
+#pragma unroll
+    for (int q = 0; q < V::WV; ++q) vw[q] = 0;
+#pragma unroll
+    for (int r = 0; r < K; ++r) {
+        uint32_t bits = sizeof(Word) == 4 ? __builtin_amdgcn_ubfe((uint32_t)rows[r], sh, K)
+                                          : (uint32_t)(rows[r] >> sh) & (V::LUTN - 1);
+        vw[r / V::RPD] |= bits << (K * (r % V::RPD));
+    }
+}
+
+// Stream record of one env from its view bits; goal at (gf cells ahead, gc cells to
+// the right) of the agent.  An empty cell is 100b, a wall 001b, the goal 010b.
+// record_lookup() only reads (the row table), record_finish() only computes, so a caller
+// that builds several records can issue all table reads before the first write.
+template <int K>
+__device__ __forceinline__ void record_lookup(const uint32_t *lut, const uint32_t (&vw)[View<K, 64>::WV],
+                                              uint32_t (&piece)[K])
+{
+    using V = View<K, 64>;
+#pragma unroll
+    for (int r = 0; r < K; ++r)
+        piece[r] = lut[(vw[r / V::RPD] >> (K * (r % V::RPD))) & (V::LUTN - 1)];
+}
+
+// Occluded view: an unseen cell's three stream bits are cleared.  The row table entry of a
+// mask has bit 3c set for every 1 of the mask (the wall pattern 001b); times 7 gives 111b.
+template <int K>
+__device__ __forceinline__ void mask_unseen(const uint32_t *lut, const uint32_t (&seenw)[View<K, 64>::WV],
+                                            uint32_t (&piece)[K])
+{
+    using V = View<K, 64>;
+    constexpr uint32_t first_of_three = 0x49249249u & ((1u << V::ROWBITS) - 1);
+#pragma unroll
+    for (int r = 0; r < K; ++r) {
+        const uint32_t seen = (seenw[r / V::RPD] >> (K * (r % V::RPD))) & (V::LUTN - 1);
+        piece[r] &= (lut[seen] & first_of_three) * 7u;
+    }
+}
+
+// seenw: the seen cells (occluded view) packed like vw, or nullptr when every cell is shown.
+template <int K>
+__device__ __forceinline__ void record_finish(const uint32_t (&piece)[K],
+                                              const uint32_t (&vw)[View<K, 64>::WV], int gf, int gc,
+                                              uint32_t (&D)[View<K, 64>::ND], uint32_t *rec,
+                                              const uint32_t *seenw = nullptr)
+{
+    using V = View<K, 64>;
+#pragma unroll
+    for (int q = 0; q < V::ND; ++q) D[q] = 0;
+#pragma unroll
+    for (int r = 0; r < K; ++r) {
+        const int off = V::ROWBITS * r, q = off >> 5, b = off & 31;
+        D[q] |= piece[r] << b;
+        if (b + V::ROWBITS > 32) D[q + 1] |= piece[r] >> (32 - b);
+    }
+    // goal: the empty cell (100b) becomes a goal cell (010b): flip stream bits 3c+1, 3c+2
+    // (a goal that sits on a wall cell -- a level the caller should not build -- shows as wall)
+    const int c = gc + K / 2;                      // view column
+    bool inview = ((unsigned)gf < (unsigned)K) & ((unsigned)c < (unsigned)K);
+    const int grow = inview ? K - 1 - gf : 0;      // view row of the goal
+    const uint32_t vw_first = vw[0], vw_last = vw[V::WV - 1];   // scalars: no indexed select
+    const uint32_t gword = (V::WV == 1 || grow < V::RPD) ? vw_first : vw_last;
+    const int gshift = K * (grow < V::RPD ? grow : grow - V::RPD) + c;
+    inview = inview & !((gword >> (gshift & 31)) & 1);
+    if (seenw) {                                   // an unseen goal is not shown
+        const uint32_t sw_first = seenw[0], sw_last = seenw[V::WV - 1];
+        const uint32_t sword = (V::WV == 1 || grow < V::RPD) ? sw_first : sw_last;
+        inview = inview & ((sword >> (gshift & 31)) & 1);
+    }
+    const int bit = inview ? 3 * (grow * K + c) + 1 : 0;
+    const uint64_t flip = inview ? (uint64_t)3 << (bit & 31) : 0;
+    const int fq = bit >> 5;
+#pragma unroll
+    for (int q = 0; q < V::ND; ++q) {
+        uint32_t m = (q == fq) ? (uint32_t)flip : 0u;
+        if (q > 0) m |= (q - 1 == fq) ? (uint32_t)(flip >> 32) : 0u;
+        rec[q] = D[q] ^ m;
+    }
+}
+
+template <int K>
+__device__ __forceinline__ void produce_record(const uint32_t *lut, uint32_t *rec,
+                                               const uint32_t (&vw)[View<K, 64>::WV], int gf, int gc)
+{
+    using V = View<K, 64>;
+    uint32_t piece[K], D[V::ND];
+    record_lookup<K>(lut, vw, piece);
+    record_finish<K>(piece, vw, gf, gc, D, rec);
+    rec[V::ND] = 0;
+}
+
+// Lane-constant description of the 16 stream bits a lane expands in one round.
+// In round j lane l takes window 64*j + l, so one store instruction of the wave
+// writes 64 consecutive 16-byte pieces = 1 KB of contiguous output.
+// Dword indices are relative to the first record of the buffer.
+struct Window {
+    int addr0;      // first dword holding the window (in env e0's record)
+    int addr1;      // env e0+1's first dword, or e0's zero dword when the window ends in e0
+    int sh;         // bit offset of the window inside addr0's dword
+    int rem;        // bits taken from env e0 when fewer than 16, else 0 (then addr1 reads zero)
+    int active;     // window exists (the last round is partial)
+    uint32_t out;   // byte offset of the window's 16 output bytes in the workgroup's block
+    // typed encoding only: which of the window's 16 bytes are a cell's first (type) and second
+    // (colour) byte; a cell is three bytes and every env starts a new cell
+    uint32_t type_pos, colour_pos;
+    int valid;      // bytes of the window that exist: 16, fewer in a partly filled workgroup
+};
+
+template <int K, int EPW>
+__device__ __forceinline__ Window make_window(int lane, int round)
+{
+    using V = View<K, EPW>;
+    Window w;
+    int m = round * 64 + lane;
+    w.active = (round < V::ROUNDS) && (m < V::NWIN);
+    int mm = w.active ? m : 0;
+    int bitpos = 16 * mm;
+    int e0 = bitpos / V::SB;
+    int s = bitpos - e0 * V::SB;
+    int rec0 = e0 * V::REC;
+    w.addr0 = rec0 + (s >> 5);
+    w.sh = s & 31;
+    int rem = V::SB - s;
+    w.rem = rem < 16 ? rem : 0;
+    w.addr1 = rem < 16 ? rec0 + V::REC : rec0 + V::ND;
+    w.out = 16u * mm;
+    w.valid = 16;
+    const int phase = bitpos % 3;                // stream bit 16*mm is byte `phase` of its cell
+    const uint32_t every_third = 0x9249u;        // bits 0, 3, 6, 9, 12, 15
+    w.type_pos = phase == 0 ? every_third : (phase == 1 ? 0x4924u : 0x2492u);
+    w.colour_pos = phase == 0 ? 0x2492u : (phase == 1 ? every_third : 0x4924u);
+    return w;
+}
+
+// Expand one 16-bit window of the concatenated streams into 16 output bytes.
+__device__ __forceinline__ void consume_window(const uint32_t *recs, const Window &w, int8_t *block)
+{
+    uint32_t lo = recs[w.addr0], hi = recs[w.addr0 + 1], nx = recs[w.addr1];
+    // bits [s, s+16) of env e0 (zero beyond its end), then env e0+1 from bit 0; when the
+    // window ends inside e0, nx is e0's zero dword and the shift amount is irrelevant
+    uint32_t bits = __builtin_amdgcn_alignbit(hi, lo, w.sh) | (nx << w.rem);
+    uint4 a;
+    a.x = expand_nibble(bits & 15);          a.y = expand_nibble((bits >> 4) & 15);
+    a.z = expand_nibble((bits >> 8) & 15);   a.w = expand_nibble((bits >> 12) & 15);
+    if (w.valid >= 16) store16(block + w.out, a);
+    else store_bytes(block + w.out, a, w.valid);
+}
+
+// The same window written in the (type, colour, state) encoding.  The one-hot stream holds,
+// per cell, the bits (wall, goal, empty); the typed bytes are
+//     type = 1*empty + 2*wall + 8*goal,  colour = 5*wall + 1*goal,  state = 0,
+// so bit planes 0..3 of the output bytes are picked from the stream bits of the same cell
+// one or two positions away, masked to the type / colour positions, expanded like the
+// plain stream and combined.  A cell never straddles two envs, so the bits needed beyond
+// the window come from the same records.
+__device__ __forceinline__ void consume_window_typed(const uint32_t *recs, const Window &w, int8_t *block)
+{
+    const uint32_t lo = recs[w.addr0], hi = recs[w.addr0 + 1], nx = recs[w.addr1];
+    const uint32_t prev = recs[w.addr0 > 0 ? w.addr0 - 1 : 0];
+    const uint32_t bits = __builtin_amdgcn_alignbit(hi, lo, w.sh) | (nx << w.rem);   // stream bits p, p+1, ...
+    const uint32_t below = w.sh ? (lo >> (w.sh - 1)) & 1u : prev >> 31;               // stream bit p-1
+    const uint32_t x = bits & 0xFFFFu, up1 = (bits >> 1) & 0xFFFFu, up2 = (bits >> 2) & 0xFFFFu;
+    const uint32_t down1 = ((bits << 1) | below) & 0xFFFFu;
+    const uint32_t p0 = (up2 & w.type_pos) | ((down1 | x) & w.colour_pos);   // empty -> 1; wall or goal -> colour bit 0
+    const uint32_t p1 = x & w.type_pos;                                      // wall -> type 2
+    const uint32_t p2 = down1 & w.colour_pos;                                // wall -> colour 4 (+1 = grey 5)
+    const uint32_t p3 = up1 & w.type_pos;                                    // goal -> type 8
+    uint32_t out[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int sh = 4 * q;
+        out[q] = expand_nibble((p0 >> sh) & 15) | (expand_nibble((p1 >> sh) & 15) << 1) |
+                 (expand_nibble((p2 >> sh) & 15) << 2) | (expand_nibble((p3 >> sh) & 15) << 3);
+    }
+    const uint4 a = make_uint4(out[0], out[1], out[2], out[3]);
+    if (w.valid >= 16) store16(block + w.out, a);
+    else store_bytes(block + w.out, a, w.valid);
+}
+
+// Which cells of the view are seen (occluded view): rows are settled from the agent's row
+// outwards as K-bit masks.  Seen cells spread sideways through cells that are not walls (a
+// seen wall spreads nothing), then every seen non-wall cell makes the three cells touching
+// it in the next row ahead seen.  The agent's own cell spreads whatever it holds.  Returns
+// the masks packed like the view bits (row r at bit K*(r % RPD) of dword r / RPD).
+template <int K>
+__device__ __forceinline__ void visible_cells(const uint32_t (&vw)[View<K, 64>::WV],
+                                              uint32_t (&seenw)[View<K, 64>::WV])
+{
+    using V = View<K, 64>;
+    constexpr uint32_t all = (1u << K) - 1;
+#pragma unroll
+    for (int q = 0; q < V::WV; ++q) seenw[q] = 0;
+    uint32_t from_below = 1u << (K / 2);
+#pragma unroll
+    for (int r = K - 1; r >= 0; --r) {
+        const uint32_t wall = (vw[r / V::RPD] >> (K * (r % V::RPD))) & all;
+        uint32_t open = ~wall & all;
+        if (r == K - 1) open |= 1u << (K / 2);
+        uint32_t seen = from_below;
+#pragma unroll
+        for (int it = 1; it < K; ++it) {
+            const uint32_t src = seen & open;
+            seen |= ((src << 1) | (src >> 1)) & all;
+        }
+        const uint32_t src = seen & open;
+        from_below = (src | (src << 1) | (src >> 1)) & all;
+        seenw[r / V::RPD] |= seen << (K * (r % V::RPD));
+    }
+}
+
+template <int K>
+__device__ __forceinline__ void fill_lut(uint32_t *lut, int tid, int nthreads)
+{
+    using V = View<K, 64>;
+    for (int i = tid; i < V::LUTN; i += nthreads) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int c = 0; c < K; ++c) v |= (((i >> c) & 1) ? 1u : 4u) << (3 * c);
+        lut[i] = v;
+    }
+}
+
+// Copy the workgroup's envs' grids into LDS (all threads take part).
+template <int K, typename Word, int EPW>
+__device__ __forceinline__ void stage_grids(const StudentDev &p, uint32_t *lds, int tid, int nthreads,
+                                            int env0, int count)
+{
+    const int gs = Lds<K, Word, EPW>::grid_stride(p.SP);
+    uint32_t *base = lds + Lds<K, Word, EPW>::GRID0;
+    const int per_env = 4 * p.SP * WordOps<Word>::DW;
+    const uint32_t *src = (const uint32_t *)p.grids + (size_t)env0 * per_env;
+    int e = 0, o = tid;
+    while (o >= per_env) { o -= per_env; ++e; }
+    while (e < count) {
+        base[e * gs + o] = src[(size_t)e * per_env + o];
+        o += nthreads;
+        while (o >= per_env) { o -= per_env; ++e; }
+    }
+}
+
+// ------------------------------------------------------------------ rollout
+// Wall word of row `row` of heading frame `dir` of one env.
+template <typename Word, bool GRID_LDS>
+__device__ __forceinline__ Word wall_row(const uint32_t *lds_env, const Word *glob_env, int SP,
+                                         int dir, int row)
+{
+    const int r = (int)__umul24((unsigned)dir, (unsigned)SP) + row;
+    if (!GRID_LDS) return glob_env[r];
+    if (sizeof(Word) == 4) return (Word)lds_env[r];
+    return (Word)(((uint64_t)lds_env[2 * r + 1] << 32) | lds_env[2 * r]);
+}
+
+// Per-lane state of the dynamics stage (one env per lane).
+template <typename Word>
+struct DynState {
+    int xd, yd, d;            // pose in the frame of its heading
+    int gf, gc;               // goal relative to the agent: cells ahead, cells to the right
+    uint32_t t;               // steps since the episode began
+    // The word of the row just ahead of the agent (row yd-1 of its frame) decides whether a
+    // forward step is blocked.  It is fetched one step early: as soon as the action is known
+    // the row ahead of the pose the action leads to -- taking a forward step as successful --
+    // is requested (`spec`), and the choice between that word, the previous one (the forward
+    // step hit a wall: pose unchanged) and the start pose's word (episode ended) is made at
+    // the top of the next step, when the LDS read has long returned.
+    Word ahead_keep, spec;
+    bool use_start, use_keep;
+    uint32_t act_off, a_next; // action ring cursor (bytes) and the next step's action
+};
+
+template <typename Word>
+struct DynConst {
+    int sxd, syd, sd, sgf, sgc;        // start pose and the goal's offset from it
+    Word ahead_start;                  // row ahead of the start pose
+    uint32_t tmax;
+    int HPm1, WPm1, SP;
+    const uint32_t *lds_env;
+    const Word *glob_env;
+    const uint8_t *act_lds;            // this env's column of the action ring
+    uint32_t act_mask, act_row;        // ring size - 1 and row pitch, bytes
+};
+
+// One env step of the dynamics stage; publishes pose, goal offset and outcome to st[].
+template <typename Word, int EPW, bool GRID_LDS, bool SQUARE>
+__device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word> &c, uint32_t *st)
+{
+    const uint32_t a = s.a_next;
+    s.act_off = (s.act_off + c.act_row) & c.act_mask;
+    s.a_next = c.act_lds[s.act_off];        // next step's action (staged >= half a block ago)
+    const bool tl = (a == 0), tr = (a == 1), f2 = (a == 2);
+    int rows_m1 = c.WPm1, bits_m1 = c.WPm1;
+    if (!SQUARE) {
+        const bool odd = s.d & 1;
+        rows_m1 = odd ? c.HPm1 : c.WPm1;
+        bits_m1 = odd ? c.WPm1 : c.HPm1;
+    }
+    // pose the action leads to if a forward step succeeds; request its row ahead
+    const int nx = tl ? rows_m1 - s.yd : (tr ? s.yd : s.xd);
+    const int sy = tl ? s.xd : (tr ? bits_m1 - s.xd : s.yd - (f2 ? 1 : 0));
+    const int nd = (s.d + (tl ? 3 : 0) + (tr ? 1 : 0)) & 3;
+    const Word ahead = s.use_start ? c.ahead_start : (s.use_keep ? s.ahead_keep : s.spec);
+    s.spec = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, c.SP, nd, sy - 1);
+    // the wall test for the current pose
+    const int blocked = sizeof(Word) == 4 ? (int)__builtin_amdgcn_ubfe((uint32_t)ahead, s.xd, 1)
+                                          : (int)((ahead >> s.xd) & 1);
+    const bool stay = f2 & (blocked != 0);          // forward into a wall: nothing moves
+    const int fw = f2 ? (blocked ^ 1) : 0;
+    const int ny = stay ? s.yd : sy;
+    const uint32_t t1 = s.t + 1;
+    const int nf = tl ? -s.gc : (tr ? s.gc : s.gf - fw);
+    const int nc = tl ? s.gf : (tr ? -s.gf : s.gc);
+    const bool reached = ((nf | nc) == 0);
+    const bool fin = reached | (t1 >= c.tmax);
+    // out word: step count if the goal was reached, done in bit 31
+    const uint32_t out = (reached ? t1 : 0u) | (fin ? 0x80000000u : 0u);
+    s.xd = fin ? c.sxd : nx;
+    s.yd = fin ? c.syd : ny;
+    s.d = fin ? c.sd : nd;
+    s.t = fin ? 0u : t1;
+    s.gf = fin ? c.sgf : nf;
+    s.gc = fin ? c.sgc : nc;
+    s.use_start = fin;
+    s.use_keep = stay;
+    s.ahead_keep = ahead;
+    st[0] = (uint32_t)s.xd | ((uint32_t)s.yd << 8) | ((uint32_t)s.d << 16);
+    st[EPW] = (uint32_t)(s.gf & 0xFFFF) | ((uint32_t)s.gc << 16);
+    st[2 * EPW] = out;
+}
+
+// Each role runs its own loop over blocks of SPB steps; every wave passes exactly
+// ceil(n_steps / SPB) + 4 barriers.
+//   between barriers b and b+1:  dynamics builds block b   -> ST[b&1]
+//                                views    builds block b-1 -> VW[(b-1)&1]   (reads ST[(b-1)&1])
+//                                records  builds block b-2 -> REC[(b-2)&1]  (reads VW[(b-2)&1])
+//                                stores   drain  block b-3                  (read REC[(b-3)&1])
+// so no buffer is written while it is read.  The block loops are unrolled by two so
+// every LDS address is a lane constant plus an immediate.
+// The body of a role handles one block: it sees i0 (the block's first step), par (the
+// block's parity: its buffers), and `full` (a compile-time flag: every one of the SPB
+// steps exists; otherwise step i0+u must be tested against n_steps).  Bodies are written
+// in phases over the block's steps -- all reads, then all writes -- so that independent
+// steps overlap their LDS round trips.
+#define MAZE_STEP_ON(u) (full || i0 + (u) < n_steps)
+#define MAZE_FOR_EACH_BLOCK(...)                                                           \
+    for (int blk0 = 0; blk0 < n_steps; blk0 += 2 * SPB) {                                  \
+        _Pragma("unroll") for (int par = 0; par < 2; ++par) {                              \
+            const int i0 = blk0 + par * SPB;                                               \
+            if (i0 + SPB <= n_steps) {                                                     \
+                constexpr bool full = true;                                                \
+                { __VA_ARGS__; }                                                           \
+                __syncthreads();                                                           \
+            } else if (i0 < n_steps) {                                                     \
+                constexpr bool full = false;                                               \
+                { __VA_ARGS__; }                                                           \
+                __syncthreads();                                                           \
+            }                                                                              \
+        }                                                                                  \
+    }
+
+// MODE 0: the default observation.  MODE 1: the observation variants (p.obs_occlusion: unseen
+// cells cleared in the records stage; p.obs_encoding: typed bytes in the stores stage).
+// PARTIAL: the workgroup may hold fewer than EPW envs (the last envs of a batch, n_end - env0 of
+// them): idle lanes repeat env 0 of the workgroup and write nothing, pieces beyond the last
+// env's bytes are not stored.
+template <int K, typename Word, int EPW, bool GRID_LDS, bool SQUARE, int MODE = 0, bool PARTIAL = false>
+__global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
+    StudentDev p, int n_begin, int n_end, const int8_t *__restrict__ actions, int n_steps,
+    float *__restrict__ reward, uint8_t *__restrict__ done, int8_t *__restrict__ obs)
+{
+    using V = View<K, EPW>;
+    using L = Lds<K, Word, EPW>;
+    constexpr int NT = 64 * V::WAVES;
+    constexpr int ACT_BLOCK = V::ACT_BLOCK;
+    constexpr int UGV = step_group(K * WordOps<Word>::DW + 3, 40);   // views: wall rows + state
+    constexpr int UGR = step_group(K + V::WV + 2, 48);               // records: table words + view
+    extern __shared__ uint32_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int env0 = n_begin + blockIdx.x * EPW;     // n_begin: a multiple of 32 (16-byte pieces)
+    const int SP = p.SP, N = p.N;
+    const int count = PARTIAL ? min(EPW, n_end - env0) : EPW;       // envs of this workgroup
+    const int live_lanes = PARTIAL ? min((int)V::LA, count) : V::LA; // (PARTIAL: one wave per stage)
+    static_assert(!PARTIAL || V::NDYN == 1, "partly filled workgroups: 64 envs at most");
+
+    fill_lut<K>(lds + L::LUT, tid, NT);
+    if (GRID_LDS) stage_grids<K, Word, EPW>(p, lds, tid, NT, env0, count);
+
+    if (wave < V::NDYN) {
+        // ================================================================ dynamics
+        const bool active = lane < live_lanes;     // a wave serves LA envs
+        const int e = wave * 64 + (active ? lane : 0);   // env within the workgroup
+        const int n = env0 + e;
+        const int last = n_steps - 1;
+        DynState<Word> s;
+        DynConst<Word> c;
+        const uint32_t pose = p.pose[n], start = p.start[n];
+        s.xd = pose & 255; s.yd = (pose >> 8) & 255; s.d = (pose >> 16) & 3;
+        s.t = p.tcount[n];
+        c.sxd = start & 255; c.syd = (start >> 8) & 255; c.sd = (start >> 16) & 3;
+        // goal relative to the agent in the agent's own frame; turning rotates this vector,
+        // moving forward shortens gf
+        const uint32_t g_now = p.goalrot[4 * (size_t)n + s.d], g_start = p.goalrot[4 * (size_t)n + c.sd];
+        s.gf = s.yd - (int)(g_now >> 8); s.gc = (int)(g_now & 255) - s.xd;
+        c.sgf = c.syd - (int)(g_start >> 8); c.sgc = (int)(g_start & 255) - c.sxd;
+        c.tmax = (uint32_t)p.max_steps;
+        c.HPm1 = p.HP - 1; c.WPm1 = p.WP - 1; c.SP = SP;
+        c.lds_env = lds + L::GRID0 + e * (GRID_LDS ? L::grid_stride(SP) : 0);
+        c.glob_env = (const Word *)p.grids + (size_t)n * 4 * SP;
+        c.act_lds = (const uint8_t *)(lds + L::ACT) + e;
+        c.act_row = L::ACT_ROW;
+        c.act_mask = 2 * ACT_BLOCK * L::ACT_ROW - 1;
+        // actions: lane l of this wave stages the bytes of step block*ACT_BLOCK + l/ACT_LPR
+        // for 16 of the wave's envs (all 64 lanes stage, whatever LA is)
+        const int stage_row = lane / V::ACT_LPR;
+        const int stage_col = wave * 64 + 16 * (lane % V::ACT_LPR);
+        const int8_t *act_lane = actions + env0 + stage_col;
+        uint8_t *act_stage = (uint8_t *)(lds + L::ACT) + stage_row * L::ACT_ROW + stage_col;
+        // bytes of a row that exist from this lane's first column on (PARTIAL: may be < 16)
+        const int act_valid = PARTIAL ? N - (env0 + stage_col) : 16;
+        *(uint4 *)act_stage = load_actions<PARTIAL>(act_lane, stage_row, last, N, act_valid);
+        uint4 act_regs = load_actions<PARTIAL>(act_lane, ACT_BLOCK + stage_row, last, N, act_valid);
+        __syncthreads();                                             // barrier 0 (set-up)
+        c.ahead_start = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, SP, c.sd, c.syd - 1);
+        s.ahead_keep = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, SP, s.d, s.yd - 1);
+        s.spec = s.ahead_keep;
+        s.use_start = false; s.use_keep = true;
+        s.act_off = 0;
+        s.a_next = c.act_lds[0];
+        uint32_t *st_e = lds + L::ST + e;
+        MAZE_FOR_EACH_BLOCK(
+            _Pragma("unroll") for (int u = 0; u < SPB; ++u) {
+                const int i = i0 + u;
+                if (!MAZE_STEP_ON(u)) continue;
+                if (active)
+                    dyn_step<Word, EPW, GRID_LDS, SQUARE>(s, c, st_e + (par * SPB + u) * L::ST_SIZE);
+                // stage the next block of actions half way through the current one
+                if ((i & (ACT_BLOCK - 1)) == ACT_BLOCK / 2) {
+                    const int nb = i / ACT_BLOCK + 1;
+                    *(uint4 *)(act_stage + (nb & 1) * (ACT_BLOCK * L::ACT_ROW)) = act_regs;
+                    act_regs = load_actions<PARTIAL>(act_lane, (nb + 1) * ACT_BLOCK + stage_row, last, N, act_valid);
+                }
+            })
+        if (active) {
+            p.pose[n] = (uint32_t)s.xd | ((uint32_t)s.yd << 8) | ((uint32_t)s.d << 16);
+            p.tcount[n] = s.t;
+        }
+        __syncthreads();
+        __syncthreads();
+        __syncthreads();
+    } else if (wave < 2 * V::NDYN) {
+        // =================================================================== views
+        const bool active = lane < live_lanes;
+        const int e = (wave - V::NDYN) * 64 + (active ? lane : 0);
+        const uint32_t *lds_env = lds + L::GRID0 + e * (GRID_LDS ? L::grid_stride(SP) : 0);
+        const Word *glob_env = (const Word *)p.grids + (size_t)(env0 + e) * 4 * SP;
+        __syncthreads();                                             // barrier 0 (set-up)
+        __syncthreads();                                             // block 0 published
+        MAZE_FOR_EACH_BLOCK(
+            if (active) {
+                _Pragma("unroll") for (int u0 = 0; u0 < SPB; u0 += UGV) {
+                    uint32_t pose[UGV], g[UGV], out[UGV];
+                    Word rows[UGV][K];
+                    _Pragma("unroll") for (int w = 0; w < UGV; ++w) if (MAZE_STEP_ON(u0 + w)) {
+                        const uint32_t *st = lds + L::ST + (par * SPB + u0 + w) * L::ST_SIZE + e;
+                        pose[w] = st[0]; g[w] = st[EPW]; out[w] = st[2 * EPW];
+                    }
+                    _Pragma("unroll") for (int w = 0; w < UGV; ++w) if (MAZE_STEP_ON(u0 + w))
+                        load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, SP, (pose[w] >> 16) & 3,
+                                                          (pose[w] >> 8) & 255, rows[w]);
+                    _Pragma("unroll") for (int w = 0; w < UGV; ++w) if (MAZE_STEP_ON(u0 + w)) {
+                        uint32_t vw[V::WV];
+                        pack_view<K, Word>(rows[w], pose[w] & 255, vw);
+                        uint32_t *v = lds + L::VW + (par * SPB + u0 + w) * L::VW_SIZE + e;
+                        _Pragma("unroll") for (int q = 0; q < V::WV; ++q) v[q * EPW] = vw[q];
+                        v[V::WV * EPW] = g[w];
+                        v[(V::WV + 1) * EPW] = out[w];
+                    }
+                }
+            })
+        __syncthreads();
+        __syncthreads();
+    } else if (wave < 3 * V::NDYN) {
+        // ================================================================= records
+        const bool active = lane < live_lanes;
+        const int e = (wave - 2 * V::NDYN) * 64 + (active ? lane : 0);
+        float *rw = reward + env0 + e;
+        uint8_t *dn = done + env0 + e;
+        const double slope = p.reward_slope;
+        // the zero dword that ends every record is written once
+        if (active)
+            for (int sl = 0; sl < 2 * SPB; ++sl) lds[L::REC + sl * L::REC_SIZE + e * V::REC + V::ND] = 0;
+        __syncthreads();                                             // barrier 0 (set-up)
+        __syncthreads();                                             // block 0 published
+        __syncthreads();                                             // block 0 viewed
+        MAZE_FOR_EACH_BLOCK(
+            if (active) {
+                _Pragma("unroll") for (int u0 = 0; u0 < SPB; u0 += UGR) {
+                    uint32_t vw[UGR][V::WV], g[UGR], out[UGR], piece[UGR][K];
+                    _Pragma("unroll") for (int w = 0; w < UGR; ++w) if (MAZE_STEP_ON(u0 + w)) {
+                        const uint32_t *v = lds + L::VW + (par * SPB + u0 + w) * L::VW_SIZE + e;
+                        _Pragma("unroll") for (int q = 0; q < V::WV; ++q) vw[w][q] = v[q * EPW];
+                        g[w] = v[V::WV * EPW]; out[w] = v[(V::WV + 1) * EPW];
+                    }
+                    _Pragma("unroll") for (int w = 0; w < UGR; ++w) if (MAZE_STEP_ON(u0 + w))
+                        record_lookup<K>(lds + L::LUT, vw[w], piece[w]);
+                    _Pragma("unroll") for (int w = 0; w < UGR; ++w) if (MAZE_STEP_ON(u0 + w)) {
+                        uint32_t D[V::ND];
+                        uint32_t *rec = lds + L::REC + (par * SPB + u0 + w) * L::REC_SIZE + e * V::REC;
+                        if (MODE == 1 && p.obs_occlusion) {
+                            uint32_t seenw[V::WV];
+                            visible_cells<K>(vw[w], seenw);
+                            mask_unseen<K>(lds + L::LUT, seenw, piece[w]);
+                            record_finish<K>(piece[w], vw[w], (int)(int16_t)(g[w] & 0xFFFF),
+                                             (int)g[w] >> 16, D, rec, seenw);
+                        } else
+                        record_finish<K>(piece[w], vw[w], (int)(int16_t)(g[w] & 0xFFFF), (int)g[w] >> 16,
+                                         D, rec);
+                        const uint32_t tr = out[w] & 0x7FFFFFFFu;
+                        rw[(size_t)(u0 + w) * N] = tr ? (float)(1.0 - (double)tr * slope) : 0.0f;
+                        dn[(size_t)(u0 + w) * N] = (uint8_t)(out[w] >> 31);
+                    }
+                }
+                rw += (size_t)SPB * N;
+                dn += (size_t)SPB * N;
+            })
+        __syncthreads();
+    } else {
+        // ================================================================== stores
+        const int cw = wave - 3 * V::NDYN;
+        constexpr int MYR = (V::ROUNDS + V::NC - 1) / V::NC;     // rounds per store wave, at most
+        Window win[MYR];
+#pragma unroll
+        for (int j = 0; j < MYR; ++j) {
+            win[j] = make_window<K, EPW>(lane, cw + j * V::NC);
+            if (PARTIAL) {
+                const int left = count * V::SB - (int)win[j].out;   // bytes of the block from this piece on
+                win[j].valid = min(16, left);
+                win[j].active = win[j].active && left > 0;
+            }
+        }
+        const size_t step_obs = (size_t)N * V::SB;
+        int8_t *out_block = obs + (size_t)env0 * V::SB;
+        __syncthreads();                                             // barrier 0 (set-up)
+        __syncthreads();                                             // block 0 published
+        __syncthreads();                                             // block 0 viewed
+        __syncthreads();                                             // block 0 recorded
+        MAZE_FOR_EACH_BLOCK(
+            _Pragma("unroll") for (int u = 0; u < SPB; ++u) if (MAZE_STEP_ON(u)) {
+                const uint32_t *rec = lds + L::REC + (par * SPB + u) * L::REC_SIZE;
+                _Pragma("unroll") for (int j = 0; j < MYR; ++j) {
+                    if (!win[j].active) continue;
+                    if (MODE == 1 && p.obs_encoding) consume_window_typed(rec, win[j], out_block + u * step_obs);
+                    else consume_window(rec, win[j], out_block + u * step_obs);
+                }
+            }
+            out_block += SPB * step_obs;)
+    }
+}
+
+// ------------------------------- observation of the state / one step + observation
+// One workgroup of REPW threads per REPW envs, no time loop: optionally advance every
+// env by one step (the call a policy loop makes: state in and out of global memory, wall
+// rows from the packed grids in L2), then produce the records and expand them.
+constexpr int REPW = 64;
+
+template <int K, typename Word, bool DO_STEP, int MODE = 0>
+__global__ __launch_bounds__(REPW) void k_step_render_tiled(
+    StudentDev p, const int8_t *__restrict__ actions, float *__restrict__ reward,
+    uint8_t *__restrict__ done, int8_t *__restrict__ obs)
+{
+    using V = View<K, REPW>;
+    using L = Lds<K, Word, REPW>;
+    extern __shared__ uint32_t lds[];
+    const int lane = threadIdx.x;
+    const int env0 = blockIdx.x * REPW;
+    const int n = env0 + lane;
+    fill_lut<K>(lds + L::LUT, lane, REPW);
+    __syncthreads();
+    const Word *glob_env = (const Word *)p.grids + (size_t)n * 4 * p.SP;
+    uint32_t pose = p.pose[n];
+    if (DO_STEP) {
+        const int a = actions[n];
+        const int xd0 = pose & 255, yd0 = (pose >> 8) & 255, d0 = (pose >> 16) & 3;
+        const bool blocked = (glob_env[d0 * p.SP + yd0 - 1] >> xd0) & 1;
+        pose = student_move(p, pose, a, blocked);
+        uint32_t t = p.tcount[n] + 1;
+        const bool reached = (pose & 0xFFFF) == p.goalrot[4 * (size_t)n + ((pose >> 16) & 3)];
+        const bool fin = reached || t >= (uint32_t)p.max_steps;
+        reward[n] = reached ? (float)(1.0 - (double)t * p.reward_slope) : 0.0f;
+        done[n] = fin ? 1 : 0;
+        if (fin) { pose = p.start[n]; t = 0; }
+        p.pose[n] = pose;
+        p.tcount[n] = t;
+    }
+    const int xd = pose & 255, yd = (pose >> 8) & 255, d = (pose >> 16) & 3;
+    Word rows[K];
+    load_view_rows<K, Word, false>(nullptr, glob_env, p.SP, d, yd, rows);
+    uint32_t vw[V::WV];
+    pack_view<K, Word>(rows, xd, vw);
+    const uint32_t g = p.goalrot[4 * (size_t)n + d];
+    uint32_t *rec = lds + L::REC + lane * V::REC;
+    if (MODE == 1 && p.obs_occlusion) {
+        uint32_t piece[K], D[V::ND], seenw[V::WV];
+        record_lookup<K>(lds + L::LUT, vw, piece);
+        visible_cells<K>(vw, seenw);
+        mask_unseen<K>(lds + L::LUT, seenw, piece);
+        record_finish<K>(piece, vw, yd - (int)(g >> 8), (int)(g & 255) - xd, D, rec, seenw);
+        rec[V::ND] = 0;
+    } else {
+        produce_record<K>(lds + L::LUT, rec, vw, yd - (int)(g >> 8), (int)(g & 255) - xd);
+    }
+    __syncthreads();
+    int8_t *block = obs + (size_t)env0 * V::SB;
+    for (int j = 0; j < V::ROUNDS; ++j) {
+        Window w = make_window<K, REPW>(lane, j);
+        if (!w.active) continue;
+        if (MODE == 1 && p.obs_encoding) consume_window_typed(lds + L::REC, w, block);
+        else consume_window(lds + L::REC, w, block);
+    }
+}
+
+constexpr size_t LDS_PER_CU = 160 * 1024;     // gfx950
+
+// Raise a kernel's dynamic LDS limit above the 64 KB default (remembered in *granted).
+template <typename Kernel>
+bool allow_large_lds(Kernel kernel, size_t bytes, size_t *granted)
+{
+    if (bytes <= 64 * 1024 || bytes <= *granted) return true;
+    if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)bytes) != hipSuccess)
+        return false;
+    *granted = bytes;
+    return true;
+}
+
+// Runs the rollout kernel on envs [n_begin, n_begin + EPW * (n_envs / EPW)) -- with PARTIAL on all
+// n_envs, the last workgroup partly filled -- and returns how many envs that is.
+template <int K, typename Word, int EPW, int MODE = 0, bool PARTIAL = false>
+int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d_actions, int n_steps,
+                   float *d_reward, uint8_t *d_done, int8_t *d_obs, hipStream_t st)
+{
+    using V = View<K, EPW>;
+    using L = Lds<K, Word, EPW>;
+    const StudentDev &p = ctx->dev;
+    const int groups = PARTIAL ? (n_envs + EPW - 1) / EPW : n_envs / EPW;
+    if (groups < 1) return 0;
+    const int n_end = PARTIAL ? n_begin + n_envs : n_begin + groups * EPW;
+    const bool grid_lds = L::bytes(p.SP, true) <= LDS_PER_CU - 1024;
+    const size_t shmem = L::bytes(p.SP, grid_lds);
+    const dim3 grid(groups), block(64 * V::WAVES);
+    // the square-grid flavour exists for the plain kernel only
+    constexpr bool PLAIN = MODE == 0 && !PARTIAL;
+    const bool square = p.HP == p.WP && PLAIN;
+    // largest LDS size granted so far, per kernel flavour and device (the attribute belongs to
+    // the kernel on one device); a race between host threads only repeats the call
+    static size_t granted_all[2][16] = {};
+    size_t *granted = &granted_all[0][ctx->device & 15];
+    constexpr int FLAVOUR_STRIDE = 16;
+    if (grid_lds && square) {
+        auto kern = k_student_rollout<K, Word, EPW, true, PLAIN, MODE, PARTIAL>;
+        if (!allow_large_lds(kern, shmem, granted)) return 0;
+        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
+                           d_done, d_obs);
+    } else if (grid_lds) {
+        auto kern = k_student_rollout<K, Word, EPW, true, false, MODE, PARTIAL>;
+        if (!allow_large_lds(kern, shmem, granted + FLAVOUR_STRIDE)) return 0;
+        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
+                           d_done, d_obs);
+    } else {
+        auto kern = k_student_rollout<K, Word, EPW, false, false, MODE, PARTIAL>;
+        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
+                           d_done, d_obs);
+    }
+    return n_end - n_begin;
+}
+
+// Envs per workgroup: the largest of 128 / 64 / 32 whose grids fit in LDS and that still
+// gives every CU a workgroup; small batches take 32 so that more CUs take part.
+template <int K, typename Word>
+int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
+             uint8_t *d_done, int8_t *d_obs, hipStream_t st)
+{
+    const StudentDev &p = ctx->dev;
+    if (n_steps <= 1) {
+        // render only (0) or the single step of a policy loop (1): one light launch
+        if (p.N < REPW) return 0;
+        const size_t shmem_render = Lds<K, Word, REPW>::bytes(p.SP, false);
+        const dim3 grid(p.N / REPW), block(REPW);
+        const bool variant = p.obs_encoding || p.obs_occlusion;
+        if (n_steps == 0 && !variant)
+            hipLaunchKernelGGL((k_step_render_tiled<K, Word, false>), grid, block, shmem_render, st, p,
+                               d_actions, d_reward, d_done, d_obs);
+        else if (n_steps == 0)
+            hipLaunchKernelGGL((k_step_render_tiled<K, Word, false, 1>), grid, block, shmem_render, st, p,
+                               d_actions, d_reward, d_done, d_obs);
+        else if (!variant)
+            hipLaunchKernelGGL((k_step_render_tiled<K, Word, true>), grid, block, shmem_render, st, p,
+                               d_actions, d_reward, d_done, d_obs);
+        else
+            hipLaunchKernelGGL((k_step_render_tiled<K, Word, true, 1>), grid, block, shmem_render, st, p,
+                               d_actions, d_reward, d_done, d_obs);
+        return REPW * (p.N / REPW);
+    }
+    if (p.obs_encoding || p.obs_occlusion) {     // observation variants: 64 envs per workgroup, then the rest
+        int done_envs = launch_rollout<K, Word, 64, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done,
+                                                       d_obs, st);
+        if (done_envs < p.N)
+            done_envs += launch_rollout<K, Word, 32, 1, true>(ctx, done_envs, p.N - done_envs, d_actions,
+                                                              n_steps, d_reward, d_done, d_obs, st);
+        return done_envs;
+    }
+    int covered = 0;
+#ifdef MAZE_FORCE_EPW
+    covered = launch_rollout<K, Word, MAZE_FORCE_EPW>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
+#else
+    const int cus = 256;
+    const bool fit128 = Lds<K, Word, 128>::bytes(p.SP, true) <= LDS_PER_CU - 1024;
+    const bool fit64 = Lds<K, Word, 64>::bytes(p.SP, true) <= LDS_PER_CU - 1024;
+    if (p.N >= 128 * cus && fit128)
+        covered = launch_rollout<K, Word, 128>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
+    else if (p.N >= 64 * cus && fit64)
+        covered = launch_rollout<K, Word, 64>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
+#endif
+    // Small batches, and the envs left over by a large workgroup size, go to workgroups of 32
+    // in one more launch on the same stream; if their number is not a multiple of 32 the
+    // flavour whose last workgroup may be partly filled takes them all.
+    const int rest = p.N - covered;
+    if (rest > 0 && rest % 32 == 0)
+        covered += launch_rollout<K, Word, 32>(ctx, covered, rest, d_actions, n_steps, d_reward, d_done,
+                                               d_obs, st);
+    else if (rest > 0)
+        covered += launch_rollout<K, Word, 32, 0, true>(ctx, covered, rest, d_actions, n_steps, d_reward,
+                                                        d_done, d_obs, st);
+    return covered;
+}
+
+// Word size dispatch for one view size; the translation units maze_student_tiled_k*.hip wrap it.
+template <int K>
+int launch_view_size(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
+                     uint8_t *d_done, int8_t *d_obs, hipStream_t st)
+{
+    return ctx->word64 ? launch_k<K, uint64_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st)
+                       : launch_k<K, uint32_t>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
+}
+
+}  // namespace

@@ -199,6 +199,37 @@ def test_rollout_lengths_around_block_boundaries(T):
         assert_state_equal(env, o)
 
 
+@pytest.mark.parametrize("k,S", [(3, 9), (5, 13), (7, 35)])
+def test_partly_filled_last_workgroup(k, S):
+    """Batch sizes that leave 1..31 envs for the last workgroup: its cut 16-byte pieces, its
+    idle lanes and the action bytes beyond the batch."""
+    for N in (1, 7, 8, 15, 17, 24, 31, 32 + 5, 64 + 29):
+        w = wl.student_random(f"partial-N{N}-k{k}", 9000 + 31 * N + k, N=N, H=S, W=S, view=k, T=21,
+                              n_walls=S * S // 4, max_steps=9)
+        note(w.name)
+        run_fused(w)
+
+
+def test_editor_partly_filled_last_workgroup():
+    for N, H, W in ((32768 + 8, 13, 13), (129, 13, 13), (7, 3, 2), (200, 6, 9)):
+        rng = np.random.default_rng(N)
+        nw, T = 5, 9
+        actions = rng.integers(0, H * W, size=(T, N), dtype=np.int32)
+        dirs = rng.integers(0, 4, size=N, dtype=np.int8)
+        note(f"editor partial N={N} {H}x{W}")
+        ed = binding.EditorEnv(N, H, W, nw, device=DEV)
+        ed.reset(to_gpu(dirs))
+        oe = oracle.EditorOracle(N, H, W, nw)
+        oe.reset(dirs)
+        obs, t, d = ed.step(to_gpu(actions))
+        oobs, ot, od = oe.step(actions, T)
+        assert (obs.cpu().numpy() == oobs).all()
+        assert (t.cpu().numpy() == ot).all() and (d.cpu().numpy() == od).all()
+        lv = oe.get_levels()
+        for a, b in zip(ed.get_levels(), (lv.walls, lv.agent_xy, lv.agent_dir, lv.goal_xy)):
+            assert (a.cpu().numpy() == b).all()
+
+
 def test_outputs_larger_than_4_gib():
     """262144 envs x 256 steps: 5.0e9 obs bytes, so every offset needs 64 bits (eight times config 3)."""
     w = wl.student_random("big", 31337, N=262144, T=256, n_walls=50)
@@ -214,8 +245,9 @@ def test_outputs_larger_than_4_gib():
     assert_state_equal(env, o)
 
 
-def test_unaligned_buffers_take_the_per_cell_path():
-    """Views into larger tensors whose addresses are not 16-byte aligned still give exact results."""
+def test_unaligned_buffers():
+    """Views into larger tensors whose addresses are not 16-byte aligned (the 16-byte stores and
+    loads of the tiled kernels then hit unaligned addresses) still give exact results."""
     w = wl.student_random("unaligned", 66, N=640, T=40, n_walls=50, max_steps=30)
     env, o = gpu_student(w), cpu_student(w)
     N, k, T = w.N, w.view, w.T
