@@ -14,6 +14,7 @@
 // Two barriers per step separate editing from reading; the edit phase is a few
 // dozen instructions, the store phase moves 3*H*W*128 bytes.
 #include "maze_internal.h"
+#include "maze_store_device.h"
 
 namespace {
 
@@ -21,11 +22,6 @@ constexpr int EPW = 128;        // envs per workgroup
 constexpr int NE = EPW / 64;    // edit waves
 constexpr int NS = 12;          // store waves
 constexpr int NWAVES = NE + NS;
-
-__device__ __forceinline__ uint32_t expand_nibble(uint32_t nib)
-{
-    return (nib * 0x00204081u) & 0x01010101u;
-}
 
 __device__ __forceinline__ void lds_set_bit(uint32_t *rec, int bit)
 {
@@ -35,30 +31,6 @@ __device__ __forceinline__ void lds_set_bit(uint32_t *rec, int bit)
 __device__ __forceinline__ void lds_clear_bit(uint32_t *rec, int bit)
 {
     atomicAnd(&rec[bit >> 5], ~(1u << (bit & 31)));
-}
-
-// The first `valid` (< 16) bytes of a piece: 8, 4, 2 and 1 bytes as the bits of `valid` say.
-__device__ __forceinline__ void store_tail(int8_t *dst, const uint4 &v, int valid)
-{
-    uint64_t cur = ((uint64_t)v.y << 32) | v.x;
-    if (valid & 8) {
-        __builtin_memcpy(dst, &cur, 8);
-        dst += 8;
-        cur = ((uint64_t)v.w << 32) | v.z;
-    }
-    if (valid & 4) {
-        const uint32_t w = (uint32_t)cur;
-        __builtin_memcpy(dst, &w, 4);
-        dst += 4;
-        cur >>= 32;
-    }
-    if (valid & 2) {
-        const uint16_t h = (uint16_t)cur;
-        __builtin_memcpy(dst, &h, 2);
-        dst += 2;
-        cur >>= 16;
-    }
-    if (valid & 1) *dst = (int8_t)cur;
 }
 
 __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
@@ -145,8 +117,8 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
                 v.x = expand_nibble(bits & 15);          v.y = expand_nibble((bits >> 4) & 15);
                 v.z = expand_nibble((bits >> 8) & 15);   v.w = expand_nibble((bits >> 12) & 15);
                 const int valid = block_bytes - 16 * m;
-                if (valid >= 16) __builtin_memcpy(out_block + 16 * (size_t)m, &v, 16);   // any alignment: one dwordx4 store
-                else store_tail(out_block + 16 * (size_t)m, v, valid);
+                if (valid >= 16) store16(out_block + 16 * (size_t)m, v);
+                else store_bytes(out_block + 16 * (size_t)m, v, valid);
                 bs += adv_r;
                 e0 += adv_q;
                 if (bs >= SB) { bs -= SB; e0 += 1; }

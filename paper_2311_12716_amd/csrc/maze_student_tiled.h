@@ -30,6 +30,7 @@
 #pragma once
 
 #include "maze_internal.h"
+#include "maze_store_device.h"
 #include "maze_student_device.h"
 
 // Compile-time knobs (overridable for measurements).
@@ -76,51 +77,6 @@ struct View {
     static_assert((EPW * SB) % 16 == 0, "a step's chunk must be a whole number of 16-byte pieces");
 };
 
-// 16-byte global accesses at addresses of any alignment (a batch size or a buffer offset that
-// is not a multiple of 16 shifts every step's block): a plain 16-byte copy, which compiles to
-// one dwordx4 instruction on this target whatever the alignment.
-__device__ __forceinline__ void store16(int8_t *dst, const uint4 &v) { __builtin_memcpy(dst, &v, 16); }
-__device__ __forceinline__ uint4 load16(const int8_t *src)
-{
-    uint4 v;
-    __builtin_memcpy(&v, src, 16);
-    return v;
-}
-
-// The same for a piece of which only the first `valid` (< 16) bytes exist (the last, partly
-// filled workgroup of a batch).
-__device__ __forceinline__ void store_bytes(int8_t *dst, const uint4 &v, int valid)
-{
-    // 8, 4, 2 and 1 bytes as the bits of `valid` say: at most four stores
-    uint64_t cur = ((uint64_t)v.y << 32) | v.x;
-    if (valid & 8) {
-        __builtin_memcpy(dst, &cur, 8);
-        dst += 8;
-        cur = ((uint64_t)v.w << 32) | v.z;
-    }
-    if (valid & 4) {
-        const uint32_t w = (uint32_t)cur;
-        __builtin_memcpy(dst, &w, 4);
-        dst += 4;
-        cur >>= 32;
-    }
-    if (valid & 2) {
-        const uint16_t h = (uint16_t)cur;
-        __builtin_memcpy(dst, &h, 2);
-        dst += 2;
-        cur >>= 16;
-    }
-    if (valid & 1) *dst = (int8_t)cur;
-}
-__device__ __forceinline__ uint4 load_bytes(const int8_t *src, int valid)
-{
-    uint32_t w[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int b = 0; b < 16; ++b)
-        if (b < valid) w[b >> 2] |= (uint32_t)(uint8_t)src[b] << (8 * (b & 3));
-    return make_uint4(w[0], w[1], w[2], w[3]);
-}
-
 // 16 action bytes of one step (row clamped to the last step), from a lane's first column on.
 template <bool PARTIAL>
 __device__ __forceinline__ uint4 load_actions(const int8_t *act_lane, int row, int last, int N, int valid)
@@ -129,12 +85,6 @@ __device__ __forceinline__ uint4 load_actions(const int8_t *act_lane, int row, i
     return (!PARTIAL || valid >= 16) ? load16(src) : load_bytes(src, valid);
 }
 
-// 4 stream bits -> 4 bytes (bit j -> byte j).  The four shifted copies do not
-// overlap, so the multiply carries nothing.
-__device__ __forceinline__ uint32_t expand_nibble(uint32_t nib)
-{
-    return (nib * 0x00204081u) & 0x01010101u;
-}
 
 template <typename Word> struct WordOps;
 template <> struct WordOps<uint32_t> { static constexpr int DW = 1; };
