@@ -71,6 +71,22 @@ def test_create_rejects_bad_arguments_before_touching_the_gpu(lib):
     assert lib.compute_gae(256, 256, 256, 0, 1, 0.9, 0.9, 256, None, None) == -1
 
 
+def test_level_tools_reject_bad_arguments_before_touching_the_gpu(lib):
+    u64 = ctypes.c_uint64
+    assert lib.maze_level_metrics(None, 256, 256, None) == -2
+    assert lib.maze_set_obs_mode(None, 0, 0) == -2
+    assert lib.editor_set_levels(None, 256, 256, 256, 256, None) == -2
+    assert lib.editor_random_levels(None, u64(1), u64(0), None) == -2
+    assert lib.editor_mutate_levels(None, u64(1), u64(0), 3, None) == -2
+    assert lib.replay_scores(None, 256, 256, 256, 4, 4, 0.99, None, 256, 256, 256, None) == -2
+    assert lib.replay_scores(256, 256, 256, 256, 0, 4, 0.99, None, 256, 256, 256, None) == -1
+    assert lib.replay_distribution(None, 256, 8, 0, 1, 0.3, 0.3, 256, None) == -2
+    assert lib.replay_distribution(256, 256, 0, 0, 1, 0.3, 0.3, 256, None) == -1       # K
+    assert lib.replay_distribution(256, 256, 8, 0, 1, 0.0, 0.3, 256, None) == -1       # temperature
+    assert lib.replay_distribution(256, 256, 8, 0, 1, 0.3, 1.5, 256, None) == -1       # staleness
+    assert lib.replay_distribution(256, 256, 1 << 20, 0, 1, 0.3, 0.3, 256, None) == -3  # K too large
+
+
 def test_strerror_names_every_code(lib):
     seen = {lib.maze_strerror(c) for c in (0, -1, -2, -3, -4)}
     assert len(seen) == 5 and all(s for s in seen)
