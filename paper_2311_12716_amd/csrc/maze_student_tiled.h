@@ -98,7 +98,7 @@ struct Lds {
     static constexpr int LUT = 0;                                  // [LUTN]
     static constexpr int ACT = LUT + V::LUTN;                      // [2][ACT_BLOCK][EPW] action bytes
     static constexpr int ACT_ROW = EPW;                            // bytes per step
-    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][3][EPW] pose, goal offset, out
+    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][3][EPW] position, goal offset, outcome + heading
     static constexpr int ST_SIZE = 3 * EPW;
     static constexpr int VW = ST + 2 * SPB * ST_SIZE;              // [2][SPB][WV+2][EPW] view bits, goal, out
     static constexpr int VW_SIZE = (V::WV + 2) * EPW;
@@ -397,11 +397,18 @@ __device__ __forceinline__ Word wall_row(const uint32_t *lds_env, const Word *gl
     return (Word)(((uint64_t)lds_env[2 * r + 1] << 32) | lds_env[2 * r]);
 }
 
+// Two 16-bit numbers in one register; arithmetic on them compiles to packed instructions
+// (one multiply-add turns a pair, the swap of its halves is an operand modifier).
+typedef short pair16 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ pair16 as_pair(uint32_t v) { return __builtin_bit_cast(pair16, v); }
+__device__ __forceinline__ uint32_t as_word(pair16 v) { return __builtin_bit_cast(uint32_t, v); }
+
 // Per-lane state of the dynamics stage (one env per lane).
 template <typename Word>
 struct DynState {
-    int xd, yd, d;            // pose in the frame of its heading
-    int gf, gc;               // goal relative to the agent: cells ahead, cells to the right
+    uint32_t pos;             // Xd | Yd << 16: position in the frame of the heading
+    uint32_t goal;            // goal relative to the agent: cells ahead | cells to the right << 16
+    int d;                    // heading
     uint32_t t;               // steps since the episode began
     // The word of the row just ahead of the agent (row yd-1 of its frame) decides whether a
     // forward step is blocked.  It is fetched one step early: as soon as the action is known
@@ -416,7 +423,8 @@ struct DynState {
 
 template <typename Word>
 struct DynConst {
-    int sxd, syd, sd, sgf, sgc;        // start pose and the goal's offset from it
+    uint32_t start_pos, start_goal;    // start position and the goal's offset from it, packed as above
+    int sd;                            // start heading
     Word ahead_start;                  // row ahead of the start pose
     uint32_t tmax;
     int HPm1, WPm1, SP;
@@ -426,7 +434,16 @@ struct DynConst {
     uint32_t act_mask, act_row;        // ring size - 1 and row pitch, bytes
 };
 
-// One env step of the dynamics stage; publishes pose, goal offset and outcome to st[].
+// Dynamics stage -> views stage, three dwords per env and step:
+//   position (Xd | Yd << 16), goal offset (ahead | right << 16),
+//   outcome: step count if the goal was reached (else 0) | heading << 29 | done << 31.
+constexpr uint32_t ST_HEADING_SHIFT = 29;
+constexpr uint32_t ST_OUTCOME_MASK = ~(3u << ST_HEADING_SHIFT);
+
+// One env step of the dynamics stage; publishes position, goal offset and outcome to st[].
+// Position and goal offset are pairs of 16-bit numbers: a right turn maps (Xd,Yd) to
+// (Yd, bits-1-Xd) and the goal vector (ahead, right) to (right, -ahead), a left turn to
+// (rows-1-Yd, Xd) and (-right, ahead) -- each one packed multiply-add of the swapped pair.
 template <typename Word, int EPW, bool GRID_LDS, bool SQUARE>
 __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word> &c, uint32_t *st)
 {
@@ -440,37 +457,39 @@ __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word>
         rows_m1 = odd ? c.HPm1 : c.WPm1;
         bits_m1 = odd ? c.WPm1 : c.HPm1;
     }
-    // pose the action leads to if a forward step succeeds; request its row ahead
-    const int nx = tl ? rows_m1 - s.yd : (tr ? s.yd : s.xd);
-    const int sy = tl ? s.xd : (tr ? bits_m1 - s.xd : s.yd - (f2 ? 1 : 0));
+    // position the action leads to if a forward step succeeds; request its row ahead
+    const pair16 pos = as_pair(s.pos), swapped = pos.yx;
+    const pair16 right = swapped * (pair16){1, -1} + (pair16){0, (short)bits_m1};
+    const pair16 left = swapped * (pair16){-1, 1} + (pair16){(short)rows_m1, 0};
+    const pair16 ahead_pos = pos - (pair16){0, (short)(f2 ? 1 : 0)};
+    pair16 next = tr ? right : ahead_pos;
+    next = tl ? left : next;
     const int nd = (s.d + (tl ? 3 : 0) + (tr ? 1 : 0)) & 3;
     const Word ahead = s.use_start ? c.ahead_start : (s.use_keep ? s.ahead_keep : s.spec);
-    s.spec = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, c.SP, nd, sy - 1);
+    s.spec = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, c.SP, nd, (int)(as_word(next) >> 16) - 1);
     // the wall test for the current pose
-    const int blocked = sizeof(Word) == 4 ? (int)__builtin_amdgcn_ubfe((uint32_t)ahead, s.xd, 1)
-                                          : (int)((ahead >> s.xd) & 1);
+    const int xd = (int)(s.pos & 0xFFFFu);
+    const int blocked = sizeof(Word) == 4 ? (int)__builtin_amdgcn_ubfe((uint32_t)ahead, xd, 1)
+                                          : (int)((ahead >> xd) & 1);
     const bool stay = f2 & (blocked != 0);          // forward into a wall: nothing moves
     const int fw = f2 ? (blocked ^ 1) : 0;
-    const int ny = stay ? s.yd : sy;
+    const uint32_t moved = stay ? s.pos : as_word(next);
     const uint32_t t1 = s.t + 1;
-    const int nf = tl ? -s.gc : (tr ? s.gc : s.gf - fw);
-    const int nc = tl ? s.gf : (tr ? -s.gf : s.gc);
-    const bool reached = ((nf | nc) == 0);
+    const pair16 goal = as_pair(s.goal), gswapped = goal.yx;
+    pair16 ngoal = tr ? gswapped * (pair16){1, -1} : goal - (pair16){(short)fw, 0};
+    ngoal = tl ? gswapped * (pair16){-1, 1} : ngoal;
+    const bool reached = as_word(ngoal) == 0;
     const bool fin = reached | (t1 >= c.tmax);
-    // out word: step count if the goal was reached, done in bit 31
-    const uint32_t out = (reached ? t1 : 0u) | (fin ? 0x80000000u : 0u);
-    s.xd = fin ? c.sxd : nx;
-    s.yd = fin ? c.syd : ny;
+    s.pos = fin ? c.start_pos : moved;
+    s.goal = fin ? c.start_goal : as_word(ngoal);
     s.d = fin ? c.sd : nd;
     s.t = fin ? 0u : t1;
-    s.gf = fin ? c.sgf : nf;
-    s.gc = fin ? c.sgc : nc;
     s.use_start = fin;
     s.use_keep = stay;
     s.ahead_keep = ahead;
-    st[0] = (uint32_t)s.xd | ((uint32_t)s.yd << 8) | ((uint32_t)s.d << 16);
-    st[EPW] = (uint32_t)(s.gf & 0xFFFF) | ((uint32_t)s.gc << 16);
-    st[2 * EPW] = out;
+    st[0] = s.pos;
+    st[EPW] = s.goal;
+    st[2 * EPW] = (reached ? t1 : 0u) | ((uint32_t)s.d << ST_HEADING_SHIFT) | (fin ? 0x80000000u : 0u);
 }
 
 // Each role runs its own loop over blocks of SPB steps; every wave passes exactly
@@ -540,14 +559,18 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         DynState<Word> s;
         DynConst<Word> c;
         const uint32_t pose = p.pose[n], start = p.start[n];
-        s.xd = pose & 255; s.yd = (pose >> 8) & 255; s.d = (pose >> 16) & 3;
+        const int xd0 = pose & 255, yd0 = (pose >> 8) & 255, sxd = start & 255, syd = (start >> 8) & 255;
+        s.pos = (uint32_t)xd0 | ((uint32_t)yd0 << 16);
+        s.d = (pose >> 16) & 3;
         s.t = p.tcount[n];
-        c.sxd = start & 255; c.syd = (start >> 8) & 255; c.sd = (start >> 16) & 3;
+        c.start_pos = (uint32_t)sxd | ((uint32_t)syd << 16);
+        c.sd = (start >> 16) & 3;
         // goal relative to the agent in the agent's own frame; turning rotates this vector,
-        // moving forward shortens gf
+        // moving forward shortens its first component
         const uint32_t g_now = p.goalrot[4 * (size_t)n + s.d], g_start = p.goalrot[4 * (size_t)n + c.sd];
-        s.gf = s.yd - (int)(g_now >> 8); s.gc = (int)(g_now & 255) - s.xd;
-        c.sgf = c.syd - (int)(g_start >> 8); c.sgc = (int)(g_start & 255) - c.sxd;
+        s.goal = (uint32_t)((yd0 - (int)(g_now >> 8)) & 0xFFFF) | ((uint32_t)((int)(g_now & 255) - xd0) << 16);
+        c.start_goal = (uint32_t)((syd - (int)(g_start >> 8)) & 0xFFFF) |
+                       ((uint32_t)((int)(g_start & 255) - sxd) << 16);
         c.tmax = (uint32_t)p.max_steps;
         c.HPm1 = p.HP - 1; c.WPm1 = p.WP - 1; c.SP = SP;
         c.lds_env = lds + L::GRID0 + e * (GRID_LDS ? L::grid_stride(SP) : 0);
@@ -566,8 +589,8 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         *(uint4 *)act_stage = load_actions<PARTIAL>(act_lane, stage_row, last, N, act_valid);
         uint4 act_regs = load_actions<PARTIAL>(act_lane, ACT_BLOCK + stage_row, last, N, act_valid);
         __syncthreads();                                             // barrier 0 (set-up)
-        c.ahead_start = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, SP, c.sd, c.syd - 1);
-        s.ahead_keep = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, SP, s.d, s.yd - 1);
+        c.ahead_start = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, SP, c.sd, syd - 1);
+        s.ahead_keep = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, SP, s.d, yd0 - 1);
         s.spec = s.ahead_keep;
         s.use_start = false; s.use_keep = true;
         s.act_off = 0;
@@ -587,7 +610,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                 }
             })
         if (active) {
-            p.pose[n] = (uint32_t)s.xd | ((uint32_t)s.yd << 8) | ((uint32_t)s.d << 16);
+            p.pose[n] = (s.pos & 255u) | ((s.pos >> 16) << 8) | ((uint32_t)s.d << 16);
             p.tcount[n] = s.t;
         }
         __syncthreads();
@@ -611,15 +634,16 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                         pose[w] = st[0]; g[w] = st[EPW]; out[w] = st[2 * EPW];
                     }
                     _Pragma("unroll") for (int w = 0; w < UGV; ++w) if (MAZE_STEP_ON(u0 + w))
-                        load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, SP, (pose[w] >> 16) & 3,
-                                                          (pose[w] >> 8) & 255, rows[w]);
+                        load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, SP,
+                                                          (out[w] >> ST_HEADING_SHIFT) & 3, pose[w] >> 16,
+                                                          rows[w]);
                     _Pragma("unroll") for (int w = 0; w < UGV; ++w) if (MAZE_STEP_ON(u0 + w)) {
                         uint32_t vw[V::WV];
-                        pack_view<K, Word>(rows[w], pose[w] & 255, vw);
+                        pack_view<K, Word>(rows[w], pose[w] & 0xFFFF, vw);
                         uint32_t *v = lds + L::VW + (par * SPB + u0 + w) * L::VW_SIZE + e;
                         _Pragma("unroll") for (int q = 0; q < V::WV; ++q) v[q * EPW] = vw[q];
                         v[V::WV * EPW] = g[w];
-                        v[(V::WV + 1) * EPW] = out[w];
+                        v[(V::WV + 1) * EPW] = out[w] & ST_OUTCOME_MASK;
                     }
                 }
             })
