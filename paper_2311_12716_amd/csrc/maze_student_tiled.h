@@ -476,8 +476,12 @@ __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word>
     const uint32_t moved = stay ? s.pos : as_word(next);
     const uint32_t t1 = s.t + 1;
     const pair16 goal = as_pair(s.goal), gswapped = goal.yx;
-    pair16 ngoal = tr ? gswapped * (pair16){1, -1} : goal - (pair16){(short)fw, 0};
-    ngoal = tl ? gswapped * (pair16){-1, 1} : ngoal;
+    // (all three alternatives first, then plain selects: a conditional expression with work in
+    // its arms compiles to a branch)
+    const pair16 goal_right = gswapped * (pair16){1, -1}, goal_left = gswapped * (pair16){-1, 1};
+    const pair16 goal_ahead = goal - (pair16){(short)fw, 0};
+    pair16 ngoal = tr ? goal_right : goal_ahead;
+    ngoal = tl ? goal_left : ngoal;
     const bool reached = as_word(ngoal) == 0;
     const bool fin = reached | (t1 >= c.tmax);
     s.pos = fin ? c.start_pos : moved;
@@ -538,6 +542,10 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     constexpr int ACT_BLOCK = V::ACT_BLOCK;
     constexpr int UGV = step_group(K * WordOps<Word>::DW + 3, 40);   // views: wall rows + state
     constexpr int UGR = step_group(K + V::WV + 2, 48);               // records: table words + view
+    // steps per pass of a views / records wave: two when the wave would be half empty
+    constexpr int UPL = (V::LA == 32 && SPB % 2 == 0) ? 2 : 1;
+    constexpr int UGVP = UGV > SPB / UPL ? SPB / UPL : UGV;
+    constexpr int UGRP = UGR > SPB / UPL ? SPB / UPL : UGR;
     extern __shared__ uint32_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -600,8 +608,9 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
             _Pragma("unroll") for (int u = 0; u < SPB; ++u) {
                 const int i = i0 + u;
                 if (!MAZE_STEP_ON(u)) continue;
-                if (active)
-                    dyn_step<Word, EPW, GRID_LDS, SQUARE>(s, c, st_e + (par * SPB + u) * L::ST_SIZE);
+                // (idle lanes of a partly filled wave repeat env 0 of the workgroup: the same
+                // values to the same addresses; stepping all lanes keeps the flags plain masks)
+                dyn_step<Word, EPW, GRID_LDS, SQUARE>(s, c, st_e + (par * SPB + u) * L::ST_SIZE);
                 // stage the next block of actions half way through the current one
                 if ((i & (ACT_BLOCK - 1)) == ACT_BLOCK / 2) {
                     const int nb = i / ACT_BLOCK + 1;
@@ -618,29 +627,35 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         __syncthreads();
     } else if (wave < 2 * V::NDYN) {
         // =================================================================== views
-        const bool active = lane < live_lanes;
-        const int e = (wave - V::NDYN) * 64 + (active ? lane : 0);
+        // With 32 envs per workgroup the wave's upper half takes every other step of a block
+        // (UPL steps per pass), so the stage issues half the instructions per step.
+        const int half = UPL == 2 ? lane >> 5 : 0;
+        const int el = UPL == 2 ? (lane & 31) : lane;
+        const bool active = el < live_lanes;
+        const int e = (wave - V::NDYN) * 64 + (active ? el : 0);
         const uint32_t *lds_env = lds + L::GRID0 + e * (GRID_LDS ? L::grid_stride(SP) : 0);
         const Word *glob_env = (const Word *)p.grids + (size_t)(env0 + e) * 4 * SP;
+        const uint32_t *st_lane = lds + L::ST + half * L::ST_SIZE + e;
+        uint32_t *vw_lane = lds + L::VW + half * L::VW_SIZE + e;
         __syncthreads();                                             // barrier 0 (set-up)
         __syncthreads();                                             // block 0 published
         MAZE_FOR_EACH_BLOCK(
             if (active) {
-                _Pragma("unroll") for (int u0 = 0; u0 < SPB; u0 += UGV) {
-                    uint32_t pose[UGV], g[UGV], out[UGV];
-                    Word rows[UGV][K];
-                    _Pragma("unroll") for (int w = 0; w < UGV; ++w) if (MAZE_STEP_ON(u0 + w)) {
-                        const uint32_t *st = lds + L::ST + (par * SPB + u0 + w) * L::ST_SIZE + e;
+                _Pragma("unroll") for (int u0 = 0; u0 < SPB / UPL; u0 += UGVP) {
+                    uint32_t pose[UGVP], g[UGVP], out[UGVP];
+                    Word rows[UGVP][K];
+                    _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half)) {
+                        const uint32_t *st = st_lane + (par * SPB + (u0 + w) * UPL) * L::ST_SIZE;
                         pose[w] = st[0]; g[w] = st[EPW]; out[w] = st[2 * EPW];
                     }
-                    _Pragma("unroll") for (int w = 0; w < UGV; ++w) if (MAZE_STEP_ON(u0 + w))
+                    _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half))
                         load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, SP,
                                                           (out[w] >> ST_HEADING_SHIFT) & 3, pose[w] >> 16,
                                                           rows[w]);
-                    _Pragma("unroll") for (int w = 0; w < UGV; ++w) if (MAZE_STEP_ON(u0 + w)) {
+                    _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half)) {
                         uint32_t vw[V::WV];
                         pack_view<K, Word>(rows[w], pose[w] & 0xFFFF, vw);
-                        uint32_t *v = lds + L::VW + (par * SPB + u0 + w) * L::VW_SIZE + e;
+                        uint32_t *v = vw_lane + (par * SPB + (u0 + w) * UPL) * L::VW_SIZE;
                         _Pragma("unroll") for (int q = 0; q < V::WV; ++q) v[q * EPW] = vw[q];
                         v[V::WV * EPW] = g[w];
                         v[(V::WV + 1) * EPW] = out[w] & ST_OUTCOME_MASK;
@@ -651,31 +666,35 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         __syncthreads();
     } else if (wave < 3 * V::NDYN) {
         // ================================================================= records
-        const bool active = lane < live_lanes;
-        const int e = (wave - 2 * V::NDYN) * 64 + (active ? lane : 0);
-        float *rw = reward + env0 + e;
-        uint8_t *dn = done + env0 + e;
+        const int half = UPL == 2 ? lane >> 5 : 0;
+        const int el = UPL == 2 ? (lane & 31) : lane;
+        const bool active = el < live_lanes;
+        const int e = (wave - 2 * V::NDYN) * 64 + (active ? el : 0);
+        float *rw = reward + env0 + e + (size_t)half * N;
+        uint8_t *dn = done + env0 + e + (size_t)half * N;
         const double slope = p.reward_slope;
+        const uint32_t *vw_lane = lds + L::VW + half * L::VW_SIZE + e;
+        uint32_t *rec_lane = lds + L::REC + half * L::REC_SIZE + e * V::REC;
         // the zero dword that ends every record is written once
-        if (active)
+        if (active && half == 0)
             for (int sl = 0; sl < 2 * SPB; ++sl) lds[L::REC + sl * L::REC_SIZE + e * V::REC + V::ND] = 0;
         __syncthreads();                                             // barrier 0 (set-up)
         __syncthreads();                                             // block 0 published
         __syncthreads();                                             // block 0 viewed
         MAZE_FOR_EACH_BLOCK(
             if (active) {
-                _Pragma("unroll") for (int u0 = 0; u0 < SPB; u0 += UGR) {
-                    uint32_t vw[UGR][V::WV], g[UGR], out[UGR], piece[UGR][K];
-                    _Pragma("unroll") for (int w = 0; w < UGR; ++w) if (MAZE_STEP_ON(u0 + w)) {
-                        const uint32_t *v = lds + L::VW + (par * SPB + u0 + w) * L::VW_SIZE + e;
+                _Pragma("unroll") for (int u0 = 0; u0 < SPB / UPL; u0 += UGRP) {
+                    uint32_t vw[UGRP][V::WV], g[UGRP], out[UGRP], piece[UGRP][K];
+                    _Pragma("unroll") for (int w = 0; w < UGRP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half)) {
+                        const uint32_t *v = vw_lane + (par * SPB + (u0 + w) * UPL) * L::VW_SIZE;
                         _Pragma("unroll") for (int q = 0; q < V::WV; ++q) vw[w][q] = v[q * EPW];
                         g[w] = v[V::WV * EPW]; out[w] = v[(V::WV + 1) * EPW];
                     }
-                    _Pragma("unroll") for (int w = 0; w < UGR; ++w) if (MAZE_STEP_ON(u0 + w))
+                    _Pragma("unroll") for (int w = 0; w < UGRP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half))
                         record_lookup<K>(lds + L::LUT, vw[w], piece[w]);
-                    _Pragma("unroll") for (int w = 0; w < UGR; ++w) if (MAZE_STEP_ON(u0 + w)) {
+                    _Pragma("unroll") for (int w = 0; w < UGRP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half)) {
                         uint32_t D[V::ND];
-                        uint32_t *rec = lds + L::REC + (par * SPB + u0 + w) * L::REC_SIZE + e * V::REC;
+                        uint32_t *rec = rec_lane + (par * SPB + (u0 + w) * UPL) * L::REC_SIZE;
                         if (MODE == 1 && p.obs_occlusion) {
                             uint32_t seenw[V::WV];
                             visible_cells<K>(vw[w], seenw);
@@ -686,8 +705,8 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                         record_finish<K>(piece[w], vw[w], (int)(int16_t)(g[w] & 0xFFFF), (int)g[w] >> 16,
                                          D, rec);
                         const uint32_t tr = out[w] & 0x7FFFFFFFu;
-                        rw[(size_t)(u0 + w) * N] = tr ? (float)(1.0 - (double)tr * slope) : 0.0f;
-                        dn[(size_t)(u0 + w) * N] = (uint8_t)(out[w] >> 31);
+                        rw[(size_t)((u0 + w) * UPL) * N] = tr ? (float)(1.0 - (double)tr * slope) : 0.0f;
+                        dn[(size_t)((u0 + w) * UPL) * N] = (uint8_t)(out[w] >> 31);
                     }
                 }
                 rw += (size_t)SPB * N;
