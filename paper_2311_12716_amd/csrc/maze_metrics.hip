@@ -5,26 +5,30 @@
 // breadth-first search is a flood over row bitmaps: a lane owns one row of one env
 // and repeats
 //     reach' = (reach | reach << 1 | reach >> 1 | row above | row below) & free
-// where the neighbouring rows come from the neighbouring lanes of the wave.  The
-// number of rounds until the goal's bit appears is the path length; a round that
-// changes nothing means the goal cannot be reached.
+// where the neighbouring rows come from the neighbouring lanes of the wave (DPP wave
+// shifts).  The number of rounds until the goal's bit appears is the path length; rounds
+// that change nothing mean the goal cannot be reached.
 #include "maze_internal.h"
 #include "maze_student_device.h"
 
 namespace {
 
-template <typename Word>
-__device__ __forceinline__ Word shuffle_up1(Word v)
+// The value of a neighbouring lane by a DPP wave shift (one full-rate instruction per dword,
+// no LDS crossbar).  SHR = true: lane i reads lane i-1; false: lane i reads lane i+1.  Which
+// lane a shift really delivers is not assumed: the kernel shifts the lane numbers once and
+// derives its edge masks from what arrives.
+template <bool SHR>
+__device__ __forceinline__ uint32_t wave_shift1(uint32_t v)
 {
-    if (sizeof(Word) == 4) return (Word)__shfl_up((unsigned)v, 1);
-    return (Word)__shfl_up((unsigned long long)v, 1);
+    return __builtin_amdgcn_update_dpp(0u, v, SHR ? 0x138 /* wave_shr:1 */ : 0x130 /* wave_shl:1 */, 0xf,
+                                       0xf, true);
 }
-
-template <typename Word>
-__device__ __forceinline__ Word shuffle_down1(Word v)
+template <bool SHR, typename Word>
+__device__ __forceinline__ Word wave_shift1_word(Word v)
 {
-    if (sizeof(Word) == 4) return (Word)__shfl_down((unsigned)v, 1);
-    return (Word)__shfl_down((unsigned long long)v, 1);
+    if (sizeof(Word) == 4) return (Word)wave_shift1<SHR>((uint32_t)v);
+    const uint32_t lo = wave_shift1<SHR>((uint32_t)v), hi = wave_shift1<SHR>((uint32_t)((uint64_t)v >> 32));
+    return (Word)(((uint64_t)hi << 32) | lo);
 }
 
 // G = lanes per env (a power of two >= H, at most 64); a wave serves 64 / G envs.
@@ -60,23 +64,42 @@ __global__ __launch_bounds__(256) void k_level_metrics(StudentDev p, int G, int3
     const uint32_t goal = p.goalrot[4 * (size_t)n + 3];
     const int gx = (int)(goal & 255) - p.P, gy = (int)((goal >> 8) & 255) - p.P;
 
+    // A shifted value counts only if it comes from the row above or below in the same env (lane
+    // numbers differ by one, same group, row inside the grid).  Lane numbers travel as lane + 1,
+    // so a lane at the wave's edge, which receives 0, reads "no lane".
+    const uint32_t from_a = wave_shift1<true>((uint32_t)lane + 1) - 1, from_b = wave_shift1<false>((uint32_t)lane + 1) - 1;
+    auto neighbour_ok = [&](uint32_t from) {
+        const int fg = (int)from / G, fr = (int)from - fg * G;
+        return from < 64u && fg == group && (fr == r - 1 || fr == r + 1) && fr < p.H && row_live;
+    };
+    const Word keep_a = neighbour_ok(from_a) ? ~(Word)0 : (Word)0;
+    const Word keep_b = neighbour_ok(from_b) ? ~(Word)0 : (Word)0;
+
     Word reach = (row_live && r == sy) ? (Word)(((Word)1 << sx) & free_cells) : (Word)0;
     const Word goal_bit = (row_live && r == gy) ? (Word)((Word)1 << gx) : (Word)0;
-    int dist = -1;
+    int dist = -1;                               // set by the goal's lane in the round its bit appears
     bool running = env_live;
     const int max_rounds = p.H * p.W;            // a shortest path visits no cell twice
-    for (int round = 0; round <= max_rounds; ++round) {
-        const uint64_t found = __ballot((reach & goal_bit) != 0) & gmask;
-        if (running && found) { dist = round; running = false; }
-        Word up = shuffle_up1(reach), down = shuffle_down1(reach);
-        if (r == 0) up = 0;
-        if (r >= p.H - 1) down = 0;
-        const Word grown = (Word)((reach | (reach << 1) | (reach >> 1) | up | down) & free_cells);
-        const uint64_t changed = __ballot(grown != reach) & gmask;
-        if (running && !changed) running = false;            // flood complete, goal not in it
-        reach = grown;
+    constexpr int CHECK = 4;                     // rounds between two looks at who is done
+    for (int round0 = 0; round0 <= max_rounds; round0 += CHECK) {
+        bool changed = false;
+#pragma unroll
+        for (int i = 0; i < CHECK; ++i) {
+            if (dist < 0 && (reach & goal_bit) != 0) dist = round0 + i;
+            const Word a = wave_shift1_word<true>(reach) & keep_a, b = wave_shift1_word<false>(reach) & keep_b;
+            const Word grown = (Word)((reach | (reach << 1) | (reach >> 1) | a | b) & free_cells);
+            changed |= grown != reach;
+            reach = grown;
+        }
+        // an env is done when its goal lane has a distance or nothing changed in these rounds
+        const uint64_t found = __ballot(dist >= 0) & gmask, moving = __ballot(changed) & gmask;
+        if (found || !moving) running = false;
         if (!__any(running)) break;
     }
+    // the goal's lane holds the distance; hand it to the env's first lane
+    const uint64_t holder = __ballot(dist >= 0) & gmask;
+    const int src_lane = holder ? __ffsll((long long)holder) - 1 : lane;
+    dist = __shfl(dist, src_lane);
     if (env_live && r == 0) {
         if (n_walls) n_walls[n] = count;
         if (path_len) path_len[n] = dist;
