@@ -40,7 +40,7 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
     extern __shared__ uint32_t lds[];            // [EPW][REC], REC = SW + 1 (last dword stays 0)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int env0 = blockIdx.x * EPW;
+    const int env0 = xcd_contiguous(blockIdx.x, gridDim.x) * EPW;
     const int SW = p.SW, REC = SW + 1;
     const int SB = 3 * p.cells;                  // stream bits = obs bytes per env
     const int count = min(EPW, p.N - env0);      // envs of this workgroup (the last one may be partly filled)

@@ -57,3 +57,16 @@ __device__ __forceinline__ uint4 load_bytes(const int8_t *src, int valid)
         if (b < valid) w[b >> 2] |= (uint32_t)(uint8_t)src[b] << (8 * (b & 3));
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
+
+// The hardware hands consecutive workgroups of a launch to the 8 XCDs in turn, each with an L2 of
+// its own.  Neighbouring workgroups write neighbouring byte ranges whose ends share a 128-byte
+// line unless the range is a whole number of lines (32 student envs x 147 B is not); this renumbering
+// gives every XCD a contiguous range of workgroups, so that such a line is completed within one L2
+// instead of leaving two of them in parts.  (If the assignment were different the result would
+// be the same, only the gain lost.)
+__device__ __forceinline__ int xcd_contiguous(int block, int blocks)
+{
+    const int xcd = block & 7, turn = block >> 3;
+    const int each = blocks >> 3, extra = blocks & 7;       // the first `extra` XCDs get one more
+    return xcd * each + min(xcd, extra) + turn;
+}

@@ -549,7 +549,8 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     extern __shared__ uint32_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int env0 = n_begin + blockIdx.x * EPW;     // n_begin: a multiple of 32 (16-byte pieces)
+    const int wg = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int env0 = n_begin + wg * EPW;             // n_begin: a multiple of 32 (16-byte pieces)
     const int SP = p.SP, N = p.N;
     const int count = PARTIAL ? min(EPW, n_end - env0) : EPW;       // envs of this workgroup
     const int live_lanes = PARTIAL ? min((int)V::LA, count) : V::LA; // (PARTIAL: one wave per stage)
@@ -761,7 +762,7 @@ __global__ __launch_bounds__(REPW) void k_step_render_tiled(
     using L = Lds<K, Word, REPW>;
     extern __shared__ uint32_t lds[];
     const int lane = threadIdx.x;
-    const int env0 = blockIdx.x * REPW;
+    const int env0 = xcd_contiguous(blockIdx.x, gridDim.x) * REPW;
     const int n = env0 + lane;
     fill_lut<K>(lds + L::LUT, lane, REPW);
     __syncthreads();
@@ -890,12 +891,19 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
                                d_actions, d_reward, d_done, d_obs);
         return REPW * (p.N / REPW);
     }
-    if (p.obs_encoding || p.obs_occlusion) {     // observation variants: 64 envs per workgroup, then the rest
-        int done_envs = launch_rollout<K, Word, 64, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done,
+    if (p.obs_encoding || p.obs_occlusion) {
+        // observation variants: 64 envs per workgroup while their grids fit in LDS, then 32
+        int done_envs = 0;
+        if (Lds<K, Word, 64>::bytes(p.SP, true) <= LDS_PER_CU - 1024)
+            done_envs = launch_rollout<K, Word, 64, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done,
                                                        d_obs, st);
-        if (done_envs < p.N)
-            done_envs += launch_rollout<K, Word, 32, 1, true>(ctx, done_envs, p.N - done_envs, d_actions,
-                                                              n_steps, d_reward, d_done, d_obs, st);
+        const int rest = p.N - done_envs;
+        if (rest > 0 && rest % 32 == 0)
+            done_envs += launch_rollout<K, Word, 32, 1>(ctx, done_envs, rest, d_actions, n_steps, d_reward,
+                                                        d_done, d_obs, st);
+        else if (rest > 0)
+            done_envs += launch_rollout<K, Word, 32, 1, true>(ctx, done_envs, rest, d_actions, n_steps,
+                                                              d_reward, d_done, d_obs, st);
         return done_envs;
     }
     int covered = 0;
