@@ -110,10 +110,13 @@ class MazeEnv:
             _check(lib.maze_create(byref(h), N, H, W, view, max_steps,
                                    self.workspace.data_ptr(), nbytes.value), "maze_create")
         self._h = h
+        self._destroy = lib.maze_destroy
 
     def close(self):
+        # (the destroy function is kept on the object: at interpreter shutdown module globals
+        # may already be gone when __del__ runs)
         if getattr(self, "_h", None):
-            load_library().maze_destroy(self._h)
+            self._destroy(self._h)
             self._h = None
 
     __del__ = close
@@ -209,10 +212,11 @@ class EditorEnv:
             _check(lib.editor_create(byref(h), N, H, W, n_walls, self.workspace.data_ptr(),
                                      nbytes.value), "editor_create")
         self._h = h
+        self._destroy = lib.editor_destroy
 
     def close(self):
         if getattr(self, "_h", None):
-            load_library().editor_destroy(self._h)
+            self._destroy(self._h)
             self._h = None
 
     __del__ = close
