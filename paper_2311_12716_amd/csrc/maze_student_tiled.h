@@ -92,11 +92,16 @@ template <> struct WordOps<uint64_t> { static constexpr int DW = 2; };
 
 // Per-workgroup LDS carve-up (dword offsets).  ST and REC hold SPB steps each and
 // are double buffered by block parity (a block = the SPB steps between two barriers).
-template <int K, typename Word, int EPW>
+template <int K, typename Word, int EPW, int MODE = 0>
 struct Lds {
     using V = View<K, EPW>;
     static constexpr int LUT = 0;                                  // [LUTN]
-    static constexpr int ACT = LUT + V::LUTN;                      // [2][ACT_BLOCK][EPW] action bytes
+    // the rollout of the observation variants (MODE 1) keeps two more tables
+    static constexpr int TYPED = LUT + V::LUTN;                    // [3][128] typed dwords (typed_table)
+    static constexpr int TYPED_N = MODE == 1 ? 3 * 128 : 0;
+    static constexpr int VIS = TYPED + TYPED_N;                    // [2^(2K)] 16-bit rows (visibility_table)
+    static constexpr int VIS_N = MODE == 1 ? (1 << (2 * K)) / 2 : 0;
+    static constexpr int ACT = VIS + VIS_N;                        // [2][ACT_BLOCK][EPW] action bytes
     static constexpr int ACT_ROW = EPW;                            // bytes per step
     static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][3][EPW] position, goal offset, outcome + heading
     static constexpr int ST_SIZE = 3 * EPW;
@@ -250,6 +255,7 @@ struct Window {
     // typed encoding only: which of the window's 16 bytes are a cell's first (type) and second
     // (colour) byte; a cell is three bytes and every env starts a new cell
     uint32_t type_pos, colour_pos;
+    int typed_row[4];   // per output dword: first entry of its phase's row of the typed table
     int valid;      // bytes of the window that exist: 16, fewer in a partly filled workgroup
 };
 
@@ -276,6 +282,8 @@ __device__ __forceinline__ Window make_window(int lane, int round)
     const uint32_t every_third = 0x9249u;        // bits 0, 3, 6, 9, 12, 15
     w.type_pos = phase == 0 ? every_third : (phase == 1 ? 0x4924u : 0x2492u);
     w.colour_pos = phase == 0 ? 0x2492u : (phase == 1 ? every_third : 0x4924u);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) w.typed_row[q] = 128 * ((phase + q) % 3);   // 4 bytes on: phase + 1
     return w;
 }
 
@@ -324,34 +332,125 @@ __device__ __forceinline__ void consume_window_typed(const uint32_t *recs, const
     else store_bytes(block + w.out, a, w.valid);
 }
 
+// The typed bytes of one output dword depend on the phase of its first byte (which of type,
+// colour, state it is) and on 7 stream bits: the one before the dword's first, its own four and
+// two more.  typed_table[phase][those bits] holds the dword, so a window is four table reads.
+__device__ __forceinline__ void fill_typed_table(uint32_t *table, int tid, int nthreads)
+{
+    for (int i = tid; i < 3 * 128; i += nthreads) {
+        const int phase = i >> 7, s = i & 127;             // bit j of s: stream bit (first - 1 + j)
+        uint32_t v = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int role = (phase + b) % 3;              // 0 type, 1 colour, 2 state
+            const int before = (s >> b) & 1, own = (s >> (b + 1)) & 1, next = (s >> (b + 2)) & 1,
+                      after = (s >> (b + 3)) & 1;
+            // a cell's stream bits are (wall, goal, empty): at its type byte own = wall, next = goal,
+            // after = empty; at its colour byte before = wall, own = goal
+            const int byte = role == 0 ? 2 * own + 8 * next + after : (role == 1 ? 5 * before + own : 0);
+            v |= (uint32_t)byte << (8 * b);
+        }
+        table[i] = v;
+    }
+}
+
+__device__ __forceinline__ void consume_window_typed(const uint32_t *recs, const Window &w, int8_t *block,
+                                                     const uint32_t *typed_table)
+{
+    const uint32_t lo = recs[w.addr0], hi = recs[w.addr0 + 1], nx = recs[w.addr1];
+    const uint32_t prev = recs[w.addr0 > 0 ? w.addr0 - 1 : 0];
+    const uint32_t bits = __builtin_amdgcn_alignbit(hi, lo, w.sh) | (nx << w.rem);   // stream bits p, p+1, ...
+    const uint32_t below = w.sh ? (lo >> (w.sh - 1)) & 1u : prev >> 31;               // stream bit p-1
+    const uint32_t from_below = (bits << 1) | below;                                  // bit j: stream bit p-1+j
+    uint4 a;
+    a.x = typed_table[w.typed_row[0] + (from_below & 127)];
+    a.y = typed_table[w.typed_row[1] + ((from_below >> 4) & 127)];
+    a.z = typed_table[w.typed_row[2] + ((from_below >> 8) & 127)];
+    a.w = typed_table[w.typed_row[3] + ((from_below >> 12) & 127)];
+    if (w.valid >= 16) store16(block + w.out, a);
+    else store_bytes(block + w.out, a, w.valid);
+}
+
 // Which cells of the view are seen (occluded view): rows are settled from the agent's row
 // outwards as K-bit masks.  Seen cells spread sideways through cells that are not walls (a
 // seen wall spreads nothing), then every seen non-wall cell makes the three cells touching
 // it in the next row ahead seen.  The agent's own cell spreads whatever it holds.  Returns
 // the masks packed like the view bits (row r at bit K*(r % RPD) of dword r / RPD).
+// One row: `wall` its wall cells, `from_below` the cells made seen by the row behind it.
+template <int K>
+__device__ __forceinline__ void visible_row(uint32_t wall, uint32_t from_below, uint32_t &seen,
+                                            uint32_t &to_next)
+{
+    constexpr uint32_t all = (1u << K) - 1;
+    const uint32_t open = ~wall & all;
+    seen = from_below;
+#pragma unroll
+    for (int it = 1; it < K; ++it) {
+        const uint32_t src = seen & open;
+        seen |= ((src << 1) | (src >> 1)) & all;
+    }
+    const uint32_t src = seen & open;
+    to_next = (src | (src << 1) | (src >> 1)) & all;
+}
+
 template <int K>
 __device__ __forceinline__ void visible_cells(const uint32_t (&vw)[View<K, 64>::WV],
                                               uint32_t (&seenw)[View<K, 64>::WV])
 {
     using V = View<K, 64>;
-    constexpr uint32_t all = (1u << K) - 1;
+    constexpr uint32_t all = (1u << K) - 1, centre = 1u << (K / 2);
 #pragma unroll
     for (int q = 0; q < V::WV; ++q) seenw[q] = 0;
-    uint32_t from_below = 1u << (K / 2);
+    uint32_t from_below = centre;
 #pragma unroll
     for (int r = K - 1; r >= 0; --r) {
-        const uint32_t wall = (vw[r / V::RPD] >> (K * (r % V::RPD))) & all;
-        uint32_t open = ~wall & all;
-        if (r == K - 1) open |= 1u << (K / 2);
-        uint32_t seen = from_below;
-#pragma unroll
-        for (int it = 1; it < K; ++it) {
-            const uint32_t src = seen & open;
-            seen |= ((src << 1) | (src >> 1)) & all;
-        }
-        const uint32_t src = seen & open;
-        from_below = (src | (src << 1) | (src >> 1)) & all;
+        uint32_t wall = (vw[r / V::RPD] >> (K * (r % V::RPD))) & all;
+        if (r == K - 1) wall &= ~centre;           // the agent's cell spreads whatever it holds
+        uint32_t seen;
+        visible_row<K>(wall, from_below, seen, from_below);
         seenw[r / V::RPD] |= seen << (K * (r % V::RPD));
+    }
+}
+
+// visibility_table[wall | from_below << K] = seen | to_next << K: a row of the occluded view is
+// one 16-bit table read in the rollout (2^(2K) entries).
+template <int K>
+__device__ __forceinline__ void fill_visibility_table(uint16_t *table, int tid, int nthreads)
+{
+    constexpr uint32_t all = (1u << K) - 1;
+    for (int i = tid; i < (1 << (2 * K)); i += nthreads) {
+        uint32_t seen, to_next;
+        visible_row<K>(i & all, (uint32_t)i >> K, seen, to_next);
+        table[i] = (uint16_t)(seen | (to_next << K));
+    }
+}
+
+// visible_cells() for G views at once through the table: the G chains of K dependent reads
+// run side by side.
+template <int K, int G>
+__device__ __forceinline__ void visible_cells_tabled(const uint16_t *table,
+                                                     const uint32_t (&vw)[G][View<K, 64>::WV],
+                                                     uint32_t (&seenw)[G][View<K, 64>::WV])
+{
+    using V = View<K, 64>;
+    constexpr uint32_t all = (1u << K) - 1, centre = 1u << (K / 2);
+    uint32_t from_below[G];
+#pragma unroll
+    for (int w = 0; w < G; ++w) {
+        from_below[w] = centre;
+#pragma unroll
+        for (int q = 0; q < V::WV; ++q) seenw[w][q] = 0;
+    }
+#pragma unroll
+    for (int r = K - 1; r >= 0; --r) {
+#pragma unroll
+        for (int w = 0; w < G; ++w) {
+            uint32_t wall = (vw[w][r / V::RPD] >> (K * (r % V::RPD))) & all;
+            if (r == K - 1) wall &= ~centre;
+            const uint32_t e = table[wall | (from_below[w] << K)];
+            seenw[w][r / V::RPD] |= (e & all) << (K * (r % V::RPD));
+            from_below[w] = e >> K;
+        }
     }
 }
 
@@ -368,12 +467,12 @@ __device__ __forceinline__ void fill_lut(uint32_t *lut, int tid, int nthreads)
 }
 
 // Copy the workgroup's envs' grids into LDS (all threads take part).
-template <int K, typename Word, int EPW>
+template <typename L, typename Word>
 __device__ __forceinline__ void stage_grids(const StudentDev &p, uint32_t *lds, int tid, int nthreads,
                                             int env0, int count)
 {
-    const int gs = Lds<K, Word, EPW>::grid_stride(p.SP);
-    uint32_t *base = lds + Lds<K, Word, EPW>::GRID0;
+    const int gs = L::grid_stride(p.SP);
+    uint32_t *base = lds + L::GRID0;
     const int per_env = 4 * p.SP * WordOps<Word>::DW;
     const uint32_t *src = (const uint32_t *)p.grids + (size_t)env0 * per_env;
     int e = 0, o = tid;
@@ -537,11 +636,12 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     float *__restrict__ reward, uint8_t *__restrict__ done, int8_t *__restrict__ obs)
 {
     using V = View<K, EPW>;
-    using L = Lds<K, Word, EPW>;
+    using L = Lds<K, Word, EPW, MODE>;
     constexpr int NT = 64 * V::WAVES;
     constexpr int ACT_BLOCK = V::ACT_BLOCK;
     constexpr int UGV = step_group(K * WordOps<Word>::DW + 3, 40);   // views: wall rows + state
-    constexpr int UGR = step_group(K + V::WV + 2, 48);               // records: table words + view
+    // records: table words + view (+ the seen cells and the chain state of the occluded view)
+    constexpr int UGR = step_group(K + V::WV + 2 + (MODE == 1 ? V::WV + 2 : 0), 48);
     // steps per pass of a views / records wave: two when the wave would be half empty
     constexpr int UPL = (V::LA == 32 && SPB % 2 == 0) ? 2 : 1;
     constexpr int UGVP = UGV > SPB / UPL ? SPB / UPL : UGV;
@@ -557,7 +657,11 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     static_assert(!PARTIAL || V::NDYN == 1, "partly filled workgroups: 64 envs at most");
 
     fill_lut<K>(lds + L::LUT, tid, NT);
-    if (GRID_LDS) stage_grids<K, Word, EPW>(p, lds, tid, NT, env0, count);
+    if (GRID_LDS) stage_grids<L, Word>(p, lds, tid, NT, env0, count);
+    if (MODE == 1) {
+        fill_typed_table(lds + L::TYPED, tid, NT);
+        if (p.obs_occlusion) fill_visibility_table<K>((uint16_t *)(lds + L::VIS), tid, NT);
+    }
 
     if (wave < V::NDYN) {
         // ================================================================ dynamics
@@ -693,15 +797,21 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                     }
                     _Pragma("unroll") for (int w = 0; w < UGRP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half))
                         record_lookup<K>(lds + L::LUT, vw[w], piece[w]);
+                    uint32_t seenw[UGRP][V::WV];
+                    if constexpr (MODE == 1) if (p.obs_occlusion) {
+                        // (steps beyond the rollout's end hold the block's stale views: their
+                        // table reads stay inside the table, their results are dropped)
+                        _Pragma("unroll") for (int w = 0; w < UGRP; ++w) if (!MAZE_STEP_ON((u0 + w) * UPL + half))
+                            _Pragma("unroll") for (int q = 0; q < V::WV; ++q) vw[w][q] = 0;
+                        visible_cells_tabled<K, UGRP>((const uint16_t *)(lds + L::VIS), vw, seenw);
+                    }
                     _Pragma("unroll") for (int w = 0; w < UGRP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half)) {
                         uint32_t D[V::ND];
                         uint32_t *rec = rec_lane + (par * SPB + (u0 + w) * UPL) * L::REC_SIZE;
                         if (MODE == 1 && p.obs_occlusion) {
-                            uint32_t seenw[V::WV];
-                            visible_cells<K>(vw[w], seenw);
-                            mask_unseen<K>(lds + L::LUT, seenw, piece[w]);
+                            mask_unseen<K>(lds + L::LUT, seenw[w], piece[w]);
                             record_finish<K>(piece[w], vw[w], (int)(int16_t)(g[w] & 0xFFFF),
-                                             (int)g[w] >> 16, D, rec, seenw);
+                                             (int)g[w] >> 16, D, rec, seenw[w]);
                         } else
                         record_finish<K>(piece[w], vw[w], (int)(int16_t)(g[w] & 0xFFFF), (int)g[w] >> 16,
                                          D, rec);
@@ -739,7 +849,8 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                 const uint32_t *rec = lds + L::REC + (par * SPB + u) * L::REC_SIZE;
                 _Pragma("unroll") for (int j = 0; j < MYR; ++j) {
                     if (!win[j].active) continue;
-                    if (MODE == 1 && p.obs_encoding) consume_window_typed(rec, win[j], out_block + u * step_obs);
+                    if (MODE == 1 && p.obs_encoding)
+                        consume_window_typed(rec, win[j], out_block + u * step_obs, lds + L::TYPED);
                     else consume_window(rec, win[j], out_block + u * step_obs);
                 }
             }
@@ -830,7 +941,7 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
                    float *d_reward, uint8_t *d_done, int8_t *d_obs, hipStream_t st)
 {
     using V = View<K, EPW>;
-    using L = Lds<K, Word, EPW>;
+    using L = Lds<K, Word, EPW, MODE>;
     const StudentDev &p = ctx->dev;
     const int groups = PARTIAL ? (n_envs + EPW - 1) / EPW : n_envs / EPW;
     if (groups < 1) return 0;
@@ -892,9 +1003,10 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
         return REPW * (p.N / REPW);
     }
     if (p.obs_encoding || p.obs_occlusion) {
-        // observation variants: 64 envs per workgroup while their grids fit in LDS, then 32
+        // observation variants: 64 envs per workgroup if that gives every CU a workgroup and
+        // the grids fit in LDS, then 32
         int done_envs = 0;
-        if (Lds<K, Word, 64>::bytes(p.SP, true) <= LDS_PER_CU - 1024)
+        if (p.N >= 64 * 256 && Lds<K, Word, 64, 1>::bytes(p.SP, true) <= LDS_PER_CU - 1024)
             done_envs = launch_rollout<K, Word, 64, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done,
                                                        d_obs, st);
         const int rest = p.N - done_envs;
