@@ -1003,10 +1003,15 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
         return REPW * (p.N / REPW);
     }
     if (p.obs_encoding || p.obs_occlusion) {
-        // observation variants: 64 envs per workgroup if that gives every CU a workgroup and
-        // the grids fit in LDS, then 32
+        // observation variants: 128 (typed bytes only: as fast as the plain observation) or 64
+        // (occluded: the records stage is the slow one, more workgroups do better) envs per
+        // workgroup if that gives every CU a workgroup and the grids fit in LDS, then 32
         int done_envs = 0;
-        if (p.N >= 64 * 256 && Lds<K, Word, 64, 1>::bytes(p.SP, true) <= LDS_PER_CU - 1024)
+        if (!p.obs_occlusion && p.N >= 128 * 256 &&
+            Lds<K, Word, 128, 1>::bytes(p.SP, true) <= LDS_PER_CU - 1024)
+            done_envs = launch_rollout<K, Word, 128, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done,
+                                                        d_obs, st);
+        else if (p.N >= 64 * 256 && Lds<K, Word, 64, 1>::bytes(p.SP, true) <= LDS_PER_CU - 1024)
             done_envs = launch_rollout<K, Word, 64, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done,
                                                        d_obs, st);
         const int rest = p.N - done_envs;
