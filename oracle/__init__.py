@@ -138,6 +138,20 @@ class MazeOracle:
     def get_state(self):
         return self.xy.copy(), self.dir.copy(), self.t.copy()
 
+    def set_state(self, xy=None, direction=None, t=None) -> None:
+        """The setter that goes with get_state (Section 2.2: env state getter and setter):
+        overwrite position, heading and the episode's step count; the levels stay.  Positions
+        are clamped into the interior, headings taken mod 4, step counts clamped to
+        [0, max_steps - 1]; a part passed as None is kept."""
+        if xy is not None:
+            xy = _req(xy, np.int32, (self.N, 2))
+            self.xy = np.stack([np.clip(xy[:, 0], 0, self.W - 1), np.clip(xy[:, 1], 0, self.H - 1)],
+                               axis=1).astype(np.int32)
+        if direction is not None:
+            self.dir = (_req(direction, np.int8, (self.N,)).astype(np.int32) & 3).astype(np.int8)
+        if t is not None:
+            self.t = np.clip(_req(t, np.int32, (self.N,)), 0, self.max_steps - 1).astype(np.int32)
+
     def get_levels(self) -> Levels:
         L = self.levels
         return Levels(L.walls.copy(), L.agent_xy.copy(), L.agent_dir.copy(), L.goal_xy.copy())

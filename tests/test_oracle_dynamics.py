@@ -218,3 +218,42 @@ def test_turn_identities(seq):
     o.step(a, len(seq), want_obs=False)
     xy, dr, t = o.get_state()
     assert (xy == w.agent_xy).all() and (dr == w.agent_dir).all() and (t == len(seq)).all()
+
+
+def test_set_state_continues_like_the_env_it_was_read_from():
+    """(Section 2.2: state getter and setter.)  Position, heading and step count are the whole
+    running state: a second env given the same levels and the state read from the first after
+    some steps must produce the same rewards, dones and observations from there on; and a state
+    written by hand must behave as the closed forms say (steps left until the cap, reward at
+    the goal for the step count set)."""
+    from paper_2311_12716_amd import workloads as wl
+    w = wl.student_random("set-state", 4242, N=64, T=90, n_walls=30, max_steps=40)
+    a = oracle.MazeOracle(w.N, w.H, w.W, w.view, w.max_steps)
+    a.reset_to_levels(w.walls, w.agent_xy, w.agent_dir, w.goal_xy)
+    a.step(w.actions[:37], 37)
+    b = oracle.MazeOracle(w.N, w.H, w.W, w.view, w.max_steps)
+    b.reset_to_levels(w.walls, w.agent_xy, w.agent_dir, w.goal_xy)
+    b.set_state(*a.get_state())
+    assert (b.render_obs() == a.render_obs()).all()
+    ra, da, oa = a.step(w.actions[37:], 53)
+    rb, db, ob = b.step(w.actions[37:], 53)
+    assert (ra == rb).all() and (da == db).all() and (oa == ob).all()
+    for x, y in zip(a.get_state(), b.get_state()):
+        assert (x == y).all()
+
+    # hand-written state on an empty 1x6 corridor: goal at x = 5, agent put at x = 3 facing +x
+    # with 7 steps already taken of 10: two forward moves reach the goal at t = 9
+    o = make(["......"], (0, 0), 0, (5, 0), max_steps=10)
+    o.set_state(np.array([[3, 0]], np.int32), np.array([0], np.int8), np.array([7], np.int32))
+    r, d = run(o, [FWD, FWD, FWD])
+    assert list(d) == [0, 1, 0] and r[0] == 0 and abs(r[1] - (1 - 0.9 * 9 / 10)) < 1e-6
+    assert [v[0] for v in o.get_state()[1:]] == [0, 1] and tuple(o.get_state()[0][0]) == (1, 0)
+    # the step count is clamped below the cap, positions into the grid, headings taken mod 4
+    o.set_state(np.array([[-4, 9]], np.int32), np.array([7], np.int8), np.array([99], np.int32))
+    xy, hd, t = o.get_state()
+    assert tuple(xy[0]) == (0, 0) and hd[0] == 3 and t[0] == 9
+    r, d = run(o, [LEFT])
+    assert d[0] == 1 and r[0] == 0                   # the cap ends the episode on the next step
+    # parts passed as None are kept
+    o.set_state(t=np.array([2], np.int32))
+    assert tuple(o.get_state()[0][0]) == (0, 0) and o.get_state()[2][0] == 2
