@@ -103,6 +103,17 @@ int maze_render_obs(maze_ctx *ctx, int8_t *d_obs, void *stream);
  * d_t int32 [N]; level arrays as in maze_reset_to_levels.  Any pointer may be
  * NULL to skip that output.                                                   */
 int maze_get_state(maze_ctx *ctx, int32_t *d_xy, int8_t *d_dir, int32_t *d_t, void *stream);
+
+/* State setter (Section 2.2: the env exposes a getter and a setter for its state).
+ * Overwrites the running state of every env -- position, heading, steps taken in
+ * the current episode -- and leaves the levels (walls, start pose, goal) as they
+ * are, so that a state read with maze_get_state, or any other, can be continued
+ * from.  d_xy int32 [N,2] (x, y), clamped into the interior; d_dir int8 [N],
+ * taken mod 4; d_t int32 [N], clamped to [0, max_steps - 1].  A NULL pointer
+ * keeps that part of the state.  Device pointers, owned by the caller; enqueued
+ * on stream.  Returns MAZE_ENULL for a NULL ctx.                              */
+int maze_set_state(maze_ctx *ctx, const int32_t *d_xy, const int8_t *d_dir, const int32_t *d_t,
+                   void *stream);
 int maze_get_levels(maze_ctx *ctx, int8_t *d_walls, int32_t *d_agent_xy, int8_t *d_agent_dir,
                     int32_t *d_goal_xy, void *stream);
 

@@ -27,6 +27,7 @@ SIGNATURES = {
     "maze_step": (c_int, [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_render_obs": (c_int, [c_void_p, c_void_p, c_void_p]),
     "maze_get_state": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
+    "maze_set_state": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_get_levels": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_level_metrics": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_set_kernel_variant": (c_int, [c_void_p, c_int]),
@@ -172,6 +173,13 @@ class MazeEnv:
         _check(load_library().maze_get_state(self._h, xy.data_ptr(), d.data_ptr(), t.data_ptr(),
                                              _stream()), "maze_get_state")
         return xy, d, t
+
+    def set_state(self, xy=None, direction=None, t=None):
+        """Overwrite position int32 [N,2], heading int8 [N], step count int32 [N]; None keeps a part."""
+        N = self.N
+        _check(load_library().maze_set_state(
+            self._h, _ptr(xy, torch.int32, (N, 2), "xy"), _ptr(direction, torch.int8, (N,), "direction"),
+            _ptr(t, torch.int32, (N,), "t"), _stream()), "maze_set_state")
 
     def get_levels(self):
         N, H, W, dev = self.N, self.H, self.W, self.device

@@ -459,6 +459,25 @@ __global__ void k_get_state(StudentDev p, int32_t *xy, int8_t *dir, int32_t *t)
     if (t) t[n] = (int32_t)p.tcount[n];
 }
 
+// The setter that goes with k_get_state: parts given as nullptr are kept.
+__global__ void k_set_state(StudentDev p, const int32_t *xy, const int8_t *dir, const int32_t *t)
+{
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= p.N) return;
+    const uint32_t pose = p.pose[n];
+    int d = (pose >> 16) & 3, X, Y;
+    frame_to_padded(p, d, pose & 255, (pose >> 8) & 255, X, Y);
+    if (xy) {
+        X = min(max(xy[2 * n], 0), p.W - 1) + p.P;
+        Y = min(max(xy[2 * n + 1], 0), p.H - 1) + p.P;
+    }
+    if (dir) d = dir[n] & 3;
+    int xd, yd;
+    padded_to_frame(p, d, X, Y, xd, yd);
+    p.pose[n] = (uint32_t)xd | ((uint32_t)yd << 8) | ((uint32_t)d << 16);
+    if (t) p.tcount[n] = (uint32_t)min(max(t[n], 0), p.max_steps - 1);
+}
+
 template <typename Word>
 __global__ void k_get_walls(StudentDev p, int8_t *walls)
 {
@@ -495,6 +514,18 @@ extern "C" int maze_get_state(maze_ctx *ctx, int32_t *d_xy, int8_t *d_dir, int32
     if (!ctx) return MAZE_ENULL;
     const StudentDev &p = ctx->dev;
     hipLaunchKernelGGL(k_get_state, dim3((p.N + 255) / 256), dim3(256), 0, (hipStream_t)stream, p,
+                       d_xy, d_dir, d_t);
+    MAZE_HIP_CHECK(hipGetLastError());
+    return MAZE_OK;
+}
+
+extern "C" int maze_set_state(maze_ctx *ctx, const int32_t *d_xy, const int8_t *d_dir,
+                              const int32_t *d_t, void *stream)
+{
+    if (!ctx) return MAZE_ENULL;
+    if (!d_xy && !d_dir && !d_t) return MAZE_OK;
+    const StudentDev &p = ctx->dev;
+    hipLaunchKernelGGL(k_set_state, dim3((p.N + 255) / 256), dim3(256), 0, (hipStream_t)stream, p,
                        d_xy, d_dir, d_t);
     MAZE_HIP_CHECK(hipGetLastError());
     return MAZE_OK;

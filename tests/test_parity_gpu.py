@@ -275,6 +275,42 @@ def test_reset_to_new_levels_replaces_everything():
     assert_rollout_equal(env.step(to_gpu(w2.actions)), o.step(w2.actions, w2.T), "after reset")
 
 
+@pytest.mark.parametrize("H,W,k", [(13, 13, 5), (9, 30, 7), (40, 40, 3), (6, 6, 9)])
+def test_set_state_matches_the_oracle(H, W, k):
+    """States written through maze_set_state (out-of-range values included: clamped, headings mod
+    4), parts left out, and the rollout that follows."""
+    w = wl.student_random(f"set-state-{H}x{W}", 700 + H, N=333, H=H, W=W, view=k, T=60,
+                          n_walls=H * W // 4, max_steps=25)
+    note(w.name)
+    rng = np.random.default_rng(99 + W)
+    env, o = gpu_student(w), cpu_student(w)
+    env.step(to_gpu(w.actions[:10]))
+    o.step(w.actions[:10], 10)
+    xy = rng.integers(-3, max(H, W) + 3, size=(w.N, 2)).astype(np.int32)
+    hd = rng.integers(-128, 128, size=w.N).astype(np.int8)
+    t = rng.integers(-5, 40, size=w.N).astype(np.int32)
+    env.set_state(to_gpu(xy), to_gpu(hd), to_gpu(t))
+    o.set_state(xy, hd, t)
+    assert_state_equal(env, o)
+    assert (env.render_obs().cpu().numpy() == o.render_obs()).all()
+    assert_rollout_equal(env.step(to_gpu(w.actions[10:30])), o.step(w.actions[10:30], 20), "after set_state")
+    # one part at a time, the others kept
+    env.set_state(direction=to_gpu(hd[::-1].copy()))
+    o.set_state(direction=hd[::-1].copy())
+    assert_state_equal(env, o)
+    env.set_state(xy=to_gpu(xy[::-1].copy()))
+    o.set_state(xy=xy[::-1].copy())
+    assert_state_equal(env, o)
+    env.set_state(t=to_gpu(t[::-1].copy()))
+    o.set_state(t=t[::-1].copy())
+    assert_state_equal(env, o)
+    assert_rollout_equal(env.step(to_gpu(w.actions[30:])), o.step(w.actions[30:], 30), "after partial set_state")
+    assert_state_equal(env, o)
+    # a state read back and written again changes nothing
+    env.set_state(*env.get_state())
+    assert_state_equal(env, o)
+
+
 @pytest.mark.parametrize("N,H,W,nw,T", [(1, 13, 13, 50, 52), (65, 5, 8, 12, 20), (300, 13, 13, 0, 5),
                                         (100, 2, 1, 3, 7), (130, 64, 64, 40, 44), (64, 9, 4, 20, 30)])
 def test_editor_shapes_and_overrun(N, H, W, nw, T):
