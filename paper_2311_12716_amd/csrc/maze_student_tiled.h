@@ -466,21 +466,37 @@ __device__ __forceinline__ void fill_lut(uint32_t *lut, int tid, int nthreads)
     }
 }
 
-// Copy the workgroup's envs' grids into LDS (all threads take part).
+// Copy the workgroup's envs' grids into LDS (all threads take part).  In global memory the
+// `count` grids are one contiguous run of 16-byte pieces (an env's four frames are a multiple of
+// four dwords and the array is 256-byte aligned); a thread takes every nthreads-th piece, four
+// of its pieces in flight at a time, and puts each into its env's slot (slots are one dword
+// longer than a grid, so a piece is written as four dwords).
 template <typename L, typename Word>
 __device__ __forceinline__ void stage_grids(const StudentDev &p, uint32_t *lds, int tid, int nthreads,
                                             int env0, int count)
 {
-    const int gs = L::grid_stride(p.SP);
     uint32_t *base = lds + L::GRID0;
-    const int per_env = 4 * p.SP * WordOps<Word>::DW;
-    const uint32_t *src = (const uint32_t *)p.grids + (size_t)env0 * per_env;
-    int e = 0, o = tid;
-    while (o >= per_env) { o -= per_env; ++e; }
-    while (e < count) {
-        base[e * gs + o] = src[(size_t)e * per_env + o];
-        o += nthreads;
-        while (o >= per_env) { o -= per_env; ++e; }
+    const int per_env = 4 * p.SP * WordOps<Word>::DW;          // dwords, a multiple of 4
+    const uint4 *src = (const uint4 *)((const uint32_t *)p.grids + (size_t)env0 * per_env);
+    const int pieces = count * (per_env >> 2);
+    // dword index of the piece in the run, and the env it falls in (advanced without dividing)
+    const int stride = 4 * nthreads, stride_envs = stride / per_env, stride_rest = stride - stride_envs * per_env;
+    int idx = 4 * tid, e = idx / per_env, o = idx - e * per_env;
+    constexpr int BATCH = 4;
+    for (int i0 = tid; i0 < pieces; i0 += BATCH * nthreads) {
+        uint4 v[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u)
+            if (i0 + u * nthreads < pieces) v[u] = src[i0 + u * nthreads];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            if (i0 + u * nthreads < pieces) {
+                uint32_t *dst = base + idx + e;                  // e slots precede it, one extra dword each
+                dst[0] = v[u].x; dst[1] = v[u].y; dst[2] = v[u].z; dst[3] = v[u].w;
+            }
+            idx += stride; e += stride_envs; o += stride_rest;
+            if (o >= per_env) { o -= per_env; ++e; }
+        }
     }
 }
 
