@@ -82,15 +82,14 @@ __global__ __launch_bounds__(256) void k_level_metrics(StudentDev p, int G, int3
     const int max_rounds = p.H * p.W;            // a shortest path visits no cell twice
     constexpr int CHECK = 4;                     // rounds between two looks at who is done
     for (int round0 = 0; round0 <= max_rounds; round0 += CHECK) {
-        bool changed = false;
+        const Word before = reach;
 #pragma unroll
         for (int i = 0; i < CHECK; ++i) {
             if (dist < 0 && (reach & goal_bit) != 0) dist = round0 + i;
             const Word a = wave_shift1_word<true>(reach) & keep_a, b = wave_shift1_word<false>(reach) & keep_b;
-            const Word grown = (Word)((reach | (reach << 1) | (reach >> 1) | a | b) & free_cells);
-            changed |= grown != reach;
-            reach = grown;
+            reach = (Word)((reach | (reach << 1) | (reach >> 1) | a | b) & free_cells);
         }
+        const bool changed = reach != before;    // the flood only grows: no change over these rounds = none in any
         // an env is done when its goal lane has a distance or nothing changed in these rounds
         const uint64_t found = __ballot(dist >= 0) & gmask, moving = __ballot(changed) & gmask;
         if (found || !moving) running = false;
