@@ -200,6 +200,12 @@ def main():
         rows["student_rollout_c3_occluded_typed_obs"] = {
             "ms": ms, "env-steps/s": N * T / ms * 1e3, "GB/s": 81.0 * N * T / ms / 1e6,
             "note": "maze_set_obs_mode(1, 1): occlusion in the records stage, typed bytes in the store stage"}
+        for mode, name in (((1, 0), "typed_obs"), ((0, 1), "occluded_obs")):
+            env.set_obs_mode(*mode)
+            ms, mn = time_calls(torch, lambda: env.step(actions, reward, done, obs), 5, warmup=1)
+            rows["student_rollout_c3_" + name] = {
+                "ms": ms, "env-steps/s": N * T / ms * 1e3, "GB/s": 81.0 * N * T / ms / 1e6,
+                "note": "maze_set_obs_mode(%d, %d)" % mode}
         env.set_obs_mode(0, 0)
         # the same single step replayed from a captured HIP graph (what a policy loop can do)
         side = torch.cuda.Stream()
