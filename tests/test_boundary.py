@@ -47,6 +47,11 @@ def test_workspace_size_validation(lib):
     assert lib.maze_workspace_bytes(0, 13, 13, 5, ctypes.byref(n)) == -1
     assert lib.maze_workspace_bytes(8, 13, 0, 5, ctypes.byref(n)) == -1
     assert lib.maze_workspace_bytes(8, 60, 60, 7, ctypes.byref(n)) == -3     # padded rows > 64 bits
+    # the limit itself: side + 2 (view - 1) = 64
+    for side, view in ((60, 3), (56, 5), (52, 7), (48, 9)):
+        assert lib.maze_workspace_bytes(8, side, side, view, ctypes.byref(n)) == 0
+        assert lib.maze_workspace_bytes(8, side + 1, side, view, ctypes.byref(n)) == -3
+        assert lib.maze_workspace_bytes(8, side, side + 1, view, ctypes.byref(n)) == -3
     assert lib.maze_workspace_bytes(8, 13, 13, 5, None) == -2
     assert lib.editor_workspace_bytes(8, 13, 13, ctypes.byref(n)) == 0 and n.value > 0
     assert lib.editor_workspace_bytes(8, 1, 1, ctypes.byref(n)) == -1

@@ -113,7 +113,9 @@ def test_ragged_batch_sizes(N, variant):
 
 @pytest.mark.parametrize("H,W,k,nw", [(13, 13, 3, 30), (7, 19, 5, 40), (20, 9, 7, 50),
                                       (5, 5, 9, 6), (51, 51, 7, 900), (40, 52, 7, 500),
-                                      (24, 24, 5, 200), (2, 2, 3, 1)])
+                                      (24, 24, 5, 200), (2, 2, 3, 1),
+                                      # the largest grids each view size takes (side + 2(k-1) = 64)
+                                      (60, 60, 3, 1200), (56, 56, 5, 1000), (48, 48, 9, 700), (60, 5, 3, 80)])
 @pytest.mark.parametrize("variant", [0, 1])
 def test_other_shapes(H, W, k, nw, variant):
     """Non-square grids, all supported view sizes, grids at the word-size limits."""
