@@ -16,6 +16,9 @@
  *     Calls validate their arguments on the host, enqueue kernels on `stream`
  *     and return without synchronising.  Two calls on the same context must be
  *     ordered by the caller (same stream, or events).
+ *   - A context belongs to the device that was current at *_create; every later
+ *     call on it must be made with that device current (MAZE_EINVAL otherwise)
+ *     and with a stream of that device.
  *   - Return value: MAZE_OK (0) or a negative MAZE_E* code; nothing aborts or
  *     throws.  maze_strerror() names a code.
  *   - Coordinates: x = column (grows right), y = row (grows down); interior
@@ -47,10 +50,11 @@ const char *maze_strerror(int code);
 
 /* ------------------------------------------------------------------ student
  * Static parameters (paper Section 2.2: fixed at initialisation): number of
- * envs N, interior size H x W, odd view size k, episode cap max_steps (250 in
- * the paper's experiments, Section 4).  Limits: W + 2(k-1) <= 64 and
+ * envs N, interior size H x W, odd view size k >= 3, episode cap max_steps (250
+ * in the paper's experiments, Section 4).  Limits: W + 2(k-1) <= 64 and
  * H + 2(k-1) <= 64 (the walls are kept as one machine word per padded row),
- * 1 <= max_steps < 2^24.
+ * 1 <= max_steps < 2^24; k = 1 or even k: MAZE_EINVAL (the k-1 rings of wall the
+ * layout pads the grid with are also what bounds the agent's moves).
  *
  * maze_workspace_bytes: device bytes maze_create needs for these parameters.
  * maze_create: builds the host handle; d_workspace must be 256-byte aligned.
@@ -88,9 +92,26 @@ int maze_reset_to_levels(maze_ctx *ctx, const int8_t *d_walls, const int32_t *d_
  *   d_obs     int8  [n_steps,N,k,k,3] or NULL: observation AFTER each step (of
  *             the reset state when done), same encoding as maze_render_obs.
  * n_steps > 1 runs the whole open-loop rollout in one launch with the state
- * held on chip; n_steps = 1 is the plain step a policy loop calls.            */
+ * held on chip; n_steps = 1 is the plain step a policy loop calls.
+ * Speed: calls with d_obs and k in {3, 5, 7} run the store-layout kernels (the
+ * observation leaves the chip as 16-byte pieces of contiguous runs); calls
+ * without d_obs, other view sizes and the last N mod 64 envs of a single step
+ * run a one-lane-per-env kernel that writes the observation byte by byte --
+ * same results, several times slower.  MAZE_EHIP if the device does not grant
+ * the LDS a workgroup of the rollout needs (up to 127 KB; never a silent switch
+ * of kernels).                                                                */
 int maze_step(maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
               uint8_t *d_done, int8_t *d_obs, void *stream);
+
+/* How a rollout (maze_step with d_obs and n_steps > 1) of these static parameters would be
+ * launched on a device with `cus` compute units and lds_per_cu bytes of LDS per unit (what
+ * maze_create reads from the device properties): envs per workgroup of the main launch (128,
+ * 64 or 32; 0 if the view size is not one the store-layout kernels take, the one-lane-per-env
+ * kernel then runs) and the LDS bytes such a workgroup needs.  Host arithmetic only, no GPU
+ * is touched.  MAZE_EHIP if even 32 envs per workgroup do not fit -- the error maze_step
+ * returns on such a device; argument errors as for maze_create and maze_set_obs_mode.     */
+int maze_rollout_plan(int N, int H, int W, int view, int encoding, int occlusion, int cus,
+                      size_t lds_per_cu, int *envs_per_workgroup, size_t *lds_bytes);
 
 /* Egocentric k x k observation of the current state (Section 3: partially
  * observable).  d_obs int8 [N,k,k,3]; view row 0 is farthest ahead, the agent
@@ -127,7 +148,7 @@ int maze_get_levels(maze_ctx *ctx, int8_t *d_walls, int32_t *d_agent_xy, int8_t 
  *                         0 if they coincide, -1 if the goal cannot be reached or
  *                         the start cell is a wall.
  * Either pointer may be NULL.  Depends only on the levels, not on the current
- * state.  MAZE_ESIZE if H > 64.                                                  */
+ * state.                                                                         */
 int maze_level_metrics(maze_ctx *ctx, int32_t *d_n_walls, int32_t *d_path_len, void *stream);
 
 /* Choose the kernel family used by maze_step / maze_render_obs: 0 = automatic

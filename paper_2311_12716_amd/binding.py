@@ -25,6 +25,8 @@ SIGNATURES = {
     "maze_destroy": (c_int, [c_void_p]),
     "maze_reset_to_levels": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_step": (c_int, [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_void_p]),
+    "maze_rollout_plan": (c_int, [c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_size_t, POINTER(c_int),
+                                  POINTER(c_size_t)]),
     "maze_render_obs": (c_int, [c_void_p, c_void_p, c_void_p]),
     "maze_get_state": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_set_state": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
@@ -78,8 +80,16 @@ def _check(rc: int, what: str):
         raise MazeError(f"{what} failed: {msg} ({rc})")
 
 
-def _stream() -> int:
-    return torch.cuda.current_stream().cuda_stream
+def _launch(device: torch.device, what: str, fn, *args):
+    """Call an entry point that takes the stream as its last argument, with `device` current
+    (the C side refuses a context used under another device) and that device's current stream."""
+    index = device.index if device.index is not None else torch.cuda.current_device()
+    if torch.cuda.current_device() == index:
+        rc = fn(*args, torch.cuda.current_stream(index).cuda_stream)
+    else:
+        with torch.cuda.device(index):
+            rc = fn(*args, torch.cuda.current_stream(index).cuda_stream)
+    _check(rc, what)
 
 
 def _ptr(t: torch.Tensor | None, dtype, shape, name: str):
@@ -132,11 +142,11 @@ class MazeEnv:
 
     def reset_to_levels(self, walls, agent_xy, agent_dir, goal_xy):
         N, H, W = self.N, self.H, self.W
-        _check(load_library().maze_reset_to_levels(
-            self._h, _ptr(walls, torch.int8, (N, H, W), "walls"),
-            _ptr(agent_xy, torch.int32, (N, 2), "agent_xy"),
-            _ptr(agent_dir, torch.int8, (N,), "agent_dir"),
-            _ptr(goal_xy, torch.int32, (N, 2), "goal_xy"), _stream()), "maze_reset_to_levels")
+        _launch(self.device, "maze_reset_to_levels", load_library().maze_reset_to_levels,
+                self._h, _ptr(walls, torch.int8, (N, H, W), "walls"),
+                _ptr(agent_xy, torch.int32, (N, 2), "agent_xy"),
+                _ptr(agent_dir, torch.int8, (N,), "agent_dir"),
+                _ptr(goal_xy, torch.int32, (N, 2), "goal_xy"))
 
     def step(self, actions, reward=None, done=None, obs=None, want_obs=True):
         """actions int8 [n_steps,N]; returns (reward, done, obs) with obs after each step."""
@@ -150,19 +160,19 @@ class MazeEnv:
             done = torch.empty((n_steps, N), dtype=torch.uint8, device=dev)
         if obs is None and want_obs:
             obs = torch.empty((n_steps, N, k, k, 3), dtype=torch.int8, device=dev)
-        _check(load_library().maze_step(
+        _launch(self.device, "maze_step", load_library().maze_step,
             self._h, _ptr(actions, torch.int8, (n_steps, N), "actions"), n_steps,
             _ptr(reward, torch.float32, (n_steps, N), "reward"),
             _ptr(done, torch.uint8, (n_steps, N), "done"),
-            _ptr(obs, torch.int8, (n_steps, N, k, k, 3), "obs"), _stream()), "maze_step")
+            _ptr(obs, torch.int8, (n_steps, N, k, k, 3), "obs"))
         return reward, done, obs
 
     def render_obs(self, obs=None):
         N, k = self.N, self.view
         if obs is None:
             obs = torch.empty((N, k, k, 3), dtype=torch.int8, device=self.device)
-        _check(load_library().maze_render_obs(self._h, _ptr(obs, torch.int8, (N, k, k, 3), "obs"),
-                                              _stream()), "maze_render_obs")
+        _launch(self.device, "maze_render_obs", load_library().maze_render_obs, self._h,
+                _ptr(obs, torch.int8, (N, k, k, 3), "obs"))
         return obs
 
     def get_state(self):
@@ -170,16 +180,16 @@ class MazeEnv:
         xy = torch.empty((N, 2), dtype=torch.int32, device=dev)
         d = torch.empty((N,), dtype=torch.int8, device=dev)
         t = torch.empty((N,), dtype=torch.int32, device=dev)
-        _check(load_library().maze_get_state(self._h, xy.data_ptr(), d.data_ptr(), t.data_ptr(),
-                                             _stream()), "maze_get_state")
+        _launch(self.device, "maze_get_state", load_library().maze_get_state, self._h, xy.data_ptr(),
+                d.data_ptr(), t.data_ptr())
         return xy, d, t
 
     def set_state(self, xy=None, direction=None, t=None):
         """Overwrite position int32 [N,2], heading int8 [N], step count int32 [N]; None keeps a part."""
         N = self.N
-        _check(load_library().maze_set_state(
+        _launch(self.device, "maze_set_state", load_library().maze_set_state,
             self._h, _ptr(xy, torch.int32, (N, 2), "xy"), _ptr(direction, torch.int8, (N,), "direction"),
-            _ptr(t, torch.int32, (N,), "t"), _stream()), "maze_set_state")
+            _ptr(t, torch.int32, (N,), "t"))
 
     def get_levels(self):
         N, H, W, dev = self.N, self.H, self.W, self.device
@@ -187,9 +197,8 @@ class MazeEnv:
         axy = torch.empty((N, 2), dtype=torch.int32, device=dev)
         ad = torch.empty((N,), dtype=torch.int8, device=dev)
         gxy = torch.empty((N, 2), dtype=torch.int32, device=dev)
-        _check(load_library().maze_get_levels(self._h, walls.data_ptr(), axy.data_ptr(),
-                                              ad.data_ptr(), gxy.data_ptr(), _stream()),
-               "maze_get_levels")
+        _launch(self.device, "maze_get_levels", load_library().maze_get_levels, self._h,
+                walls.data_ptr(), axy.data_ptr(), ad.data_ptr(), gxy.data_ptr())
         return walls, axy, ad, gxy
 
 
@@ -200,8 +209,8 @@ class MazeEnv:
             n_walls = torch.empty((N,), dtype=torch.int32, device=dev)
         if path_len is None:
             path_len = torch.empty((N,), dtype=torch.int32, device=dev)
-        _check(load_library().maze_level_metrics(self._h, n_walls.data_ptr(), path_len.data_ptr(),
-                                                 _stream()), "maze_level_metrics")
+        _launch(self.device, "maze_level_metrics", load_library().maze_level_metrics, self._h,
+                n_walls.data_ptr(), path_len.data_ptr())
         return n_walls, path_len
 
 
@@ -230,9 +239,8 @@ class EditorEnv:
     __del__ = close
 
     def reset(self, agent_dir_init):
-        _check(load_library().editor_reset(
-            self._h, _ptr(agent_dir_init, torch.int8, (self.N,), "agent_dir_init"), _stream()),
-            "editor_reset")
+        _launch(self.device, "editor_reset", load_library().editor_reset,
+            self._h, _ptr(agent_dir_init, torch.int8, (self.N,), "agent_dir_init"))
 
     def step(self, actions, obs=None, t=None, done=None, want_obs=True):
         if actions.dim() != 2:
@@ -244,11 +252,11 @@ class EditorEnv:
             t = torch.empty((n_steps, N), dtype=torch.int32, device=dev)
         if done is None:
             done = torch.empty((n_steps, N), dtype=torch.uint8, device=dev)
-        _check(load_library().editor_step(
+        _launch(self.device, "editor_step", load_library().editor_step,
             self._h, _ptr(actions, torch.int32, (n_steps, N), "actions"), n_steps,
             _ptr(obs, torch.int8, (n_steps, N, H, W, 3), "obs"),
             _ptr(t, torch.int32, (n_steps, N), "t"),
-            _ptr(done, torch.uint8, (n_steps, N), "done"), _stream()), "editor_step")
+            _ptr(done, torch.uint8, (n_steps, N), "done"))
         return obs, t, done
 
     def get_levels(self):
@@ -257,27 +265,26 @@ class EditorEnv:
         axy = torch.empty((N, 2), dtype=torch.int32, device=dev)
         ad = torch.empty((N,), dtype=torch.int8, device=dev)
         gxy = torch.empty((N, 2), dtype=torch.int32, device=dev)
-        _check(load_library().editor_get_levels(self._h, walls.data_ptr(), axy.data_ptr(),
-                                                ad.data_ptr(), gxy.data_ptr(), _stream()),
-               "editor_get_levels")
+        _launch(self.device, "editor_get_levels", load_library().editor_get_levels, self._h,
+                walls.data_ptr(), axy.data_ptr(), ad.data_ptr(), gxy.data_ptr())
         return walls, axy, ad, gxy
 
     def set_levels(self, walls, agent_xy, agent_dir, goal_xy):
         N, H, W = self.N, self.H, self.W
-        _check(load_library().editor_set_levels(
+        _launch(self.device, "editor_set_levels", load_library().editor_set_levels,
             self._h, _ptr(walls, torch.int8, (N, H, W), "walls"),
             _ptr(agent_xy, torch.int32, (N, 2), "agent_xy"),
             _ptr(agent_dir, torch.int8, (N,), "agent_dir"),
-            _ptr(goal_xy, torch.int32, (N, 2), "goal_xy"), _stream()), "editor_set_levels")
+            _ptr(goal_xy, torch.int32, (N, 2), "goal_xy"))
 
     def random_levels(self, seed: int, first_level_id: int = 0):
         """Replace every env by a level of the counter-based random generator."""
-        _check(load_library().editor_random_levels(self._h, int(seed), int(first_level_id), _stream()),
-               "editor_random_levels")
+        _launch(self.device, "editor_random_levels", load_library().editor_random_levels, self._h,
+                int(seed), int(first_level_id))
 
     def mutate_levels(self, seed: int, first_level_id: int, n_edits: int):
-        _check(load_library().editor_mutate_levels(self._h, int(seed), int(first_level_id),
-                                                   int(n_edits), _stream()), "editor_mutate_levels")
+        _launch(self.device, "editor_mutate_levels", load_library().editor_mutate_levels, self._h,
+                int(seed), int(first_level_id), int(n_edits))
 
 
 def compute_gae(rewards, values, dones, gamma: float, lam: float, adv=None, returns=None,
@@ -290,12 +297,12 @@ def compute_gae(rewards, values, dones, gamma: float, lam: float, adv=None, retu
         adv = torch.empty((T, N), dtype=torch.float32, device=rewards.device)
     if returns is None and want_returns:
         returns = torch.empty((T, N), dtype=torch.float32, device=rewards.device)
-    _check(load_library().compute_gae(
+    _launch(rewards.device, "compute_gae", load_library().compute_gae,
         _ptr(rewards, torch.float32, (T, N), "rewards"),
         _ptr(values, torch.float32, (T + 1, N), "values"),
         _ptr(dones, torch.uint8, (T, N), "dones"), T, N, float(gamma), float(lam),
         _ptr(adv, torch.float32, (T, N), "adv"),
-        _ptr(returns, torch.float32, (T, N), "returns"), _stream()), "compute_gae")
+        _ptr(returns, torch.float32, (T, N), "returns"))
     return adv, returns
 
 
@@ -311,12 +318,12 @@ def replay_scores(rewards, values, dones, adv, gamma: float, rmax=None):
         rmax = torch.empty((N,), dtype=torch.float32, device=dev)
     maxmc = torch.empty((N,), dtype=torch.float32, device=dev)
     pvl = torch.empty((N,), dtype=torch.float32, device=dev)
-    _check(load_library().replay_scores(
+    _launch(rewards.device, "replay_scores", load_library().replay_scores,
         _ptr(rewards, torch.float32, (T, N), "rewards"),
         _ptr(values, torch.float32, (T + 1, N), "values"),
         _ptr(dones, torch.uint8, (T, N), "dones"),
         _ptr(adv, torch.float32, (T, N), "adv"), T, N, float(gamma), rmax_in,
-        rmax.data_ptr(), maxmc.data_ptr(), pvl.data_ptr(), _stream()), "replay_scores")
+        rmax.data_ptr(), maxmc.data_ptr(), pvl.data_ptr())
     return rmax, maxmc, pvl
 
 
@@ -328,8 +335,8 @@ def replay_distribution(scores, last_seen, now: int, rank: bool, temperature: fl
     K = scores.shape[0]
     if prob is None:
         prob = torch.empty((K,), dtype=torch.float32, device=scores.device)
-    _check(load_library().replay_distribution(
+    _launch(scores.device, "replay_distribution", load_library().replay_distribution,
         _ptr(scores, torch.float32, (K,), "scores"), _ptr(last_seen, torch.int32, (K,), "last_seen"),
         K, int(now), 1 if rank else 0, float(temperature), float(staleness_coef),
-        _ptr(prob, torch.float32, (K,), "prob"), _stream()), "replay_distribution")
+        _ptr(prob, torch.float32, (K,), "prob"))
     return prob

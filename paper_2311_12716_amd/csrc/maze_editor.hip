@@ -92,6 +92,7 @@ __global__ void k_editor_reset(EditorDev p, const int8_t *__restrict__ dir_init)
 extern "C" int editor_reset(editor_ctx *ctx, const int8_t *d_agent_dir_init, void *stream)
 {
     if (!ctx || !d_agent_dir_init) return MAZE_ENULL;
+    MAZE_DEVICE_CHECK(ctx);
     const EditorDev &p = ctx->dev;
     long long total = (long long)p.N * p.SW;
     hipLaunchKernelGGL(k_editor_reset, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,
@@ -134,6 +135,7 @@ extern "C" int editor_step(editor_ctx *ctx, const int32_t *d_actions, int n_step
                            int32_t *d_t, uint8_t *d_done, void *stream)
 {
     if (!ctx || !d_actions) return MAZE_ENULL;
+    MAZE_DEVICE_CHECK(ctx);
     if (n_steps < 1) return MAZE_EINVAL;
     const EditorDev &p = ctx->dev;
     hipStream_t st = (hipStream_t)stream;
@@ -178,6 +180,7 @@ extern "C" int editor_get_levels(editor_ctx *ctx, int8_t *d_walls, int32_t *d_ag
                                  int8_t *d_agent_dir, int32_t *d_goal_xy, void *stream)
 {
     if (!ctx) return MAZE_ENULL;
+    MAZE_DEVICE_CHECK(ctx);
     const EditorDev &p = ctx->dev;
     hipStream_t st = (hipStream_t)stream;
     if (d_walls) {

@@ -49,9 +49,24 @@ struct maze_ctx {
     StudentDev dev;
     int word64;             // rows need 64-bit words
     int variant;            // 0 auto, 1 per-cell kernels only
-    int device;
+    int device;             // the device that was current at maze_create; every call must run on it
+    int cus;                // its compute units and the LDS of one of them (device properties):
+    size_t lds_per_cu;      // they decide how many envs a workgroup of the rollout takes
     size_t workspace_bytes;
 };
+
+// MAZE_OK if the calling thread's current device is the one the context was created on.
+static inline int maze_same_device(int ctx_device)
+{
+    int now = -1;
+    if (hipGetDevice(&now) != hipSuccess) return MAZE_EHIP;
+    return now == ctx_device ? MAZE_OK : MAZE_EINVAL;
+}
+#define MAZE_DEVICE_CHECK(ctx)                          \
+    do {                                                \
+        int rc__ = maze_same_device((ctx)->device);     \
+        if (rc__ != MAZE_OK) return rc__;               \
+    } while (0)
 
 // ---------------------------------------------------------------------------
 // Teacher editor env: device-side layout.

@@ -147,6 +147,7 @@ int levelgen_launch(const editor_ctx *ctx, int mode, uint64_t seed, uint64_t fir
 extern "C" int editor_random_levels(editor_ctx *ctx, uint64_t seed, uint64_t first_level_id, void *stream)
 {
     if (!ctx) return MAZE_ENULL;
+    MAZE_DEVICE_CHECK(ctx);
     return levelgen_launch(ctx, GENERATE, seed, first_level_id, 0, (hipStream_t)stream);
 }
 
@@ -154,6 +155,7 @@ extern "C" int editor_mutate_levels(editor_ctx *ctx, uint64_t seed, uint64_t fir
                                     void *stream)
 {
     if (!ctx) return MAZE_ENULL;
+    MAZE_DEVICE_CHECK(ctx);
     if (n_edits < 0) return MAZE_EINVAL;
     if (n_edits == 0) return MAZE_OK;
     return levelgen_launch(ctx, MUTATE, seed, first_level_id, n_edits, (hipStream_t)stream);
@@ -163,6 +165,7 @@ extern "C" int editor_set_levels(editor_ctx *ctx, const int8_t *d_walls, const i
                                  const int8_t *d_agent_dir, const int32_t *d_goal_xy, void *stream)
 {
     if (!ctx || !d_walls || !d_agent_xy || !d_agent_dir || !d_goal_xy) return MAZE_ENULL;
+    MAZE_DEVICE_CHECK(ctx);
     const EditorDev &p = ctx->dev;
     const long long total = (long long)p.N * p.SW;
     hipLaunchKernelGGL(k_editor_set_levels, dim3((unsigned)((total + 255) / 256)), dim3(256), 0,

@@ -110,9 +110,10 @@ __global__ __launch_bounds__(256) void k_level_metrics(StudentDev p, int G, int3
 extern "C" int maze_level_metrics(maze_ctx *ctx, int32_t *d_n_walls, int32_t *d_path_len, void *stream)
 {
     if (!ctx) return MAZE_ENULL;
+    MAZE_DEVICE_CHECK(ctx);
     if (!d_n_walls && !d_path_len) return MAZE_OK;
     const StudentDev &p = ctx->dev;
-    if (p.H > 64) return MAZE_ESIZE;             // one lane per row of an env
+    // one lane per row of an env: H <= 64 holds for every context maze_create makes
     int G = 1;
     while (G < p.H) G <<= 1;
     const int per_wave = 64 / G;

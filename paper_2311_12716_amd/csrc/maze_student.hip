@@ -8,7 +8,9 @@
 // ------------------------------------------------------------------ host side
 static int student_dims(int N, int H, int W, int view, StudentDev *d, int *word64)
 {
-    if (N <= 0 || H <= 0 || W <= 0 || view <= 0 || (view & 1) == 0) return MAZE_EINVAL;
+    // view >= 3: the padding of view - 1 rings of wall is also what stops a forward step at the
+    // edge of the interior, so a 1 x 1 view (no ring) is not a shape this layout can hold
+    if (N <= 0 || H <= 0 || W <= 0 || view < 3 || (view & 1) == 0) return MAZE_EINVAL;
     int P = view - 1;
     int HP = H + 2 * P, WP = W + 2 * P;
     if (HP > 64 || WP > 64) return MAZE_ESIZE;
@@ -75,7 +77,11 @@ extern "C" int maze_create(maze_ctx **out, int N, int H, int W, int view, int ma
     c->dev.obs_encoding = 0;
     c->dev.obs_occlusion = 0;
     c->workspace_bytes = workspace_bytes;
-    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return MAZE_EHIP; }
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&c->device) != hipSuccess ||
+        hipGetDeviceProperties(&prop, c->device) != hipSuccess) { delete c; return MAZE_EHIP; }
+    c->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+    c->lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
     *out = c;
     return MAZE_OK;
 }
@@ -264,6 +270,7 @@ extern "C" int maze_reset_to_levels(maze_ctx *ctx, const int8_t *d_walls,
                                     const int32_t *d_goal_xy, void *stream)
 {
     if (!ctx || !d_walls || !d_agent_xy || !d_agent_dir || !d_goal_xy) return MAZE_ENULL;
+    MAZE_DEVICE_CHECK(ctx);
     hipStream_t st = (hipStream_t)stream;
     const StudentDev &p = ctx->dev;
     if (ctx->word64)
@@ -397,23 +404,43 @@ __global__ void k_render_percell(StudentDev p, int n_begin, int8_t *__restrict__
     render_cells<Word>(p, grid_n, pose, goal, obs + (size_t)n * p.k * p.k * 3);
 }
 
-// Implemented in maze_student_tiled.hip: launches the tiled kernel on the first
-// *covered envs (a multiple of the workgroup size; 0 if the shape is not covered) and returns 1 if
-// it launched.  n_steps == 0 renders the current state.
+// Implemented in maze_student_tiled.hip: launches the tiled kernels on the first *covered envs
+// (0 if the call is not one they take) and returns 1 if it launched, 0 if not, or a negative
+// error code.  n_steps == 0 renders the current state.
 int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_steps,
                          float *d_reward, uint8_t *d_done, int8_t *d_obs, int *covered,
                          hipStream_t st);
+
+int student_tiled_plan(int k, int N, int SP, bool variant, bool occlusion, int cus, size_t budget,
+                       int *epw, size_t *lds_bytes);
+
+extern "C" int maze_rollout_plan(int N, int H, int W, int view, int encoding, int occlusion, int cus,
+                                 size_t lds_per_cu, int *envs_per_workgroup, size_t *lds_bytes)
+{
+    if (!envs_per_workgroup || !lds_bytes) return MAZE_ENULL;
+    StudentDev d;
+    int w64;
+    const int rc = student_dims(N, H, W, view, &d, &w64);
+    if (rc != MAZE_OK) return rc;
+    if (cus < 1 || encoding < 0 || encoding > 1 || occlusion < 0 || occlusion > 1) return MAZE_EINVAL;
+    const size_t budget = lds_per_cu > 1024 ? lds_per_cu - 1024 : 0;
+    return student_tiled_plan(view, N, d.SP, encoding || occlusion, occlusion != 0, cus, budget,
+                              envs_per_workgroup, lds_bytes);
+}
 
 extern "C" int maze_step(maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
                          uint8_t *d_done, int8_t *d_obs, void *stream)
 {
     if (!ctx || !d_actions || !d_reward || !d_done) return MAZE_ENULL;
     if (n_steps < 1) return MAZE_EINVAL;
+    MAZE_DEVICE_CHECK(ctx);
     hipStream_t st = (hipStream_t)stream;
     const StudentDev &p = ctx->dev;
     int covered = 0;
-    if (ctx->variant == 0)
-        student_tiled_launch(ctx, d_actions, n_steps, d_reward, d_done, d_obs, &covered, st);
+    if (ctx->variant == 0) {
+        const int rc = student_tiled_launch(ctx, d_actions, n_steps, d_reward, d_done, d_obs, &covered, st);
+        if (rc < 0) return rc;
+    }
     if (covered < p.N) {
         dim3 grid((p.N - covered + 63) / 64), block(64);
         if (ctx->word64)
@@ -430,11 +457,14 @@ extern "C" int maze_step(maze_ctx *ctx, const int8_t *d_actions, int n_steps, fl
 extern "C" int maze_render_obs(maze_ctx *ctx, int8_t *d_obs, void *stream)
 {
     if (!ctx || !d_obs) return MAZE_ENULL;
+    MAZE_DEVICE_CHECK(ctx);
     hipStream_t st = (hipStream_t)stream;
     const StudentDev &p = ctx->dev;
     int covered = 0;
-    if (ctx->variant == 0)
-        student_tiled_launch(ctx, nullptr, 0, nullptr, nullptr, d_obs, &covered, st);
+    if (ctx->variant == 0) {
+        const int rc = student_tiled_launch(ctx, nullptr, 0, nullptr, nullptr, d_obs, &covered, st);
+        if (rc < 0) return rc;
+    }
     if (covered < p.N) {
         dim3 grid((p.N - covered + 63) / 64), block(64);
         if (ctx->word64)
@@ -512,6 +542,7 @@ extern "C" int maze_get_state(maze_ctx *ctx, int32_t *d_xy, int8_t *d_dir, int32
                               void *stream)
 {
     if (!ctx) return MAZE_ENULL;
+    MAZE_DEVICE_CHECK(ctx);
     const StudentDev &p = ctx->dev;
     hipLaunchKernelGGL(k_get_state, dim3((p.N + 255) / 256), dim3(256), 0, (hipStream_t)stream, p,
                        d_xy, d_dir, d_t);
@@ -524,6 +555,7 @@ extern "C" int maze_set_state(maze_ctx *ctx, const int32_t *d_xy, const int8_t *
 {
     if (!ctx) return MAZE_ENULL;
     if (!d_xy && !d_dir && !d_t) return MAZE_OK;
+    MAZE_DEVICE_CHECK(ctx);
     const StudentDev &p = ctx->dev;
     hipLaunchKernelGGL(k_set_state, dim3((p.N + 255) / 256), dim3(256), 0, (hipStream_t)stream, p,
                        d_xy, d_dir, d_t);
@@ -535,6 +567,7 @@ extern "C" int maze_get_levels(maze_ctx *ctx, int8_t *d_walls, int32_t *d_agent_
                                int8_t *d_agent_dir, int32_t *d_goal_xy, void *stream)
 {
     if (!ctx) return MAZE_ENULL;
+    MAZE_DEVICE_CHECK(ctx);
     const StudentDev &p = ctx->dev;
     hipStream_t st = (hipStream_t)stream;
     if (d_walls) {

@@ -33,17 +33,10 @@
 #include "maze_store_device.h"
 #include "maze_student_device.h"
 
-// Compile-time knobs (overridable for measurements).
-#ifndef MAZE_SPB
-#define MAZE_SPB 8
-#endif
-#ifndef MAZE_STORE_WAVES
-#define MAZE_STORE_WAVES 10
-#endif
-
 namespace {
 
-constexpr int SPB = MAZE_SPB;   // steps per barrier: every stage handles SPB steps between barriers
+constexpr int SPB = 8;            // steps per barrier: every stage handles SPB steps between barriers
+constexpr int STORE_WAVES = 10;   // store waves of a workgroup, at most
 // Steps a stage handles together (all reads, then all writes): the largest power of two
 // that divides SPB and keeps the group's registers within `budget` dwords.
 constexpr int step_group(int dwords_per_step, int budget)
@@ -68,7 +61,7 @@ struct View {
     static constexpr int NDYN = EPW / LA;          // dynamics waves (and records waves)
     static constexpr int NWIN = EPW * SB / 16;     // 16-bit windows per workgroup step
     static constexpr int ROUNDS = (NWIN + 63) / 64;
-    static constexpr int NC = ROUNDS < MAZE_STORE_WAVES ? ROUNDS : MAZE_STORE_WAVES;   // store waves
+    static constexpr int NC = ROUNDS < STORE_WAVES ? ROUNDS : STORE_WAVES;   // store waves
     static constexpr int WAVES = 3 * NDYN + NC;
     // actions: one 16-byte load per lane covers 16 envs of one step, so a dynamics wave
     // stages ACT_BLOCK steps of its LA envs per load
@@ -114,10 +107,9 @@ struct Lds {
     {
         return (4 * SP * WordOps<Word>::DW) | 1;
     }
-    __host__ static size_t bytes(int SP, bool grid_in_lds)
-    {
-        return 4 * (size_t)(GRID0 + (grid_in_lds ? EPW * grid_stride(SP) : 0));
-    }
+    // with the staged grids of the EPW envs / without (the single-step kernel reads them from L2)
+    __host__ static size_t bytes(int SP) { return 4 * (size_t)(GRID0 + EPW * grid_stride(SP)); }
+    __host__ static size_t bytes_without_grids() { return 4 * (size_t)GRID0; }
 };
 
 // The K wall words of an env's view (row 0 farthest).  From LDS or, for grids too
@@ -502,12 +494,10 @@ __device__ __forceinline__ void stage_grids(const StudentDev &p, uint32_t *lds, 
 
 // ------------------------------------------------------------------ rollout
 // Wall word of row `row` of heading frame `dir` of one env.
-template <typename Word, bool GRID_LDS>
-__device__ __forceinline__ Word wall_row(const uint32_t *lds_env, const Word *glob_env, int SP,
-                                         int dir, int row)
+template <typename Word>
+__device__ __forceinline__ Word wall_row(const uint32_t *lds_env, int SP, int dir, int row)
 {
     const int r = (int)__umul24((unsigned)dir, (unsigned)SP) + row;
-    if (!GRID_LDS) return glob_env[r];
     if (sizeof(Word) == 4) return (Word)lds_env[r];
     return (Word)(((uint64_t)lds_env[2 * r + 1] << 32) | lds_env[2 * r]);
 }
@@ -543,8 +533,7 @@ struct DynConst {
     Word ahead_start;                  // row ahead of the start pose
     uint32_t tmax;
     int HPm1, WPm1, SP;
-    const uint32_t *lds_env;
-    const Word *glob_env;
+    const uint32_t *lds_env;           // this env's staged grids
     const uint8_t *act_lds;            // this env's column of the action ring
     uint32_t act_mask, act_row;        // ring size - 1 and row pitch, bytes
 };
@@ -559,7 +548,7 @@ constexpr uint32_t ST_OUTCOME_MASK = ~(3u << ST_HEADING_SHIFT);
 // Position and goal offset are pairs of 16-bit numbers: a right turn maps (Xd,Yd) to
 // (Yd, bits-1-Xd) and the goal vector (ahead, right) to (right, -ahead), a left turn to
 // (rows-1-Yd, Xd) and (-right, ahead) -- each one packed multiply-add of the swapped pair.
-template <typename Word, int EPW, bool GRID_LDS, bool SQUARE>
+template <typename Word, int EPW, bool SQUARE>
 __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word> &c, uint32_t *st)
 {
     const uint32_t a = s.a_next;
@@ -581,7 +570,7 @@ __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word>
     next = tl ? left : next;
     const int nd = (s.d + (tl ? 3 : 0) + (tr ? 1 : 0)) & 3;
     const Word ahead = s.use_start ? c.ahead_start : (s.use_keep ? s.ahead_keep : s.spec);
-    s.spec = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, c.SP, nd, (int)(as_word(next) >> 16) - 1);
+    s.spec = wall_row<Word>(c.lds_env, c.SP, nd, (int)(as_word(next) >> 16) - 1);
     // the wall test for the current pose
     const int xd = (int)(s.pos & 0xFFFFu);
     const int blocked = sizeof(Word) == 4 ? (int)__builtin_amdgcn_ubfe((uint32_t)ahead, xd, 1)
@@ -646,7 +635,7 @@ __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word>
 // PARTIAL: the workgroup may hold fewer than EPW envs (the last envs of a batch, n_end - env0 of
 // them): idle lanes repeat env 0 of the workgroup and write nothing, pieces beyond the last
 // env's bytes are not stored.
-template <int K, typename Word, int EPW, bool GRID_LDS, bool SQUARE, int MODE = 0, bool PARTIAL = false>
+template <int K, typename Word, int EPW, bool SQUARE, int MODE = 0, bool PARTIAL = false>
 __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     StudentDev p, int n_begin, int n_end, const int8_t *__restrict__ actions, int n_steps,
     float *__restrict__ reward, uint8_t *__restrict__ done, int8_t *__restrict__ obs)
@@ -673,7 +662,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     static_assert(!PARTIAL || V::NDYN == 1, "partly filled workgroups: 64 envs at most");
 
     fill_lut<K>(lds + L::LUT, tid, NT);
-    if (GRID_LDS) stage_grids<L, Word>(p, lds, tid, NT, env0, count);
+    stage_grids<L, Word>(p, lds, tid, NT, env0, count);
     if (MODE == 1) {
         fill_typed_table(lds + L::TYPED, tid, NT);
         if (p.obs_occlusion) fill_visibility_table<K>((uint16_t *)(lds + L::VIS), tid, NT);
@@ -702,8 +691,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                        ((uint32_t)((int)(g_start & 255) - sxd) << 16);
         c.tmax = (uint32_t)p.max_steps;
         c.HPm1 = p.HP - 1; c.WPm1 = p.WP - 1; c.SP = SP;
-        c.lds_env = lds + L::GRID0 + e * (GRID_LDS ? L::grid_stride(SP) : 0);
-        c.glob_env = (const Word *)p.grids + (size_t)n * 4 * SP;
+        c.lds_env = lds + L::GRID0 + e * L::grid_stride(SP);
         c.act_lds = (const uint8_t *)(lds + L::ACT) + e;
         c.act_row = L::ACT_ROW;
         c.act_mask = 2 * ACT_BLOCK * L::ACT_ROW - 1;
@@ -718,8 +706,8 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         *(uint4 *)act_stage = load_actions<PARTIAL>(act_lane, stage_row, last, N, act_valid);
         uint4 act_regs = load_actions<PARTIAL>(act_lane, ACT_BLOCK + stage_row, last, N, act_valid);
         __syncthreads();                                             // barrier 0 (set-up)
-        c.ahead_start = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, SP, c.sd, syd - 1);
-        s.ahead_keep = wall_row<Word, GRID_LDS>(c.lds_env, c.glob_env, SP, s.d, yd0 - 1);
+        c.ahead_start = wall_row<Word>(c.lds_env, SP, c.sd, syd - 1);
+        s.ahead_keep = wall_row<Word>(c.lds_env, SP, s.d, yd0 - 1);
         s.spec = s.ahead_keep;
         s.use_start = false; s.use_keep = true;
         s.act_off = 0;
@@ -731,7 +719,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                 if (!MAZE_STEP_ON(u)) continue;
                 // (idle lanes of a partly filled wave repeat env 0 of the workgroup: the same
                 // values to the same addresses; stepping all lanes keeps the flags plain masks)
-                dyn_step<Word, EPW, GRID_LDS, SQUARE>(s, c, st_e + (par * SPB + u) * L::ST_SIZE);
+                dyn_step<Word, EPW, SQUARE>(s, c, st_e + (par * SPB + u) * L::ST_SIZE);
                 // stage the next block of actions half way through the current one
                 if ((i & (ACT_BLOCK - 1)) == ACT_BLOCK / 2) {
                     const int nb = i / ACT_BLOCK + 1;
@@ -754,8 +742,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         const int el = UPL == 2 ? (lane & 31) : lane;
         const bool active = el < live_lanes;
         const int e = (wave - V::NDYN) * 64 + (active ? el : 0);
-        const uint32_t *lds_env = lds + L::GRID0 + e * (GRID_LDS ? L::grid_stride(SP) : 0);
-        const Word *glob_env = (const Word *)p.grids + (size_t)(env0 + e) * 4 * SP;
+        const uint32_t *lds_env = lds + L::GRID0 + e * L::grid_stride(SP);
         const uint32_t *st_lane = lds + L::ST + half * L::ST_SIZE + e;
         uint32_t *vw_lane = lds + L::VW + half * L::VW_SIZE + e;
         __syncthreads();                                             // barrier 0 (set-up)
@@ -770,7 +757,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                         pose[w] = st[0]; g[w] = st[EPW]; out[w] = st[2 * EPW];
                     }
                     _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half))
-                        load_view_rows<K, Word, GRID_LDS>(lds_env, glob_env, SP,
+                        load_view_rows<K, Word, true>(lds_env, nullptr, SP,
                                                           (out[w] >> ST_HEADING_SHIFT) & 3, pose[w] >> 16,
                                                           rows[w]);
                     _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half)) {
@@ -936,7 +923,15 @@ __global__ __launch_bounds__(REPW) void k_step_render_tiled(
     }
 }
 
-constexpr size_t LDS_PER_CU = 160 * 1024;     // gfx950
+// LDS a workgroup of a rollout may use on this device: what a CU has, less 1 KB that the
+// runtime may claim for itself.
+inline size_t lds_budget(const maze_ctx *ctx) { return ctx->lds_per_cu > 1024 ? ctx->lds_per_cu - 1024 : 0; }
+
+// The largest grids (64 rows of 64 bits in each of the four frames) of 32 envs fit beside the
+// pipeline buffers of every flavour in the 160 KB of a gfx950 CU, so a rollout with 32 envs per
+// workgroup exists for every shape the library accepts.
+static_assert(Lds<7, uint64_t, 32, 1>::GRID0 * 4 + 32 * 4 * ((4 * 64 * 2) | 1) <= 159 * 1024,
+              "32 envs per workgroup must fit in LDS for every supported shape");
 
 // Raise a kernel's dynamic LDS limit above the 64 KB default (remembered in *granted).
 template <typename Kernel>
@@ -951,7 +946,8 @@ bool allow_large_lds(Kernel kernel, size_t bytes, size_t *granted)
 }
 
 // Runs the rollout kernel on envs [n_begin, n_begin + EPW * (n_envs / EPW)) -- with PARTIAL on all
-// n_envs, the last workgroup partly filled -- and returns how many envs that is.
+// n_envs, the last workgroup partly filled -- and returns how many envs that is, or MAZE_EHIP
+// if the device does not grant the LDS the workgroup needs.
 template <int K, typename Word, int EPW, int MODE = 0, bool PARTIAL = false>
 int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d_actions, int n_steps,
                    float *d_reward, uint8_t *d_done, int8_t *d_obs, hipStream_t st)
@@ -962,8 +958,8 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
     const int groups = PARTIAL ? (n_envs + EPW - 1) / EPW : n_envs / EPW;
     if (groups < 1) return 0;
     const int n_end = PARTIAL ? n_begin + n_envs : n_begin + groups * EPW;
-    const bool grid_lds = L::bytes(p.SP, true) <= LDS_PER_CU - 1024;
-    const size_t shmem = L::bytes(p.SP, grid_lds);
+    const size_t shmem = L::bytes(p.SP);
+    if (shmem > lds_budget(ctx)) return MAZE_EHIP;
     const dim3 grid(groups), block(64 * V::WAVES);
     // the square-grid flavour exists for the plain kernel only
     constexpr bool PLAIN = MODE == 0 && !PARTIAL;
@@ -971,28 +967,65 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
     // largest LDS size granted so far, per kernel flavour and device (the attribute belongs to
     // the kernel on one device); a race between host threads only repeats the call
     static size_t granted_all[2][16] = {};
-    size_t *granted = &granted_all[0][ctx->device & 15];
-    constexpr int FLAVOUR_STRIDE = 16;
-    if (grid_lds && square) {
-        auto kern = k_student_rollout<K, Word, EPW, true, PLAIN, MODE, PARTIAL>;
-        if (!allow_large_lds(kern, shmem, granted)) return 0;
-        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
-                           d_done, d_obs);
-    } else if (grid_lds) {
-        auto kern = k_student_rollout<K, Word, EPW, true, false, MODE, PARTIAL>;
-        if (!allow_large_lds(kern, shmem, granted + FLAVOUR_STRIDE)) return 0;
+    size_t *granted = &granted_all[square ? 0 : 1][ctx->device & 15];
+    if (square) {
+        auto kern = k_student_rollout<K, Word, EPW, PLAIN, MODE, PARTIAL>;
+        if (!allow_large_lds(kern, shmem, granted)) return MAZE_EHIP;
         hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
                            d_done, d_obs);
     } else {
-        auto kern = k_student_rollout<K, Word, EPW, false, false, MODE, PARTIAL>;
+        auto kern = k_student_rollout<K, Word, EPW, false, MODE, PARTIAL>;
+        if (!allow_large_lds(kern, shmem, granted)) return MAZE_EHIP;
         hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
                            d_done, d_obs);
     }
     return n_end - n_begin;
 }
 
-// Envs per workgroup: the largest of 128 / 64 / 32 whose grids fit in LDS and that still
-// gives every CU a workgroup; small batches take 32 so that more CUs take part.
+// The envs the large workgroups left over, and small batches: workgroups of 32 in one more
+// launch on the same stream; if their number is not a multiple of 32 the flavour whose last
+// workgroup may be partly filled takes them all.
+template <int K, typename Word, int MODE>
+int launch_rest(const maze_ctx *ctx, int covered, const int8_t *d_actions, int n_steps, float *d_reward,
+                uint8_t *d_done, int8_t *d_obs, hipStream_t st)
+{
+    if (covered < 0) return covered;
+    const int rest = ctx->dev.N - covered;
+    if (rest <= 0) return covered;
+    const int more = rest % 32 == 0
+        ? launch_rollout<K, Word, 32, MODE>(ctx, covered, rest, d_actions, n_steps, d_reward, d_done, d_obs, st)
+        : launch_rollout<K, Word, 32, MODE, true>(ctx, covered, rest, d_actions, n_steps, d_reward, d_done,
+                                                  d_obs, st);
+    return more < 0 ? more : covered + more;
+}
+
+// Envs per workgroup of a rollout's main launch: the largest of 128 / 64 / 32 whose grids fit
+// in LDS and that still gives every CU a workgroup; small batches take 32 so that more CUs
+// take part.  Observation variants: 128 for typed bytes alone (as fast as the plain
+// observation), at most 64 with occlusion (the records stage is the slow one there: more
+// workgroups do better).  MAZE_EHIP if not even 32 envs fit into `budget` bytes of LDS.
+template <int K, typename Word>
+int plan_k(int N, int SP, bool variant, bool occlusion, int cus, size_t budget, int *epw, size_t *lds_bytes)
+{
+    const size_t b128 = variant ? Lds<K, Word, 128, 1>::bytes(SP) : Lds<K, Word, 128>::bytes(SP);
+    const size_t b64 = variant ? Lds<K, Word, 64, 1>::bytes(SP) : Lds<K, Word, 64>::bytes(SP);
+    const size_t b32 = variant ? Lds<K, Word, 32, 1>::bytes(SP) : Lds<K, Word, 32>::bytes(SP);
+    if (b32 > budget) return MAZE_EHIP;
+    if (!occlusion && N >= 128 * (long long)cus && b128 <= budget) { *epw = 128; *lds_bytes = b128; }
+    else if (N >= 64 * (long long)cus && b64 <= budget) { *epw = 64; *lds_bytes = b64; }
+    else { *epw = 32; *lds_bytes = b32; }
+    return MAZE_OK;
+}
+
+template <int K>
+int plan_view_size(int N, int SP, bool variant, bool occlusion, int cus, size_t budget, int *epw,
+                   size_t *lds_bytes)
+{
+    return SP > 32 ? plan_k<K, uint64_t>(N, SP, variant, occlusion, cus, budget, epw, lds_bytes)
+                   : plan_k<K, uint32_t>(N, SP, variant, occlusion, cus, budget, epw, lds_bytes);
+}
+
+// Returns the number of envs covered (all of them for a rollout) or a negative error code.
 template <int K, typename Word>
 int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_reward,
              uint8_t *d_done, int8_t *d_obs, hipStream_t st)
@@ -1001,7 +1034,7 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
     if (n_steps <= 1) {
         // render only (0) or the single step of a policy loop (1): one light launch
         if (p.N < REPW) return 0;
-        const size_t shmem_render = Lds<K, Word, REPW>::bytes(p.SP, false);
+        const size_t shmem_render = Lds<K, Word, REPW>::bytes_without_grids();
         const dim3 grid(p.N / REPW), block(REPW);
         const bool variant = p.obs_encoding || p.obs_occlusion;
         if (n_steps == 0 && !variant)
@@ -1018,50 +1051,26 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
                                d_actions, d_reward, d_done, d_obs);
         return REPW * (p.N / REPW);
     }
-    if (p.obs_encoding || p.obs_occlusion) {
-        // observation variants: 128 (typed bytes only: as fast as the plain observation) or 64
-        // (occluded: the records stage is the slow one, more workgroups do better) envs per
-        // workgroup if that gives every CU a workgroup and the grids fit in LDS, then 32
-        int done_envs = 0;
-        if (!p.obs_occlusion && p.N >= 128 * 256 &&
-            Lds<K, Word, 128, 1>::bytes(p.SP, true) <= LDS_PER_CU - 1024)
-            done_envs = launch_rollout<K, Word, 128, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done,
-                                                        d_obs, st);
-        else if (p.N >= 64 * 256 && Lds<K, Word, 64, 1>::bytes(p.SP, true) <= LDS_PER_CU - 1024)
-            done_envs = launch_rollout<K, Word, 64, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done,
-                                                       d_obs, st);
-        const int rest = p.N - done_envs;
-        if (rest > 0 && rest % 32 == 0)
-            done_envs += launch_rollout<K, Word, 32, 1>(ctx, done_envs, rest, d_actions, n_steps, d_reward,
-                                                        d_done, d_obs, st);
-        else if (rest > 0)
-            done_envs += launch_rollout<K, Word, 32, 1, true>(ctx, done_envs, rest, d_actions, n_steps,
-                                                              d_reward, d_done, d_obs, st);
-        return done_envs;
+    const bool variant = p.obs_encoding || p.obs_occlusion;
+    int epw = 0, covered = 0;
+    size_t lds_bytes = 0;
+    const int rc = plan_k<K, Word>(p.N, p.SP, variant, p.obs_occlusion != 0, ctx->cus, lds_budget(ctx), &epw,
+                                   &lds_bytes);
+    if (rc != MAZE_OK) return rc;
+    if (variant) {
+        if (epw == 128)
+            covered = launch_rollout<K, Word, 128, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done,
+                                                      d_obs, st);
+        else if (epw == 64)
+            covered = launch_rollout<K, Word, 64, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done,
+                                                     d_obs, st);
+        return launch_rest<K, Word, 1>(ctx, covered, d_actions, n_steps, d_reward, d_done, d_obs, st);
     }
-    int covered = 0;
-#ifdef MAZE_FORCE_EPW
-    covered = launch_rollout<K, Word, MAZE_FORCE_EPW>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
-#else
-    const int cus = 256;
-    const bool fit128 = Lds<K, Word, 128>::bytes(p.SP, true) <= LDS_PER_CU - 1024;
-    const bool fit64 = Lds<K, Word, 64>::bytes(p.SP, true) <= LDS_PER_CU - 1024;
-    if (p.N >= 128 * cus && fit128)
+    if (epw == 128)
         covered = launch_rollout<K, Word, 128>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
-    else if (p.N >= 64 * cus && fit64)
+    else if (epw == 64)
         covered = launch_rollout<K, Word, 64>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
-#endif
-    // Small batches, and the envs left over by a large workgroup size, go to workgroups of 32
-    // in one more launch on the same stream; if their number is not a multiple of 32 the
-    // flavour whose last workgroup may be partly filled takes them all.
-    const int rest = p.N - covered;
-    if (rest > 0 && rest % 32 == 0)
-        covered += launch_rollout<K, Word, 32>(ctx, covered, rest, d_actions, n_steps, d_reward, d_done,
-                                               d_obs, st);
-    else if (rest > 0)
-        covered += launch_rollout<K, Word, 32, 0, true>(ctx, covered, rest, d_actions, n_steps, d_reward,
-                                                        d_done, d_obs, st);
-    return covered;
+    return launch_rest<K, Word, 0>(ctx, covered, d_actions, n_steps, d_reward, d_done, d_obs, st);
 }
 
 // Word size dispatch for one view size; the translation units maze_student_tiled_k*.hip wrap it.

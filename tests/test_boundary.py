@@ -44,6 +44,11 @@ def test_workspace_size_validation(lib):
     assert lib.maze_workspace_bytes(32768, 13, 13, 5, ctypes.byref(n)) == 0 and n.value > 0
     assert n.value % 256 == 0
     assert lib.maze_workspace_bytes(8, 13, 13, 4, ctypes.byref(n)) == -1      # even view
+    # a 1 x 1 view would leave the grid without the ring of wall that bounds the moves
+    assert lib.maze_workspace_bytes(8, 13, 13, 1, ctypes.byref(n)) == -1
+    assert lib.maze_workspace_bytes(8, 13, 13, -3, ctypes.byref(n)) == -1
+    h = ctypes.c_void_p()
+    assert lib.maze_create(ctypes.byref(h), 8, 13, 13, 1, 250, 256, 1 << 20) == -1 and h.value is None
     assert lib.maze_workspace_bytes(0, 13, 13, 5, ctypes.byref(n)) == -1
     assert lib.maze_workspace_bytes(8, 13, 0, 5, ctypes.byref(n)) == -1
     assert lib.maze_workspace_bytes(8, 60, 60, 7, ctypes.byref(n)) == -3     # padded rows > 64 bits
@@ -90,6 +95,43 @@ def test_level_tools_reject_bad_arguments_before_touching_the_gpu(lib):
     assert lib.replay_distribution(256, 256, 8, 0, 1, 0.0, 0.3, 256, None) == -1       # temperature
     assert lib.replay_distribution(256, 256, 8, 0, 1, 0.3, 1.5, 256, None) == -1       # staleness
     assert lib.replay_distribution(256, 256, 1 << 20, 0, 1, 0.3, 0.3, 256, None) == -3  # K too large
+
+
+def test_rollout_plan_and_the_lds_error_path(lib):
+    """Which workgroup size a rollout takes, from the device's unit count and LDS size; a device
+    whose LDS cannot hold 32 envs gets MAZE_EHIP (what maze_step then returns), never a
+    silent switch to the slow kernel."""
+    epw, lds = ctypes.c_int(-1), ctypes.c_size_t(0)
+
+    def plan(N, H, W, k, enc=0, occ=0, cus=256, per_cu=160 * 1024):
+        rc = lib.maze_rollout_plan(N, H, W, k, enc, occ, cus, per_cu, ctypes.byref(epw), ctypes.byref(lds))
+        return rc, epw.value, lds.value
+
+    # the benchmark configurations on a 256-unit device with 160 KB per unit
+    rc, e, b = plan(32768, 13, 13, 5)
+    assert (rc, e) == (0, 128) and 100 * 1024 < b <= 159 * 1024
+    assert plan(32768, 13, 13, 5, enc=1)[:2] == (0, 128)
+    assert plan(32768, 13, 13, 5, occ=1)[:2] == (0, 64)
+    assert plan(16384, 13, 13, 5)[:2] == (0, 64)
+    assert plan(4096, 13, 13, 5)[:2] == (0, 32)
+    assert plan(32, 13, 13, 5)[:2] == (0, 32)
+    assert plan(8192, 51, 51, 7)[:2] == (0, 32)
+    # fewer units: large workgroups from smaller batches on
+    assert plan(8192, 13, 13, 5, cus=64)[:2] == (0, 128)
+    # the same shapes with the 64 KB of an older part: smaller workgroups, still the fast kernel
+    rc, e, b = plan(32768, 13, 13, 5, per_cu=64 * 1024)
+    assert rc == 0 and e < 128 and b <= 63 * 1024
+    # the largest grids with view 7 and both variants on need 126 KB for 32 envs
+    rc, e, b = plan(64, 52, 52, 7, enc=1, occ=1)
+    assert (rc, e) == (0, 32) and 120 * 1024 < b <= 127 * 1024
+    assert plan(64, 52, 52, 7, enc=1, occ=1, per_cu=64 * 1024)[0] == -4      # MAZE_EHIP
+    assert plan(8192, 51, 51, 7, per_cu=64 * 1024)[0] == -4
+    # view sizes the store-layout kernels do not take: no error, no workgroup size
+    assert plan(64, 13, 13, 9)[:2] == (0, 0)
+    # argument errors
+    assert plan(64, 13, 13, 4)[0] == -1 and plan(64, 13, 13, 5, enc=2)[0] == -1
+    assert plan(64, 13, 13, 5, cus=0)[0] == -1 and plan(64, 60, 60, 7)[0] == -3
+    assert lib.maze_rollout_plan(64, 13, 13, 5, 0, 0, 256, 160 * 1024, None, ctypes.byref(lds)) == -2
 
 
 def test_strerror_names_every_code(lib):
