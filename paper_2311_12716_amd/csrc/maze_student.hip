@@ -36,6 +36,27 @@ static StudentLayout student_layout(const StudentDev &d, int word64)
     return L;
 }
 
+// Point a context at its workspace (device memory laid out by student_layout) with the
+// defaults of a fresh env: automatic kernel choice, plain observation.
+static void student_bind(maze_ctx *c, StudentDev d, int word64, int max_steps, void *d_workspace,
+                         const StudentLayout &L)
+{
+    char *ws = (char *)d_workspace;
+    d.max_steps = max_steps;
+    d.pose = (uint32_t *)(ws + L.pose);
+    d.tcount = (uint32_t *)(ws + L.tcount);
+    d.start = (uint32_t *)(ws + L.start);
+    d.goalrot = (uint32_t *)(ws + L.goalrot);
+    d.grids = ws + L.grids;
+    d.reward_slope = 0.9 / (double)max_steps;
+    d.obs_encoding = 0;
+    d.obs_occlusion = 0;
+    c->dev = d;
+    c->word64 = word64;
+    c->variant = 0;
+    c->workspace_bytes = L.total;
+}
+
 extern "C" int maze_workspace_bytes(int N, int H, int W, int view, size_t *out)
 {
     if (!out) return MAZE_ENULL;
@@ -63,19 +84,7 @@ extern "C" int maze_create(maze_ctx **out, int N, int H, int W, int view, int ma
     if (workspace_bytes < L.total) return MAZE_ESIZE;
     maze_ctx *c = new (std::nothrow) maze_ctx;
     if (!c) return MAZE_EINVAL;
-    char *ws = (char *)d_workspace;
-    d.max_steps = max_steps;
-    d.pose = (uint32_t *)(ws + L.pose);
-    d.tcount = (uint32_t *)(ws + L.tcount);
-    d.start = (uint32_t *)(ws + L.start);
-    d.goalrot = (uint32_t *)(ws + L.goalrot);
-    d.grids = ws + L.grids;
-    d.reward_slope = 0.9 / (double)max_steps;
-    c->dev = d;
-    c->word64 = w64;
-    c->variant = 0;
-    c->dev.obs_encoding = 0;
-    c->dev.obs_occlusion = 0;
+    student_bind(c, d, w64, max_steps, d_workspace, L);
     c->workspace_bytes = workspace_bytes;
     hipDeviceProp_t prop;
     if (hipGetDevice(&c->device) != hipSuccess ||

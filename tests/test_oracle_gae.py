@@ -86,3 +86,20 @@ def test_a_done_in_the_middle_decouples_the_two_halves():
     adv2, _ = oracle.compute_gae(r2, V2, d, 0.995, 0.98)
     assert (adv[:25] == adv2[:25]).all()
     assert not np.allclose(adv[25:], adv2[25:])
+
+
+@pytest.mark.parametrize("reward,peak", [(0.5, 20.0), (1.0, 40.0)])
+def test_dense_rewards_reach_the_geometric_limit(reward, peak):
+    """Dense rewards, no episode ends, V = 0: A_t = r (1 - (gamma lambda)^(T-t)) / (1 - gamma lambda),
+    which climbs to r / (1 - 0.995 * 0.98) = 40.16 r -- the largest magnitudes the recurrence
+    produces with the paper's gamma and lambda."""
+    T, N, g, l = 512, 2, 0.995, 0.98
+    r = np.full((T, N), reward, np.float32)
+    V = np.zeros((T + 1, N), np.float32)
+    d = np.zeros((T, N), np.uint8)
+    adv, ret = oracle.compute_gae(r, V, d, g, l)
+    gl = g * l
+    want = reward * (1 - gl ** (T - np.arange(T))) / (1 - gl)
+    assert np.allclose(adv, want[:, None], rtol=1e-12, atol=0)
+    assert (ret == adv).all()
+    assert peak < adv.max() < 1.01 * peak * 1.004 + 0.2

@@ -363,6 +363,32 @@ def test_gae_shapes(T, N, g, l):
     assert none is None and bool((adv2 == adv).all())
 
 
+@pytest.mark.parametrize("scale,peak", [(0.5, 20.0), (1.0, 40.0)])
+def test_gae_at_large_magnitudes(scale, peak):
+    """Dense rewards drive |A| to scale / (1 - gamma lambda) = 40 scale.  The kernel carries the
+    recurrence in double and rounds once, so its float32 output is within half a float32 spacing
+    of the oracle's double everywhere; 1e-6 absolute follows wherever |A| < 32 (spacing 1.9e-6
+    below 32, 3.8e-6 from 32 on, where no float32 result can promise 1e-6)."""
+    T, N, g, l = 512, 2048, 0.995, 0.98
+    rng = np.random.default_rng(int(100 * scale))
+    r = (scale * (0.75 + 0.5 * rng.random((T, N), dtype=np.float32))).astype(np.float32)
+    V = (0.1 * rng.random((T + 1, N), dtype=np.float32)).astype(np.float32)
+    d = (rng.random((T, N)) < 0.001).astype(np.uint8)
+    adv, ret = binding.compute_gae(to_gpu(r), to_gpu(V), to_gpu(d), g, l)
+    oadv, oret = oracle.compute_gae(r, V, d, g, l)
+    assert peak < np.abs(oadv).max() < 1.3 * peak
+    for got, want in ((adv.cpu().numpy(), oadv), (ret.cpu().numpy(), oret)):
+        err = np.abs(got.astype(np.float64) - want)
+        half_spacing = 0.5 * np.spacing(np.abs(want).astype(np.float32)).astype(np.float64)
+        assert (err <= half_spacing * (1 + 1e-6) + 1e-13).all()
+        below_32 = np.abs(want) < 32.0
+        assert err[below_32].max() <= TOL
+        if scale == 0.5:
+            assert below_32.all()            # the whole output is in the domain of the 1e-6 bound
+        else:
+            assert (~below_32).any()
+
+
 def test_error_paths_on_the_gpu_box():
     env = binding.MazeEnv(64, 13, 13, 5, 250, device=DEV)
     with pytest.raises(binding.MazeError):
@@ -375,3 +401,5 @@ def test_error_paths_on_the_gpu_box():
         binding.MazeEnv(64, 60, 60, 7, 250, device=DEV)                     # rows > 64 bits
     with pytest.raises(binding.MazeError):
         env.set_kernel_variant(9)
+    with pytest.raises(binding.MazeError):
+        binding.MazeEnv(64, 13, 13, 1, 250, device=DEV)                     # no ring of wall

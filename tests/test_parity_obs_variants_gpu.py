@@ -39,6 +39,47 @@ def test_config_3_sampled_steps(encoding, occlusion):
 
 
 @pytest.mark.parametrize("encoding,occlusion", MODES)
+def test_config_3_full_size_full_rollout(encoding, occlusion):
+    """The launch bench.py times for the variant rows: 32768 envs x 256 steps, i.e. the kernels with
+    128 (typed bytes alone) and 64 (occluded) envs per workgroup through 32 full blocks of 8 steps,
+    the double-buffered stage buffers and 16 refills of the action ring; every byte compared."""
+    run_variant(wl.config(3), encoding, occlusion)
+
+
+@pytest.mark.parametrize("T", [7, 8, 9, 16, 17, 33])
+@pytest.mark.parametrize("encoding,occlusion", MODES)
+def test_64_env_workgroups_around_block_boundaries(encoding, occlusion, T):
+    # 16384 envs: 64 envs per workgroup in every mode; rollout lengths around the 8-step blocks
+    # and the action ring's 16- and 32-step refills; short episodes so that resets are frequent
+    w = wl.student_random(f"variant-16384-T{T}", 1000 + T, N=16384, T=T, n_walls=50, max_steps=11)
+    run_variant(w, encoding, occlusion)
+
+
+@pytest.mark.parametrize("T", [8, 17, 41])
+@pytest.mark.parametrize("encoding,occlusion", MODES)
+def test_largest_workgroups_around_block_boundaries(encoding, occlusion, T):
+    # 32768 envs: 128 envs per workgroup (two dynamics waves) for typed bytes alone, 64 with occlusion
+    w = wl.student_random(f"variant-32768-T{T}", 2000 + T, N=32768, T=T, n_walls=40, max_steps=9)
+    run_variant(w, encoding, occlusion)
+
+
+def test_large_workgroups_with_a_ragged_tail_and_two_calls():
+    # 32768 + 64 + 7 envs: the large workgroups, then one launch of 32-env workgroups whose last
+    # one is partly filled; the rollout split into two calls (the state carries over)
+    w = wl.student_random("variant-ragged", 77, N=32768 + 64 + 7, T=26, n_walls=50, max_steps=15)
+    for enc, occ in MODES:
+        note(f"ragged two-call enc={enc} occ={occ}")
+        env, o = gpu_student(w), cpu_student(w)
+        env.set_obs_mode(enc, occ)
+        o.set_obs_mode(enc, occ)
+        acts = to_gpu(w.actions)
+        for t0, t1 in ((0, 10), (10, 26)):
+            out = env.step(acts[t0:t1].contiguous())
+            assert_rollout_equal(out, o.step(w.actions[t0:t1], t1 - t0), f"steps {t0}..{t1}")
+        assert_state_equal(env, o)
+
+
+@pytest.mark.parametrize("encoding,occlusion", MODES)
 def test_perfect_mazes_view_7(encoding, occlusion):
     run_variant(wl.config(5, N=512, T=40), encoding, occlusion)
 
