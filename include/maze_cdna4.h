@@ -113,6 +113,29 @@ int maze_step(maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_rewa
 int maze_rollout_plan(int N, int H, int W, int view, int encoding, int occlusion, int cus,
                       size_t lds_per_cu, int *envs_per_workgroup, size_t *lds_bytes);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: maze_reset_to_levels followed by maze_step
+ * on a fresh env, with no context and no workspace.  The packed levels and the env state are
+ * kept in a static device array of MAZE_STATIC_WORKSPACE_BYTES inside the library (each GPU
+ * the library runs on holds its copy until the process ends); the call allocates nothing on
+ * the host or the device.  Arguments as for maze_create (N, H, W, view, max_steps),
+ * maze_reset_to_levels (the levels) and maze_step (d_actions [n_steps,N], d_reward, d_done,
+ * d_obs or NULL); all d_* are device pointers owned by the caller; the kernels are enqueued
+ * on `stream` of the current device and nothing synchronises.  The env state is not kept
+ * for a later call: every call starts from the levels' start poses with t = 0, with the
+ * default observation (one-hot, no occlusion).
+ * Limit: maze_workspace_bytes(N, H, W, view) <= MAZE_STATIC_WORKSPACE_BYTES (16 MiB), which
+ * holds e.g. 32768 envs of 13 x 13 with view 5 (11.9 MB) or 8192 envs of 51 x 51 with view 7
+ * (16.7 MB); MAZE_ESIZE beyond it.  Other errors as for the three calls it stands for.
+ * All calls on one GPU share the one array: two calls that may overlap in time (different
+ * streams, or host threads without ordering) race and give undefined results; calls on one
+ * stream are safe back to back.                                                         */
+#define MAZE_STATIC_WORKSPACE_BYTES (16u << 20)
+int maze_rollout_static(int N, int H, int W, int view, int max_steps, const int8_t *d_walls,
+                        const int32_t *d_agent_xy, const int8_t *d_agent_dir,
+                        const int32_t *d_goal_xy, const int8_t *d_actions, int n_steps,
+                        float *d_reward, uint8_t *d_done, int8_t *d_obs, void *stream);
+
 /* Egocentric k x k observation of the current state (Section 3: partially
  * observable).  d_obs int8 [N,k,k,3]; view row 0 is farthest ahead, the agent
  * is at row k-1, column k/2, facing row 0; column 0 is on its left.  Channels

@@ -27,6 +27,8 @@ SIGNATURES = {
     "maze_step": (c_int, [c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_rollout_plan": (c_int, [c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_size_t, POINTER(c_int),
                                   POINTER(c_size_t)]),
+    "maze_rollout_static": (c_int, [c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p,
+                                    c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_render_obs": (c_int, [c_void_p, c_void_p, c_void_p]),
     "maze_get_state": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "maze_set_state": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
@@ -285,6 +287,23 @@ class EditorEnv:
     def mutate_levels(self, seed: int, first_level_id: int, n_edits: int):
         _launch(self.device, "editor_mutate_levels", load_library().editor_mutate_levels, self._h,
                 int(seed), int(first_level_id), int(n_edits))
+
+
+def maze_rollout_static(H: int, W: int, view: int, max_steps: int, walls, agent_xy, agent_dir, goal_xy,
+                        actions, reward, done, obs=None):
+    """Reset to the given levels and roll out `actions` with no env object and no workspace (the
+    library's static device array holds the state); every tensor, outputs included, is the caller's."""
+    if actions.dim() != 2:
+        raise MazeError("actions must be [n_steps, N]")
+    n_steps, N = actions.shape
+    _launch(actions.device, "maze_rollout_static", load_library().maze_rollout_static,
+            N, H, W, view, max_steps, _ptr(walls, torch.int8, (N, H, W), "walls"),
+            _ptr(agent_xy, torch.int32, (N, 2), "agent_xy"), _ptr(agent_dir, torch.int8, (N,), "agent_dir"),
+            _ptr(goal_xy, torch.int32, (N, 2), "goal_xy"), _ptr(actions, torch.int8, (n_steps, N), "actions"),
+            n_steps, _ptr(reward, torch.float32, (n_steps, N), "reward"),
+            _ptr(done, torch.uint8, (n_steps, N), "done"),
+            _ptr(obs, torch.int8, (n_steps, N, view, view, 3), "obs"))
+    return reward, done, obs
 
 
 def compute_gae(rewards, values, dones, gamma: float, lam: float, adv=None, returns=None,

@@ -3,6 +3,7 @@
 #include "maze_internal.h"
 #include "maze_student_device.h"
 
+#include <atomic>
 #include <new>
 
 // ------------------------------------------------------------------ host side
@@ -483,6 +484,67 @@ extern "C" int maze_render_obs(maze_ctx *ctx, int8_t *d_obs, void *stream)
     }
     MAZE_HIP_CHECK(hipGetLastError());
     return MAZE_OK;
+}
+
+// ------------------------------------------- rollout without context or workspace
+// For callers that cannot allocate device memory: the packed levels and the env state of
+// one rollout live in a static device array instead of a caller's workspace.  Each GPU
+// holds its own copy of the array at its own address; the address is looked up once per
+// device (with that device current) and used from then on -- the array's name itself is
+// only a host-side stand-in and never goes to a kernel.
+static __device__ __align__(256) unsigned char scratch[MAZE_STATIC_WORKSPACE_BYTES];
+
+namespace {
+struct StaticDevice {
+    std::atomic<int> ready{0};
+    void *scratch_ptr = nullptr;
+    int cus = 0;
+    size_t lds_per_cu = 0;
+};
+StaticDevice static_devices[16];
+}  // namespace
+
+extern "C" int maze_rollout_static(int N, int H, int W, int view, int max_steps,
+                                   const int8_t *d_walls, const int32_t *d_agent_xy,
+                                   const int8_t *d_agent_dir, const int32_t *d_goal_xy,
+                                   const int8_t *d_actions, int n_steps, float *d_reward,
+                                   uint8_t *d_done, int8_t *d_obs, void *stream)
+{
+    if (!d_walls || !d_agent_xy || !d_agent_dir || !d_goal_xy || !d_actions || !d_reward || !d_done)
+        return MAZE_ENULL;
+    StudentDev d;
+    int w64;
+    const int rc = student_dims(N, H, W, view, &d, &w64);
+    if (rc != MAZE_OK) return rc;
+    if (max_steps < 1 || max_steps >= (1 << 24) || n_steps < 1) return MAZE_EINVAL;
+    const StudentLayout L = student_layout(d, w64);
+    if (L.total > (size_t)MAZE_STATIC_WORKSPACE_BYTES) return MAZE_ESIZE;
+    int device = -1;
+    MAZE_HIP_CHECK(hipGetDevice(&device));
+    if (device < 0 || device >= 16) return MAZE_EINVAL;
+    StaticDevice &sd = static_devices[device];
+    if (!sd.ready.load(std::memory_order_acquire)) {
+        // first call on this device (two threads racing here look up the same values)
+        void *ptr = nullptr;
+        MAZE_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || ((uintptr_t)ptr & 255) != 0) return MAZE_EHIP;
+        hipDeviceProp_t prop;
+        MAZE_HIP_CHECK(hipGetDeviceProperties(&prop, device));
+        sd.scratch_ptr = ptr;
+        sd.cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+        sd.lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
+        sd.ready.store(1, std::memory_order_release);
+    }
+    maze_ctx ctx;                                   // on the stack: nothing is allocated
+    student_bind(&ctx, d, w64, max_steps, sd.scratch_ptr, L);
+    ctx.device = device;
+    ctx.cus = sd.cus;
+    ctx.lds_per_cu = sd.lds_per_cu;
+    // every word of the array that the rollout reads is written by the packing kernel first
+    // (state and grids of envs 0..N-1), so contents left by an earlier call do not matter
+    int rc2 = maze_reset_to_levels(&ctx, d_walls, d_agent_xy, d_agent_dir, d_goal_xy, stream);
+    if (rc2 != MAZE_OK) return rc2;
+    return maze_step(&ctx, d_actions, n_steps, d_reward, d_done, d_obs, stream);
 }
 
 // -------------------------------------------------------------------- getters
