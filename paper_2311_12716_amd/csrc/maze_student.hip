@@ -253,6 +253,134 @@ __global__ __launch_bounds__(64 * PACK_WAVES) void k_pack_levels(
     }
 }
 
+// Level packing for grids whose padded rows fit 32-bit words (every 13 x 13 configuration).
+// G = 16 or 32 lanes per env, max(H, W) <= G: lane l assembles row l of the wall grid as a
+// bit mask from the wall bytes (parked in LDS by the whole wave, one coalesced read of the
+// wave's envs), a log2(G)-stage butterfly over the env's lanes transposes the G x G bit matrix
+// so that lane l also holds column l, and the four heading frames follow directly: frame 3
+// holds the rows, frame 1 the rows reversed in both directions, frames 0 and 2 the columns
+// (one of them reversed each way).  The frames are staged in LDS and leave as 16-byte pieces
+// of one contiguous run per wave.  No loop over cells, no 64-bit arithmetic.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// value of lane (id ^ J) within groups of 32 lanes (the LDS crossbar's bit-mode swizzle)
+template <int J>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x1F | (J << 10));
+}
+
+// One butterfly stage of the bit-matrix transpose: blocks of J x J off the diagonal swap.
+template <int J>
+__device__ __forceinline__ uint32_t transpose_stage(uint32_t r, int l)
+{
+    constexpr uint32_t keep = J == 16 ? 0x0000FFFFu : J == 8 ? 0x00FF00FFu : J == 4 ? 0x0F0F0F0Fu
+                            : J == 2 ? 0x33333333u : 0x55555555u;     // columns x with (x & J) == 0
+    const uint32_t t = lane_xor<J>(r);
+    const uint32_t lower = (r & keep) | ((t & keep) << J);            // lanes with (l & J) == 0
+    const uint32_t upper = (r & (keep << J)) | ((t >> J) & keep);
+    return (l & J) ? upper : lower;
+}
+
+template <int G>
+__global__ __launch_bounds__(64 * PACK_WAVES) void k_pack_levels_rows(
+    StudentDev p, const int8_t *__restrict__ walls, const int32_t *__restrict__ agent_xy,
+    const int8_t *__restrict__ agent_dir, const int32_t *__restrict__ goal_xy)
+{
+    constexpr int EPV = 64 / G;                      // envs per wave
+    constexpr int IN_DWORDS = EPV * G * G / 4;       // wall bytes of a wave's envs, at most
+    constexpr int OUT_DWORDS = EPV * 4 * 32;         // their frames, at most (SP <= 32)
+    __shared__ uint32_t in_lds[PACK_WAVES][IN_DWORDS];
+    __shared__ __align__(16) uint32_t out_lds[PACK_WAVES][OUT_DWORDS];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane / G, l = lane % G;
+    const int n0 = (blockIdx.x * PACK_WAVES + wave) * EPV;      // first env of the wave
+    if (n0 >= p.N) return;                                      // (no workgroup barrier below)
+    const int live_envs = min(EPV, p.N - n0);
+    const bool live = sub < live_envs;
+    const int n = n0 + (live ? sub : 0);
+    // the five pose lanes of an env request their inputs first
+    const int32_t *pos_src = l < 4 ? goal_xy : agent_xy;
+    const int pos_x = l < 5 ? pos_src[2 * n] : 0, pos_y = l < 5 ? pos_src[2 * n + 1] : 0;
+    const int start_dir = agent_dir[n] & 3;
+    const int H = p.H, W = p.W, P = p.P, SP = p.SP, cells = H * W;
+    // wall bytes of the wave's envs: one contiguous run, a dword per lane and round (of any
+    // alignment; the run's last bytes singly, so that nothing beyond the array is read)
+    const int bytes = live_envs * cells;
+    const int8_t *src = walls + (size_t)n0 * cells;
+    uint32_t *in = in_lds[wave];
+    for (int i = lane; 4 * i < bytes; i += 64) {
+        uint32_t v = 0;
+        if (4 * i + 4 <= bytes) {
+            __builtin_memcpy(&v, src + 4 * i, 4);
+        } else {
+            for (int b = 0; 4 * i + b < bytes; ++b) v |= (uint32_t)(uint8_t)src[4 * i + b] << (8 * b);
+        }
+        in[i] = v;
+    }
+    wave_lds_sync();
+    uint32_t r = 0;                                  // row l: bit x = wall(x, l)
+    if (live && l < H) {
+        const uint8_t *row = (const uint8_t *)in + sub * cells + l * W;
+        for (int x0 = 0; x0 < W; x0 += 8) {
+            uint32_t b[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) b[u] = row[min(x0 + u, W - 1)];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) r |= (b[u] ? 1u : 0u) << (x0 + u);
+        }
+        r &= (1u << W) - 1u;
+    }
+    uint32_t c = r;                                  // column l after the transpose: bit y = wall(l, y)
+    if (G == 32) c = transpose_stage<16>(c, l);
+    c = transpose_stage<8>(c, l);
+    c = transpose_stage<4>(c, l);
+    c = transpose_stage<2>(c, l);
+    c = transpose_stage<1>(c, l);
+    // frames: everything outside the interior is wall
+    uint32_t *out = out_lds[wave];
+    const int per_env = 4 * SP;
+    for (int i = lane; i < live_envs * per_env; i += 64) out[i] = ~0u;
+    wave_lds_sync();
+    if (live) {
+        uint32_t *o = out + sub * per_env;
+        if (l < H) {
+            const uint32_t field = ((1u << W) - 1u) << P;
+            o[3 * SP + P + l] = (r << P) | ~field;
+            o[1 * SP + (p.HP - 1 - P - l)] = ((__brev(r) >> (32 - W)) << P) | ~field;
+        }
+        if (l < W) {
+            const uint32_t field = ((1u << H) - 1u) << P;
+            o[0 * SP + (p.WP - 1 - P - l)] = (c << P) | ~field;
+            o[2 * SP + P + l] = ((__brev(c) >> (32 - H)) << P) | ~field;
+        }
+    }
+    wave_lds_sync();
+    uint4 *dst = (uint4 *)((uint32_t *)p.grids + (size_t)n0 * per_env);
+    for (int i = lane; i < live_envs * SP; i += 64) dst[i] = ((const uint4 *)out)[i];
+    if (l < 5 && live) {
+        const int X = min(max(pos_x, 0), W - 1) + P;
+        const int Y = min(max(pos_y, 0), H - 1) + P;
+        const int d = l < 4 ? l : start_dir;
+        int xd, yd;
+        padded_to_frame(p, d, X, Y, xd, yd);
+        const uint32_t v = (uint32_t)xd | ((uint32_t)yd << 8);
+        if (l < 4) {
+            p.goalrot[4 * n + l] = v;
+        } else {
+            const uint32_t st = v | ((uint32_t)d << 16);
+            p.start[n] = st;
+            p.pose[n] = st;
+            p.tcount[n] = 0;
+        }
+    }
+}
+
 template <typename Word>
 static void launch_pack(const StudentDev &p, const int8_t *d_walls, const int32_t *d_agent_xy,
                         const int8_t *d_agent_dir, const int32_t *d_goal_xy, hipStream_t st)
@@ -283,10 +411,22 @@ extern "C" int maze_reset_to_levels(maze_ctx *ctx, const int8_t *d_walls,
     MAZE_DEVICE_CHECK(ctx);
     hipStream_t st = (hipStream_t)stream;
     const StudentDev &p = ctx->dev;
-    if (ctx->word64)
+    if (ctx->word64) {
         launch_pack<uint64_t>(p, d_walls, d_agent_xy, d_agent_dir, d_goal_xy, st);
-    else
-        launch_pack<uint32_t>(p, d_walls, d_agent_xy, d_agent_dir, d_goal_xy, st);
+    } else {
+        // 32-bit rows: SP <= 32, so max(H, W) <= 28
+        const dim3 block(64 * PACK_WAVES);
+        auto blocks = [&](int envs_per_wave) {
+            const int per_block = PACK_WAVES * envs_per_wave;
+            return dim3((p.N + per_block - 1) / per_block);
+        };
+        if (p.H <= 16 && p.W <= 16)
+            hipLaunchKernelGGL(k_pack_levels_rows<16>, blocks(4), block, 0, st, p, d_walls, d_agent_xy,
+                               d_agent_dir, d_goal_xy);
+        else
+            hipLaunchKernelGGL(k_pack_levels_rows<32>, blocks(2), block, 0, st, p, d_walls, d_agent_xy,
+                               d_agent_dir, d_goal_xy);
+    }
     MAZE_HIP_CHECK(hipGetLastError());
     return MAZE_OK;
 }
