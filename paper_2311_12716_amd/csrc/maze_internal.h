@@ -52,6 +52,7 @@ struct maze_ctx {
     int device;             // the device that was current at maze_create; every call must run on it
     int cus;                // its compute units and the LDS of one of them (device properties):
     size_t lds_per_cu;      // they decide how many envs a workgroup of the rollout takes
+    int clock_khz;          // rate of the constant-rate clock kernels read (the rollout paces its stores by it)
     size_t workspace_bytes;
 };
 

@@ -12,22 +12,27 @@ __device__ __forceinline__ uint32_t expand_nibble(uint32_t nib)
 }
 
 // 16-byte global accesses at addresses of any alignment (a batch size or a buffer offset that
-// is not a multiple of 16 shifts every step's block): a 16-byte vector type of alignment 1, which
-// compiles to one dwordx4 instruction on this target whatever the address.
-// The observation is a pure output stream: nothing on the chip reads it back.  Its stores carry
-// the non-temporal hint, which lets the L2s pass the lines on early instead of collecting
-// dirty lines that all have to be written back when the kernel ends (each of the 8 XCDs has an
-// L2 of its own, so a kernel's output must leave them before the next kernel starts).
-// Measured on config 3: 256-step rollout 133.5 -> 127.5 us per launch, launches back to back.
-typedef uint32_t maze_u4_unaligned __attribute__((ext_vector_type(4), aligned(1)));
-__device__ __forceinline__ void store16(int8_t *dst, const uint4 &v)
+// is not a multiple of 16 shifts every step's block): a plain 16-byte copy, which compiles to
+// one dwordx4 instruction on this target whatever the alignment.
+__device__ __forceinline__ void store16(int8_t *dst, const uint4 &v) { __builtin_memcpy(dst, &v, 16); }
+
+// The same store for output that is a pure stream -- nothing on the chip reads it back -- and
+// whose 128-byte line is written completely by this workgroup: non-temporal, system scope
+// (written through, nothing of it kept).  Each of the 8 XCDs has an L2 of its own, so a
+// kernel's output has to leave them before the next kernel starts; without the hint the
+// rollout's output collects there as dirty lines and is written back when the kernel ends.
+// Measured on config 3, 256-step rollout, launches back to back: plain stores 133.5 us,
+// nt 127.1, sc0 sc1 nt 125.2, sc0 sc1 alone 134.3 (the compiler's non-temporal store gives nt
+// alone, hence the instruction written out).  Lines that two workgroups share must not carry
+// the hint: they would leave the L2 half written and be merged in memory (config 5, whose
+// 4704-byte chunks end inside lines: 129 -> 152 us with nt on every store; the same on the
+// rollout's 4-byte reward and 1-byte done stores: 127 -> 135 us).
+typedef uint32_t maze_u4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store16_stream(int8_t *dst, const uint4 &v)
 {
-    const maze_u4_unaligned t = {v.x, v.y, v.z, v.w};
-    __builtin_nontemporal_store(t, (maze_u4_unaligned *)dst);
+    const maze_u4 t = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(dst), "v"(t) : "memory");
 }
-// (Only whole-line streams gain: with the hint on the rollout's reward and done stores -- 256 and
-// 64 bytes per wave instruction, lines completed by several instructions -- the launch was
-// slower than with no hint at all, 135 us.)
 __device__ __forceinline__ uint4 load16(const int8_t *src)
 {
     uint4 v;

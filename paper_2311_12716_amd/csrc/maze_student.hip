@@ -92,6 +92,9 @@ extern "C" int maze_create(maze_ctx **out, int N, int H, int W, int view, int ma
         hipGetDeviceProperties(&prop, c->device) != hipSuccess) { delete c; return MAZE_EHIP; }
     c->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
     c->lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
+    c->clock_khz = 0;
+    if (hipDeviceGetAttribute(&c->clock_khz, hipDeviceAttributeWallClockRate, c->device) != hipSuccess)
+        c->clock_khz = 0;
     *out = c;
     return MAZE_OK;
 }
@@ -640,6 +643,7 @@ struct StaticDevice {
     void *scratch_ptr = nullptr;
     int cus = 0;
     size_t lds_per_cu = 0;
+    int clock_khz = 0;
 };
 StaticDevice static_devices[16];
 }  // namespace
@@ -673,6 +677,8 @@ extern "C" int maze_rollout_static(int N, int H, int W, int view, int max_steps,
         sd.scratch_ptr = ptr;
         sd.cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
         sd.lds_per_cu = prop.maxSharedMemoryPerMultiProcessor;
+        if (hipDeviceGetAttribute(&sd.clock_khz, hipDeviceAttributeWallClockRate, device) != hipSuccess)
+            sd.clock_khz = 0;
         sd.ready.store(1, std::memory_order_release);
     }
     maze_ctx ctx;                                   // on the stack: nothing is allocated
@@ -680,6 +686,7 @@ extern "C" int maze_rollout_static(int N, int H, int W, int view, int max_steps,
     ctx.device = device;
     ctx.cus = sd.cus;
     ctx.lds_per_cu = sd.lds_per_cu;
+    ctx.clock_khz = sd.clock_khz;
     // every word of the array that the rollout reads is written by the packing kernel first
     // (state and grids of envs 0..N-1), so contents left by an earlier call do not matter
     int rc2 = maze_reset_to_levels(&ctx, d_walls, d_agent_xy, d_agent_dir, d_goal_xy, stream);

@@ -249,6 +249,8 @@ struct Window {
     uint32_t type_pos, colour_pos;
     int typed_row[4];   // per output dword: first entry of its phase's row of the typed table
     int valid;      // bytes of the window that exist: 16, fewer in a partly filled workgroup
+    bool stream;    // the window's 128-byte output line is written by this workgroup alone, at
+                    // every step: its stores take the streaming form
 };
 
 template <int K, int EPW>
@@ -270,6 +272,7 @@ __device__ __forceinline__ Window make_window(int lane, int round)
     w.addr1 = rem < 16 ? rec0 + V::REC : rec0 + V::ND;
     w.out = 16u * mm;
     w.valid = 16;
+    w.stream = false;
     const int phase = bitpos % 3;                // stream bit 16*mm is byte `phase` of its cell
     const uint32_t every_third = 0x9249u;        // bits 0, 3, 6, 9, 12, 15
     w.type_pos = phase == 0 ? every_third : (phase == 1 ? 0x4924u : 0x2492u);
@@ -277,6 +280,13 @@ __device__ __forceinline__ Window make_window(int lane, int round)
 #pragma unroll
     for (int q = 0; q < 4; ++q) w.typed_row[q] = 128 * ((phase + q) % 3);   // 4 bytes on: phase + 1
     return w;
+}
+
+__device__ __forceinline__ void store_window(int8_t *dst, const uint4 &a, const Window &w)
+{
+    if (w.stream) store16_stream(dst, a);
+    else if (w.valid >= 16) store16(dst, a);
+    else store_bytes(dst, a, w.valid);
 }
 
 // Expand one 16-bit window of the concatenated streams into 16 output bytes.
@@ -289,8 +299,7 @@ __device__ __forceinline__ void consume_window(const uint32_t *recs, const Windo
     uint4 a;
     a.x = expand_nibble(bits & 15);          a.y = expand_nibble((bits >> 4) & 15);
     a.z = expand_nibble((bits >> 8) & 15);   a.w = expand_nibble((bits >> 12) & 15);
-    if (w.valid >= 16) store16(block + w.out, a);
-    else store_bytes(block + w.out, a, w.valid);
+    store_window(block + w.out, a, w);
 }
 
 // The same window written in the (type, colour, state) encoding.  The one-hot stream holds,
@@ -320,8 +329,7 @@ __device__ __forceinline__ void consume_window_typed(const uint32_t *recs, const
                  (expand_nibble((p2 >> sh) & 15) << 2) | (expand_nibble((p3 >> sh) & 15) << 3);
     }
     const uint4 a = make_uint4(out[0], out[1], out[2], out[3]);
-    if (w.valid >= 16) store16(block + w.out, a);
-    else store_bytes(block + w.out, a, w.valid);
+    store_window(block + w.out, a, w);
 }
 
 // The typed bytes of one output dword depend on the phase of its first byte (which of type,
@@ -359,8 +367,7 @@ __device__ __forceinline__ void consume_window_typed(const uint32_t *recs, const
     a.y = typed_table[w.typed_row[1] + ((from_below >> 4) & 127)];
     a.z = typed_table[w.typed_row[2] + ((from_below >> 8) & 127)];
     a.w = typed_table[w.typed_row[3] + ((from_below >> 12) & 127)];
-    if (w.valid >= 16) store16(block + w.out, a);
-    else store_bytes(block + w.out, a, w.valid);
+    store_window(block + w.out, a, w);
 }
 
 // Which cells of the view are seen (occluded view): rows are settled from the agent's row
@@ -638,7 +645,7 @@ __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word>
 template <int K, typename Word, int EPW, bool SQUARE, int MODE = 0, bool PARTIAL = false>
 __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     StudentDev p, int n_begin, int n_end, const int8_t *__restrict__ actions, int n_steps,
-    float *__restrict__ reward, uint8_t *__restrict__ done, int8_t *__restrict__ obs)
+    float *__restrict__ reward, uint8_t *__restrict__ done, int8_t *__restrict__ obs, uint32_t pace_fp)
 {
     using V = View<K, EPW>;
     using L = Lds<K, Word, EPW, MODE>;
@@ -843,19 +850,90 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         }
         const size_t step_obs = (size_t)N * V::SB;
         int8_t *out_block = obs + (size_t)env0 * V::SB;
+        // Streaming stores for the windows whose 128-byte line lies inside this workgroup's
+        // chunk -- decided once, which needs the lines to fall the same way at every step.
+        // (Workgroups of 32 envs keep plain stores: with streaming stores on their inner lines
+        // config 5 took 166 instead of 123 us.)
+        if (EPW >= 64 && step_obs % 128 == 0) {
+            const uintptr_t chunk_lo = (uintptr_t)out_block, chunk_hi = chunk_lo + (size_t)count * V::SB;
+#pragma unroll
+            for (int j = 0; j < MYR; ++j) {
+                const uintptr_t line = (chunk_lo + win[j].out) & ~(uintptr_t)127;
+                win[j].stream = win[j].active && win[j].valid >= 16 && line >= chunk_lo && line + 128 <= chunk_hi;
+            }
+        }
         __syncthreads();                                             // barrier 0 (set-up)
         __syncthreads();                                             // block 0 published
         __syncthreads();                                             // block 0 viewed
         __syncthreads();                                             // block 0 recorded
+        // Pacing.  The memory system takes this write stream fastest when it is offered at a
+        // steady rate just below what it can sustain; offered more (every wave storing as fast as
+        // the queues accept) its throughput drops by a fifth.  So the store waves keep to a
+        // schedule: pace_fp is the time one step of the whole launch should take (ticks of the
+        // constant-rate clock, 8 fractional bits; 0 = no pacing), a block of steps gets that much
+        // time, and what a wave does not need for its own work -- the previous block's time less
+        // its sleep -- it sleeps, spread over the block's steps.  The schedule is absolute, so
+        // errors do not add up; a wave that cannot keep it (the launch is bound by something else)
+        // drops it after a few blocks and costs nothing from then on.
+        uint32_t pace = pace_fp;
+        uint32_t unit_fp = 256;                      // one sleep unit in ticks (8 fractional bits)
+        if (pace) {
+            const uint64_t c0 = __builtin_amdgcn_s_memrealtime();
+            _Pragma("unroll") for (int q = 0; q < 16; ++q) __builtin_amdgcn_s_sleep(1);
+            const uint64_t c1 = __builtin_amdgcn_s_memrealtime();
+            unit_fp = max(16u, (uint32_t)(c1 - c0) * 16u);
+        }
+        uint64_t sched_fp = 0;                       // when the current block's stores should be out
+        uint32_t work_fp = 0;                        // the previous block's duration less its sleep
+        int behind = -1;                             // blocks in a row without time to sleep (-1: first block)
         MAZE_FOR_EACH_BLOCK(
-            _Pragma("unroll") for (int u = 0; u < SPB; ++u) if (MAZE_STEP_ON(u)) {
-                const uint32_t *rec = lds + L::REC + (par * SPB + u) * L::REC_SIZE;
-                _Pragma("unroll") for (int j = 0; j < MYR; ++j) {
-                    if (!win[j].active) continue;
-                    if (MODE == 1 && p.obs_encoding)
-                        consume_window_typed(rec, win[j], out_block + u * step_obs, lds + L::TYPED);
-                    else consume_window(rec, win[j], out_block + u * step_obs);
+            uint32_t units = 0;
+            uint64_t t_begin = 0;
+            if (pace) {
+                t_begin = __builtin_amdgcn_s_memrealtime() << 8;
+                const uint64_t block_fp = (uint64_t)(full ? SPB : n_steps - i0) * pace;
+                if (behind < 0) { sched_fp = t_begin; behind = 0; }
+                sched_fp += block_fp;
+                const int64_t spare = (int64_t)(sched_fp - t_begin) - (int64_t)work_fp;
+                if (spare >= (int64_t)unit_fp) {
+                    units = min(SPB * 63u, (uint32_t)(spare / unit_fp));
+                    behind = 0;
+                } else {
+                    if (spare < -(int64_t)block_fp) sched_fp = t_begin + block_fp;   // never catch up in a burst
+                    if (++behind >= 4) pace = 0;
                 }
+            }
+            if (units == 0) {
+                _Pragma("unroll") for (int u = 0; u < SPB; ++u) if (MAZE_STEP_ON(u)) {
+                    const uint32_t *rec = lds + L::REC + (par * SPB + u) * L::REC_SIZE;
+                    _Pragma("unroll") for (int j = 0; j < MYR; ++j) {
+                        if (!win[j].active) continue;
+                        if (MODE == 1 && p.obs_encoding)
+                            consume_window_typed(rec, win[j], out_block + u * step_obs, lds + L::TYPED);
+                        else consume_window(rec, win[j], out_block + u * step_obs);
+                    }
+                }
+            } else {
+                // the sleep units go evenly between the block's SPB * MYR stores
+                constexpr uint32_t SLOTS = SPB * MYR;
+                const uint32_t per_slot = units / SLOTS, extra = units % SLOTS;
+                _Pragma("unroll") for (int u = 0; u < SPB; ++u) if (MAZE_STEP_ON(u)) {
+                    const uint32_t *rec = lds + L::REC + (par * SPB + u) * L::REC_SIZE;
+                    _Pragma("unroll") for (int j = 0; j < MYR; ++j) {
+                        if (win[j].active) {
+                            if (MODE == 1 && p.obs_encoding)
+                                consume_window_typed(rec, win[j], out_block + u * step_obs, lds + L::TYPED);
+                            else consume_window(rec, win[j], out_block + u * step_obs);
+                        }
+                        const uint32_t naps = per_slot + ((uint32_t)(u * MYR + j) < extra ? 1u : 0u);
+                        for (uint32_t q = 0; q < naps; ++q) __builtin_amdgcn_s_sleep(1);
+                    }
+                }
+            }
+            if (pace) {
+                const uint64_t t_end = __builtin_amdgcn_s_memrealtime() << 8;
+                const uint64_t slept = (uint64_t)units * unit_fp;
+                work_fp = t_end - t_begin > slept ? (uint32_t)min((uint64_t)0x7FFFFFFF, t_end - t_begin - slept) : 0u;
             }
             out_block += SPB * step_obs;)
     }
@@ -923,6 +1001,14 @@ __global__ __launch_bounds__(REPW) void k_step_render_tiled(
     }
 }
 
+// The write rate the store waves of a large launch are paced to.  Config 3 (256 workgroups x
+// 9600 B per step), 256-step rollout, launches back to back: unpaced 125 us; paced to 6700 GB/s
+// 113.1, 6900: 110.2, 7100: 107.5, 7300: 104.8 -- but past a shape-dependent point the stream
+// falls back to the unpaced rate (view 7 on 20 x 20 grids: 115 us at 6700 and 6900, 124 at 7100,
+// 126 unpaced; typed observation and 65536 envs: fine at 7100, back at 7300), so the
+// constant stays below the lowest such point.
+constexpr double PACED_GBS = 6900.0;
+
 // LDS a workgroup of a rollout may use on this device: what a CU has, less 1 KB that the
 // runtime may claim for itself.
 inline size_t lds_budget(const maze_ctx *ctx) { return ctx->lds_per_cu > 1024 ? ctx->lds_per_cu - 1024 : 0; }
@@ -961,6 +1047,23 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
     const size_t shmem = L::bytes(p.SP);
     if (shmem > lds_budget(ctx)) return MAZE_EHIP;
     const dim3 grid(groups), block(64 * V::WAVES);
+    // Pacing of the store waves (see the kernel's stores stage): the time one step of the launch
+    // should take if the workgroups resident at once write their chunks, reward and done at
+    // PACED_GBS.  Paced are launches of 64- and 128-env workgroups that write more than twice
+    // what the 256 MB memory-side cache holds (a smaller output is absorbed there and leaves
+    // the chip later: 16384 envs x 256 steps take 52 us unpaced, 57 paced) and do not build the
+    // occluded view (there the records stage sets the pace: 117 us unpaced, 120 paced).
+    // A launch whose steps would be scheduled shorter than the pipeline's own latency per step can
+    // never be ahead of its schedule and is not paced either.
+    uint32_t pace_fp = 0;
+    const double out_bytes = (double)(n_end - n_begin) * n_steps * (V::SB + 5);
+    if (EPW >= 64 && !p.obs_occlusion && out_bytes > 2.0 * 256.0 * 1048576.0 && ctx->clock_khz > 0) {
+        const size_t per_cu = max((size_t)1, min(lds_budget(ctx) / shmem, (size_t)(32 / V::WAVES)));
+        const double resident = (double)min((long long)groups, (long long)ctx->cus * (long long)per_cu);
+        const double step_ns = resident * EPW * (V::SB + 6) / PACED_GBS;      // bytes / (GB/s) = ns
+        const double step_ticks_fp = step_ns * 1e-6 * ctx->clock_khz * 256.0;
+        if (step_ns >= 150.0 && step_ticks_fp < 4.0e9) pace_fp = (uint32_t)step_ticks_fp;
+    }
     // the square-grid flavour exists for the plain kernel only
     constexpr bool PLAIN = MODE == 0 && !PARTIAL;
     const bool square = p.HP == p.WP && PLAIN;
@@ -972,12 +1075,12 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
         auto kern = k_student_rollout<K, Word, EPW, PLAIN, MODE, PARTIAL>;
         if (!allow_large_lds(kern, shmem, granted)) return MAZE_EHIP;
         hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
-                           d_done, d_obs);
+                           d_done, d_obs, pace_fp);
     } else {
         auto kern = k_student_rollout<K, Word, EPW, false, MODE, PARTIAL>;
         if (!allow_large_lds(kern, shmem, granted)) return MAZE_EHIP;
         hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
-                           d_done, d_obs);
+                           d_done, d_obs, pace_fp);
     }
     return n_end - n_begin;
 }
