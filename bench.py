@@ -13,7 +13,10 @@ env-steps per second over the K timed steps.
 The JSON line also carries
   roofline      achieved algorithmic HBM GB/s of the rollout kernel (81 bytes per
                 env-step: 1 action in, 75 obs + 4 reward + 1 done out), timed with
-                HIP events on the launch stream inside the timed region;
+                HIP events on the launch stream around every 4th maze_step of the
+                timed region (an event pair costs the stream about 10 us, so not
+                every pass carries one); frac_whole_pass is the same figure for the
+                whole timed pass, reset and first render included;
   cpu_baseline  the CPU oracle on the same workload on this host's cores;
   rows          the other calls of the path (teacher editor at config 4, GAE,
                 the 51x51 config 5 rollout, the per-step call pattern), each timed
@@ -75,6 +78,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row measurements")
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 per-cell kernels")
+    ap.add_argument("--event-every", type=int, default=4,
+                    help="bracket every n-th maze_step of the timed region with HIP events")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -122,9 +127,10 @@ def main():
     for _ in range(args.warmup):
         one_step(False)
     torch.cuda.synchronize()
+    every = max(1, args.event_every)
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step(True)
+    for i in range(args.steps):
+        one_step(i % every == every - 1 or args.steps < every)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
@@ -134,6 +140,10 @@ def main():
     k_avg_s = float(np.mean(kms)) * 1e-3
     alg_bytes = BYTES_PER_ENV_STEP[k] * N * T
     achieved = alg_bytes / k_avg_s / 1e9
+    # the whole pass also reads the levels (H*W wall bytes + 17 bytes of poses per env) and
+    # writes the first observation
+    pass_bytes = alg_bytes + N * (w.H * w.W + 17) + N * 3 * k * k
+    pass_gbs = pass_bytes / (elapsed / args.steps) / 1e9
     traffic = load_traffic().get("student_rollout_c3")
     n_resets = int(done.sum().item())
 
@@ -157,7 +167,15 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "student rollout (maze_step, 256 steps fused)",
                      "kernel_ms_avg": k_avg_s * 1e3, "kernel_ms_min": float(np.min(kms)),
-                     "algorithmic_bytes_per_launch": alg_bytes},
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "timing": f"HIP events on the launch stream around {len(kms)} of the {args.steps} "
+                               "timed maze_step launches; bytes are algorithmic, `traffic` is the "
+                               "counter figure of profiles/hbm_traffic.json",
+                     "frac_whole_pass": pass_gbs / HBM_PEAK_GBS,
+                     "whole_pass": {"achieved": pass_gbs, "algorithmic_bytes": pass_bytes,
+                                    "ms": elapsed / args.steps * 1e3,
+                                    "what": "reset to levels + first render + rollout, wall clock "
+                                            "over the timed region"}},
     }
 
     if args.calib_copy:
@@ -176,6 +194,35 @@ def main():
         rows["maze_reset_to_levels_c3"] = {"ms": ms, "GB/s": N * (169 + 17) / ms / 1e6}
         ms, mn = time_calls(torch, lambda: env.render_obs(obs0), 20)
         rows["maze_render_obs_c3"] = {"ms": ms, "GB/s": N * 75 / ms / 1e6}
+        # where the time of a pass goes: each call alone, launches back to back, and the rest
+        ms_roll, mn = time_calls(torch, lambda: env.step(actions, reward, done, obs), 20, warmup=3)
+        rows["pass_breakdown_c3"] = {
+            "pass_ms": out["ms_per_step"], "rollout_ms": ms_roll,
+            "reset_plus_render_ms": out["ms_per_step"] - ms_roll,
+            "note": "rollout = maze_step alone, launches back to back; the rest is what reset to levels "
+                    "and the first render add to a pass (their kernels, the gaps between three dependent "
+                    "launches, the packing kernel running behind the rollout's last writes); kernel by "
+                    "kernel: profiles/kernels.md"}
+        # the same pass replayed from a captured HIP graph
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            one_step(False)
+        torch.cuda.current_stream().wait_stream(side)
+        pass_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(pass_graph):
+            one_step(False)
+        for _ in range(3):
+            pass_graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(30):
+            pass_graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - g0) / 30 * 1e3
+        rows["pass_graph_replay_c3"] = {"ms": g_ms, "env-steps/s": N * T / g_ms * 1e3,
+                                        "note": "reset + render + rollout captured once, replayed 30 times"}
+        del pass_graph
         a1 = actions[:1].contiguous()
         r1, d1 = reward[:1], done[:1]
 

@@ -65,6 +65,11 @@ extern "C" int editor_create(editor_ctx **out, int N, int H, int W, int n_walls,
     c->dev = d;
     c->workspace_bytes = workspace_bytes;
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return MAZE_EHIP; }
+    c->cus = 0;
+    c->clock_khz = 0;
+    if (hipDeviceGetAttribute(&c->cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess ||
+        hipDeviceGetAttribute(&c->clock_khz, hipDeviceAttributeWallClockRate, c->device) != hipSuccess)
+        c->clock_khz = 0;                         // unknown: the store waves are not paced
     *out = c;
     return MAZE_OK;
 }

@@ -35,7 +35,7 @@ __device__ __forceinline__ void lds_clear_bit(uint32_t *rec, int bit)
 
 __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
     EditorDev p, const int32_t *__restrict__ actions, int n_steps, int8_t *__restrict__ obs,
-    int32_t *__restrict__ t_out, uint8_t *__restrict__ done)
+    int32_t *__restrict__ t_out, uint8_t *__restrict__ done, uint32_t pace_fp)
 {
     extern __shared__ uint32_t lds[];            // [EPW][REC], REC = SW + 1 (last dword stays 0)
     const int tid = threadIdx.x, lane = tid & 63;
@@ -103,10 +103,21 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
         const int e_first = (16 * m0) / SB, s_first = 16 * m0 - e_first * SB;
         const size_t step_obs = (size_t)p.N * SB;
         int8_t *out_block = obs + (size_t)env0 * SB;
+        // windows of this lane per step, and whether the lines fall the same way at every step
+        // (then a window whose 128-byte line lies inside the workgroup's chunk is stored in
+        // the streaming form)
+        const int max_rounds = (nwin + NS * 64 - 1) / (NS * 64);
+        const bool steady = step_obs % 128 == 0;
+        const uintptr_t chunk_lo = (uintptr_t)out_block, chunk_hi = chunk_lo + (size_t)block_bytes;
+        StorePacer pacer;                         // (see maze_store_device.h)
+        pacer.init(pace_fp);
         for (int s = 0; s < n_steps; ++s) {
             __syncthreads();                     // edits of step s visible
+            const uint32_t units = pacer.begin(1, (uint32_t)max_rounds * 63u);
+            const uint32_t per_round = units / (uint32_t)max_rounds, extra = units % (uint32_t)max_rounds;
             int e0 = e_first, bs = s_first;
-            for (int m = m0; m < nwin; m += NS * 64) {
+            uint32_t round = 0;
+            for (int m = m0; m < nwin; m += NS * 64, ++round) {
                 const uint32_t *r0 = lds + e0 * REC;
                 const int rem = SB - bs;
                 const bool spill = rem < 16;     // window runs into the next env
@@ -117,12 +128,17 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
                 v.x = expand_nibble(bits & 15);          v.y = expand_nibble((bits >> 4) & 15);
                 v.z = expand_nibble((bits >> 8) & 15);   v.w = expand_nibble((bits >> 12) & 15);
                 const int valid = block_bytes - 16 * m;
-                if (valid >= 16) store16(out_block + 16 * (size_t)m, v);
+                const uintptr_t line = (chunk_lo + 16 * (size_t)m) & ~(uintptr_t)127;
+                if (steady && valid >= 16 && line >= chunk_lo && line + 128 <= chunk_hi)
+                    store16_stream(out_block + 16 * (size_t)m, v);
+                else if (valid >= 16) store16(out_block + 16 * (size_t)m, v);
                 else store_bytes(out_block + 16 * (size_t)m, v, valid);
                 bs += adv_r;
                 e0 += adv_q;
                 if (bs >= SB) { bs -= SB; e0 += 1; }
+                if (units) StorePacer::nap(per_round + (round < extra ? 1u : 0u));
             }
+            pacer.end();
             out_block += step_obs;
             __syncthreads();                     // reads done before the next edit
         }
@@ -143,8 +159,13 @@ int editor_tiled_launch(const editor_ctx *ctx, const int32_t *d_actions, int n_s
     if (shmem > 60 * 1024) return 0;
     if (3 * p.cells < 16) return 0;              // a 16-bit window must not span more than two envs
     const int groups = (p.N + EPW - 1) / EPW;
+    // store waves paced like the student rollout's: the workgroups resident at once (one per
+    // CU: 14 waves each) write their obs, t and done of a step and read its actions
+    const double resident = (double)(groups < ctx->cus ? groups : ctx->cus);
+    const uint32_t pace_fp = maze_pace_fp(ctx->clock_khz, resident * EPW * (3.0 * p.cells + 9.0),
+                                          (double)p.N * n_steps * (3.0 * p.cells + 5.0), MAZE_PACED_GBS_EDITOR);
     hipLaunchKernelGGL(k_editor_tiled, dim3(groups), dim3(64 * NWAVES), shmem, st, p, d_actions,
-                       n_steps, d_obs, d_t, d_done);
+                       n_steps, d_obs, d_t, d_done, pace_fp);
     *covered = p.N;
     return 1;
 }

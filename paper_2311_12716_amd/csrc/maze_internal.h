@@ -69,6 +69,33 @@ static inline int maze_same_device(int ctx_device)
         if (rc__ != MAZE_OK) return rc__;               \
     } while (0)
 
+// The write rate the store waves of a large launch are paced to (see StorePacer).  Config 3
+// (256 workgroups x 9600 B per step), 256-step rollout, launches back to back: unpaced 125 us;
+// paced to 6700 GB/s 113.1, 6900: 110.2, 7100: 107.5, 7300: 104.8 -- but past a shape-dependent
+// point the stream falls back to the unpaced rate (view 7 on 20 x 20 grids: 115 us at 6700 and
+// 6900, 124 at 7100, 126 unpaced; typed observation and 65536 envs: fine at 7100, back at
+// 7300), so the constant stays below the lowest such point.
+#define MAZE_PACED_GBS 6900.0
+// The editor's stream (64896 B per workgroup and step at 13 x 13) turns earlier: config 4 takes
+// 163 us unpaced and at 6900, 144 to 158 at 6200 to 6600 (the faster state is not always
+// reached), 156 at 6000, 229 at 4000 (there the schedule alone sets the time).
+#define MAZE_PACED_GBS_EDITOR 6400.0
+
+// Time one step of a launch should take, in ticks of the device's constant-rate clock with 8
+// fractional bits, if the workgroups resident at once move bytes_per_step at rate_gbs;
+// 0 = do not pace: no clock, an output small enough for the 256 MB memory-side cache to absorb
+// most of it (it leaves the chip later: 16384 envs x 256 steps take 52 us unpaced, 57 paced), or
+// steps scheduled shorter than a pipeline's own latency per step (such a launch can never be
+// ahead of its schedule).
+static inline uint32_t maze_pace_fp(int clock_khz, double bytes_per_step, double out_bytes_total,
+                                    double rate_gbs)
+{
+    if (clock_khz <= 0 || out_bytes_total <= 2.0 * 256.0 * 1048576.0) return 0;
+    const double step_ns = bytes_per_step / rate_gbs;                 // bytes / (GB/s) = ns
+    const double ticks_fp = step_ns * 1e-6 * clock_khz * 256.0;
+    return step_ns >= 150.0 && ticks_fp < 4.0e9 ? (uint32_t)ticks_fp : 0u;
+}
+
 // ---------------------------------------------------------------------------
 // Teacher editor env: device-side layout.
 //
@@ -89,5 +116,7 @@ struct EditorDev {
 struct editor_ctx {
     EditorDev dev;
     int device;
+    int cus;                // compute units and clock rate of the device (pacing of the store waves)
+    int clock_khz;
     size_t workspace_bytes;
 };

@@ -40,6 +40,68 @@ __device__ __forceinline__ uint4 load16(const int8_t *src)
     return v;
 }
 
+// Pacing of a store wave.  The memory system takes the observation stream fastest when it is
+// offered at a steady rate just below what it can sustain; offered more -- every wave storing
+// as fast as the queues accept -- its throughput drops by a fifth (config 3: 125 us per
+// rollout launch unpaced, 110 paced).  So a store wave keeps to a schedule: pace_fp is the time
+// one step of the whole launch should take (ticks of the constant-rate clock, 8 fractional
+// bits; 0 = no pacing); a block of steps gets that much time, and what the wave does not need
+// for its own work -- the previous block's time less its sleep -- it sleeps, in units spread
+// between the block's stores.  The schedule is absolute, so errors do not add up; a wave that
+// falls a whole block behind restarts it instead of catching up in a burst; a wave that
+// cannot keep it at all (the launch is bound by something else) drops it after four blocks
+// and costs nothing from then on.
+struct StorePacer {
+    uint32_t pace;        // ticks per step (8 fractional bits), 0 = off
+    uint32_t unit_fp;     // one sleep unit (s_sleep 1) in the same measure, calibrated at the start
+    uint32_t work_fp;     // the previous block's duration less its sleep
+    uint64_t sched_fp;    // when the current block's stores should be out
+    uint64_t t_begin;
+    uint32_t units;       // sleep units of the current block
+    int behind;           // blocks in a row without time to sleep (-1: before the first block)
+
+    __device__ __forceinline__ static uint64_t now_fp() { return __builtin_amdgcn_s_memrealtime() << 8; }
+    __device__ __forceinline__ static void nap(uint32_t n)
+    {
+        for (uint32_t q = 0; q < n; ++q) __builtin_amdgcn_s_sleep(1);
+    }
+    __device__ __forceinline__ void init(uint32_t pace_fp)
+    {
+        pace = pace_fp; unit_fp = 256; work_fp = 0; sched_fp = 0; t_begin = 0; units = 0; behind = -1;
+        if (pace) {
+            const uint64_t c0 = now_fp();
+#pragma unroll
+            for (int q = 0; q < 16; ++q) __builtin_amdgcn_s_sleep(1);
+            unit_fp = max(16u, (uint32_t)((now_fp() - c0) >> 4));
+        }
+    }
+    // Start a block of `steps` steps; returns the sleep units to spread over it (at most max_units).
+    __device__ __forceinline__ uint32_t begin(uint32_t steps, uint32_t max_units)
+    {
+        units = 0;
+        if (!pace) return 0;
+        t_begin = now_fp();
+        const uint64_t block_fp = (uint64_t)steps * pace;
+        if (behind < 0) { sched_fp = t_begin; behind = 0; }
+        sched_fp += block_fp;
+        const int64_t spare = (int64_t)(sched_fp - t_begin) - (int64_t)work_fp;
+        if (spare >= (int64_t)unit_fp) {
+            units = min(max_units, (uint32_t)(spare / unit_fp));
+            behind = 0;
+        } else {
+            if (spare < -(int64_t)block_fp) sched_fp = t_begin + block_fp;
+            if (++behind >= 4) pace = 0;
+        }
+        return units;
+    }
+    __device__ __forceinline__ void end()
+    {
+        if (!pace) return;
+        const uint64_t took = now_fp() - t_begin, slept = (uint64_t)units * unit_fp;
+        work_fp = took > slept ? (uint32_t)min((uint64_t)0x7FFFFFFF, took - slept) : 0u;
+    }
+};
+
 // The same for a piece of which only the first `valid` (< 16) bytes exist (the last, partly
 // filled workgroup of a batch).
 __device__ __forceinline__ void store_bytes(int8_t *dst, const uint4 &v, int valid)

@@ -866,44 +866,14 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         __syncthreads();                                             // block 0 published
         __syncthreads();                                             // block 0 viewed
         __syncthreads();                                             // block 0 recorded
-        // Pacing.  The memory system takes this write stream fastest when it is offered at a
-        // steady rate just below what it can sustain; offered more (every wave storing as fast as
-        // the queues accept) its throughput drops by a fifth.  So the store waves keep to a
-        // schedule: pace_fp is the time one step of the whole launch should take (ticks of the
-        // constant-rate clock, 8 fractional bits; 0 = no pacing), a block of steps gets that much
-        // time, and what a wave does not need for its own work -- the previous block's time less
-        // its sleep -- it sleeps, spread over the block's steps.  The schedule is absolute, so
-        // errors do not add up; a wave that cannot keep it (the launch is bound by something else)
-        // drops it after a few blocks and costs nothing from then on.
-        uint32_t pace = pace_fp;
-        uint32_t unit_fp = 256;                      // one sleep unit in ticks (8 fractional bits)
-        if (pace) {
-            const uint64_t c0 = __builtin_amdgcn_s_memrealtime();
-            _Pragma("unroll") for (int q = 0; q < 16; ++q) __builtin_amdgcn_s_sleep(1);
-            const uint64_t c1 = __builtin_amdgcn_s_memrealtime();
-            unit_fp = max(16u, (uint32_t)(c1 - c0) * 16u);
-        }
-        uint64_t sched_fp = 0;                       // when the current block's stores should be out
-        uint32_t work_fp = 0;                        // the previous block's duration less its sleep
-        int behind = -1;                             // blocks in a row without time to sleep (-1: first block)
+        StorePacer pacer;                      // (see maze_store_device.h)
+        pacer.init(pace_fp);
         MAZE_FOR_EACH_BLOCK(
-            uint32_t units = 0;
-            uint64_t t_begin = 0;
-            if (pace) {
-                t_begin = __builtin_amdgcn_s_memrealtime() << 8;
-                const uint64_t block_fp = (uint64_t)(full ? SPB : n_steps - i0) * pace;
-                if (behind < 0) { sched_fp = t_begin; behind = 0; }
-                sched_fp += block_fp;
-                const int64_t spare = (int64_t)(sched_fp - t_begin) - (int64_t)work_fp;
-                if (spare >= (int64_t)unit_fp) {
-                    units = min(SPB * 63u, (uint32_t)(spare / unit_fp));
-                    behind = 0;
-                } else {
-                    if (spare < -(int64_t)block_fp) sched_fp = t_begin + block_fp;   // never catch up in a burst
-                    if (++behind >= 4) pace = 0;
-                }
-            }
+            constexpr uint32_t SLOTS = SPB * MYR;  // stores of a wave per block
+            const uint32_t units = pacer.begin(full ? SPB : n_steps - i0, SLOTS * 63u);
             if (units == 0) {
+                // (kept apart: without the sleep loops between them the compiler overlaps the
+                // LDS reads of the block's steps)
                 _Pragma("unroll") for (int u = 0; u < SPB; ++u) if (MAZE_STEP_ON(u)) {
                     const uint32_t *rec = lds + L::REC + (par * SPB + u) * L::REC_SIZE;
                     _Pragma("unroll") for (int j = 0; j < MYR; ++j) {
@@ -914,8 +884,6 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                     }
                 }
             } else {
-                // the sleep units go evenly between the block's SPB * MYR stores
-                constexpr uint32_t SLOTS = SPB * MYR;
                 const uint32_t per_slot = units / SLOTS, extra = units % SLOTS;
                 _Pragma("unroll") for (int u = 0; u < SPB; ++u) if (MAZE_STEP_ON(u)) {
                     const uint32_t *rec = lds + L::REC + (par * SPB + u) * L::REC_SIZE;
@@ -925,16 +893,11 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                                 consume_window_typed(rec, win[j], out_block + u * step_obs, lds + L::TYPED);
                             else consume_window(rec, win[j], out_block + u * step_obs);
                         }
-                        const uint32_t naps = per_slot + ((uint32_t)(u * MYR + j) < extra ? 1u : 0u);
-                        for (uint32_t q = 0; q < naps; ++q) __builtin_amdgcn_s_sleep(1);
+                        StorePacer::nap(per_slot + ((uint32_t)(u * MYR + j) < extra ? 1u : 0u));
                     }
                 }
             }
-            if (pace) {
-                const uint64_t t_end = __builtin_amdgcn_s_memrealtime() << 8;
-                const uint64_t slept = (uint64_t)units * unit_fp;
-                work_fp = t_end - t_begin > slept ? (uint32_t)min((uint64_t)0x7FFFFFFF, t_end - t_begin - slept) : 0u;
-            }
+            pacer.end();
             out_block += SPB * step_obs;)
     }
 }
@@ -1001,14 +964,6 @@ __global__ __launch_bounds__(REPW) void k_step_render_tiled(
     }
 }
 
-// The write rate the store waves of a large launch are paced to.  Config 3 (256 workgroups x
-// 9600 B per step), 256-step rollout, launches back to back: unpaced 125 us; paced to 6700 GB/s
-// 113.1, 6900: 110.2, 7100: 107.5, 7300: 104.8 -- but past a shape-dependent point the stream
-// falls back to the unpaced rate (view 7 on 20 x 20 grids: 115 us at 6700 and 6900, 124 at 7100,
-// 126 unpaced; typed observation and 65536 envs: fine at 7100, back at 7300), so the
-// constant stays below the lowest such point.
-constexpr double PACED_GBS = 6900.0;
-
 // LDS a workgroup of a rollout may use on this device: what a CU has, less 1 KB that the
 // runtime may claim for itself.
 inline size_t lds_budget(const maze_ctx *ctx) { return ctx->lds_per_cu > 1024 ? ctx->lds_per_cu - 1024 : 0; }
@@ -1049,20 +1004,16 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
     const dim3 grid(groups), block(64 * V::WAVES);
     // Pacing of the store waves (see the kernel's stores stage): the time one step of the launch
     // should take if the workgroups resident at once write their chunks, reward and done at
-    // PACED_GBS.  Paced are launches of 64- and 128-env workgroups that write more than twice
+    // MAZE_PACED_GBS.  Paced are launches of 64- and 128-env workgroups that write more than twice
     // what the 256 MB memory-side cache holds (a smaller output is absorbed there and leaves
     // the chip later: 16384 envs x 256 steps take 52 us unpaced, 57 paced) and do not build the
     // occluded view (there the records stage sets the pace: 117 us unpaced, 120 paced).
-    // A launch whose steps would be scheduled shorter than the pipeline's own latency per step can
-    // never be ahead of its schedule and is not paced either.
     uint32_t pace_fp = 0;
-    const double out_bytes = (double)(n_end - n_begin) * n_steps * (V::SB + 5);
-    if (EPW >= 64 && !p.obs_occlusion && out_bytes > 2.0 * 256.0 * 1048576.0 && ctx->clock_khz > 0) {
+    if (EPW >= 64 && !p.obs_occlusion) {
         const size_t per_cu = max((size_t)1, min(lds_budget(ctx) / shmem, (size_t)(32 / V::WAVES)));
         const double resident = (double)min((long long)groups, (long long)ctx->cus * (long long)per_cu);
-        const double step_ns = resident * EPW * (V::SB + 6) / PACED_GBS;      // bytes / (GB/s) = ns
-        const double step_ticks_fp = step_ns * 1e-6 * ctx->clock_khz * 256.0;
-        if (step_ns >= 150.0 && step_ticks_fp < 4.0e9) pace_fp = (uint32_t)step_ticks_fp;
+        pace_fp = maze_pace_fp(ctx->clock_khz, resident * EPW * (V::SB + 6),
+                               (double)(n_end - n_begin) * n_steps * (V::SB + 5), MAZE_PACED_GBS);
     }
     // the square-grid flavour exists for the plain kernel only
     constexpr bool PLAIN = MODE == 0 && !PARTIAL;
