@@ -70,6 +70,50 @@ def time_calls(torch, fn, iters, warmup=2):
     return float(np.mean(ms)), float(np.min(ms))
 
 
+def store_patterns(torch, env, actions, reward, done, obs, N, T, k):
+    """The rollout's write pattern on its own (probe library), the rollout kernel and a plain
+    fill, each timed over back-to-back launches; GB/s of the observation bytes written."""
+    import ctypes
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2311_12716_amd", "libmaze_storeprobe.so"))
+    lib.storeprobe_run.restype = ctypes.c_int
+    lib.storeprobe_run.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
+                                   ctypes.c_int, ctypes.c_void_p]
+    slab = N * 3 * k * k                       # bytes per step
+    groups = N // 128                          # the rollout's workgroups at 128 envs each
+    obs_bytes = obs.numel()
+
+    def probe(pattern, sleep=0):
+        def fn():
+            rc = lib.storeprobe_run(pattern, obs.data_ptr(), slab, groups, T, sleep,
+                                    torch.cuda.current_stream().cuda_stream)
+            if rc != 0:
+                raise RuntimeError(f"storeprobe_run({pattern}) returned {rc}")
+        return fn
+
+    def timed(fn, iters=10):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / iters * 1e3
+        return {"ms": ms, "GB/s": obs_bytes / ms / 1e6}
+
+    table = {"geometry": f"{groups} workgroups x {slab // groups} B per step, {T} steps, {obs_bytes} B",
+             "torch_fill": timed(lambda: obs.fill_(1)),
+             "probe_fill_4KB_blocks": timed(probe(0)),
+             "probe_contiguous_per_workgroup": timed(probe(3)),
+             "probe_slab_plain": timed(probe(1)),
+             "probe_slab_plain_sleep8": timed(probe(1, 8)),
+             "probe_slab_streaming": timed(probe(2))}
+    for sleep in (2, 4, 6, 7, 8, 9, 10, 12, 16):
+        table[f"probe_slab_streaming_sleep{sleep}"] = timed(probe(2, sleep))
+    table["rollout_kernel_obs_bytes_only"] = timed(lambda: env.step(actions, reward, done, obs))
+    return {"store_patterns": table}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -80,6 +124,9 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 per-cell kernels")
     ap.add_argument("--event-every", type=int, default=4,
                     help="bracket every n-th maze_step of the timed region with HIP events")
+    ap.add_argument("--store-patterns", action="store_true",
+                    help="only run the store-pattern probe (paper_2311_12716_amd/probe) at config 3's "
+                         "geometry next to the rollout kernel and a plain fill, print its table")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -110,6 +157,10 @@ def main():
     reward = torch.empty((T, N), dtype=torch.float32, device=dev)
     done = torch.empty((T, N), dtype=torch.uint8, device=dev)
     obs = torch.empty((T, N, k, k, 3), dtype=torch.int8, device=dev)
+
+    if args.store_patterns:
+        print(json.dumps(store_patterns(torch, env, actions, reward, done, obs, N, T, k)))
+        return
 
     kernel_events = []
 
