@@ -61,6 +61,16 @@ def test_c3_full_size():
     assert int(d.sum()) == int(od.sum()) > 0
 
 
+@pytest.mark.parametrize("T", [253, 258])
+def test_paced_rollout_with_a_partial_last_block(T):
+    """Launches that write more than 512 MB run with their store waves on a schedule; here the
+    rollout's length is not a multiple of the 8-step blocks, so the last block is a short one
+    (one step beyond a block at 258, three short of one at 253)."""
+    w = wl.config(3, T=T)
+    note(f"{w.name} T={T}")
+    run_fused(w)
+
+
 def test_c4_editor_full_size_and_handoff():
     """Config 4: 32768 editor envs x 52 placements, full-grid observation and timestep each
     step, then the designed levels go into maze_reset_to_levels and come back unchanged."""
