@@ -87,10 +87,11 @@ static inline int maze_same_device(int ctx_device)
 // most of it (it leaves the chip later: 16384 envs x 256 steps take 52 us unpaced, 57 paced), or
 // steps scheduled shorter than a pipeline's own latency per step (such a launch can never be
 // ahead of its schedule).
+#define MAZE_CACHE_ABSORBS_BYTES (2.0 * 256.0 * 1048576.0)
 static inline uint32_t maze_pace_fp(int clock_khz, double bytes_per_step, double out_bytes_total,
                                     double rate_gbs)
 {
-    if (clock_khz <= 0 || out_bytes_total <= 2.0 * 256.0 * 1048576.0) return 0;
+    if (clock_khz <= 0 || out_bytes_total <= MAZE_CACHE_ABSORBS_BYTES) return 0;
     const double step_ns = bytes_per_step / rate_gbs;                 // bytes / (GB/s) = ns
     const double ticks_fp = step_ns * 1e-6 * clock_khz * 256.0;
     return step_ns >= 150.0 && ticks_fp < 4.0e9 ? (uint32_t)ticks_fp : 0u;

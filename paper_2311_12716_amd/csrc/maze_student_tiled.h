@@ -642,7 +642,10 @@ __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word>
 // PARTIAL: the workgroup may hold fewer than EPW envs (the last envs of a batch, n_end - env0 of
 // them): idle lanes repeat env 0 of the workgroup and write nothing, pieces beyond the last
 // env's bytes are not stored.
-template <int K, typename Word, int EPW, bool SQUARE, int MODE = 0, bool PARTIAL = false>
+// BIG (workgroups of 32 envs only; the larger ones always have it): the flavour for launches whose
+// output is too large for the memory-side cache to absorb, with streaming stores and paced
+// store waves.  Small launches are bound by latency and keep the plain store stage.
+template <int K, typename Word, int EPW, bool SQUARE, int MODE = 0, bool PARTIAL = false, bool BIG = false>
 __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     StudentDev p, int n_begin, int n_end, const int8_t *__restrict__ actions, int n_steps,
     float *__restrict__ reward, uint8_t *__restrict__ done, int8_t *__restrict__ obs, uint32_t pace_fp)
@@ -650,6 +653,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     using V = View<K, EPW>;
     using L = Lds<K, Word, EPW, MODE>;
     constexpr int NT = 64 * V::WAVES;
+    constexpr bool LARGE = EPW >= 64 || BIG;
     constexpr int ACT_BLOCK = V::ACT_BLOCK;
     constexpr int UGV = step_group(K * WordOps<Word>::DW + 3, 40);   // views: wall rows + state
     // records: table words + view (+ the seen cells and the chain state of the occluded view)
@@ -850,16 +854,21 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         }
         const size_t step_obs = (size_t)N * V::SB;
         int8_t *out_block = obs + (size_t)env0 * V::SB;
-        // Streaming stores for the windows whose 128-byte line lies inside this workgroup's
-        // chunk -- decided once, which needs the lines to fall the same way at every step.
-        // (Workgroups of 32 envs keep plain stores: with streaming stores on their inner lines
-        // config 5 took 166 instead of 123 us.)
-        if (EPW >= 64 && step_obs % 128 == 0) {
+        // Streaming stores for the windows whose 128-byte line is written whole by one store
+        // instruction of this wave -- decided once, which needs the lines to fall the same way at
+        // every step.  (A line that two instructions share must stay in the L2 until both have
+        // written it: streamed, its parts reach memory one by one; with every inner line of a
+        // chunk streamed, whichever instruction wrote it, config 5 took 166 instead of 124 us.)
+        if (LARGE && step_obs % 128 == 0) {
             const uintptr_t chunk_lo = (uintptr_t)out_block, chunk_hi = chunk_lo + (size_t)count * V::SB;
 #pragma unroll
             for (int j = 0; j < MYR; ++j) {
+                // the line must be written whole by this one store instruction of the wave (its
+                // 64 windows, 1 KB from the wave's first window on)
                 const uintptr_t line = (chunk_lo + win[j].out) & ~(uintptr_t)127;
-                win[j].stream = win[j].active && win[j].valid >= 16 && line >= chunk_lo && line + 128 <= chunk_hi;
+                const uintptr_t piece_lo = chunk_lo + (win[j].out - 16u * (uint32_t)lane);
+                const uintptr_t piece_hi = piece_lo + 1024 < chunk_hi ? piece_lo + 1024 : chunk_hi;
+                win[j].stream = win[j].active && win[j].valid >= 16 && line >= piece_lo && line + 128 <= piece_hi;
             }
         }
         __syncthreads();                                             // barrier 0 (set-up)
@@ -867,10 +876,10 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         __syncthreads();                                             // block 0 viewed
         __syncthreads();                                             // block 0 recorded
         StorePacer pacer;                      // (see maze_store_device.h)
-        pacer.init(pace_fp);
+        pacer.init(LARGE ? pace_fp : 0u);
         MAZE_FOR_EACH_BLOCK(
             constexpr uint32_t SLOTS = SPB * MYR;  // stores of a wave per block
-            const uint32_t units = pacer.begin(full ? SPB : n_steps - i0, SLOTS * 63u);
+            const uint32_t units = LARGE ? pacer.begin(full ? SPB : n_steps - i0, SLOTS * 63u) : 0u;
             if (units == 0) {
                 // (kept apart: without the sleep loops between them the compiler overlaps the
                 // LDS reads of the block's steps)
@@ -897,7 +906,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                     }
                 }
             }
-            pacer.end();
+            if (LARGE) pacer.end();
             out_block += SPB * step_obs;)
     }
 }
@@ -989,7 +998,7 @@ bool allow_large_lds(Kernel kernel, size_t bytes, size_t *granted)
 // Runs the rollout kernel on envs [n_begin, n_begin + EPW * (n_envs / EPW)) -- with PARTIAL on all
 // n_envs, the last workgroup partly filled -- and returns how many envs that is, or MAZE_EHIP
 // if the device does not grant the LDS the workgroup needs.
-template <int K, typename Word, int EPW, int MODE = 0, bool PARTIAL = false>
+template <int K, typename Word, int EPW, int MODE = 0, bool PARTIAL = false, bool BIG = false>
 int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d_actions, int n_steps,
                    float *d_reward, uint8_t *d_done, int8_t *d_obs, hipStream_t st)
 {
@@ -1004,31 +1013,39 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
     const dim3 grid(groups), block(64 * V::WAVES);
     // Pacing of the store waves (see the kernel's stores stage): the time one step of the launch
     // should take if the workgroups resident at once write their chunks, reward and done at
-    // MAZE_PACED_GBS.  Paced are launches of 64- and 128-env workgroups that write more than twice
+    // MAZE_PACED_GBS.  Paced are launches that write more than twice
     // what the 256 MB memory-side cache holds (a smaller output is absorbed there and leaves
     // the chip later: 16384 envs x 256 steps take 52 us unpaced, 57 paced) and do not build the
     // occluded view (there the records stage sets the pace: 117 us unpaced, 120 paced).
+    const double out_bytes = (double)(n_end - n_begin) * n_steps * (V::SB + 5);
     uint32_t pace_fp = 0;
-    if (EPW >= 64 && !p.obs_occlusion) {
+    if (!p.obs_occlusion) {
         const size_t per_cu = max((size_t)1, min(lds_budget(ctx) / shmem, (size_t)(32 / V::WAVES)));
         const double resident = (double)min((long long)groups, (long long)ctx->cus * (long long)per_cu);
-        pace_fp = maze_pace_fp(ctx->clock_khz, resident * EPW * (V::SB + 6),
-                               (double)(n_end - n_begin) * n_steps * (V::SB + 5), MAZE_PACED_GBS);
+        pace_fp = maze_pace_fp(ctx->clock_khz, resident * EPW * (V::SB + 6), out_bytes, MAZE_PACED_GBS);
+    }
+    // Workgroups of 32 envs: launches too large for the memory-side cache go to the flavour with
+    // streaming stores and pacing, the others (bound by latency: 4096 envs x 256 steps take 39.6 us
+    // with the plain store stage, 42.1 with the other) keep the plain one.
+    if constexpr (EPW == 32 && !PARTIAL && !BIG) {
+        if (out_bytes > MAZE_CACHE_ABSORBS_BYTES)
+            return launch_rollout<K, Word, EPW, MODE, PARTIAL, true>(ctx, n_begin, n_envs, d_actions, n_steps,
+                                                                     d_reward, d_done, d_obs, st);
     }
     // the square-grid flavour exists for the plain kernel only
     constexpr bool PLAIN = MODE == 0 && !PARTIAL;
     const bool square = p.HP == p.WP && PLAIN;
     // largest LDS size granted so far, per kernel flavour and device (the attribute belongs to
     // the kernel on one device); a race between host threads only repeats the call
-    static size_t granted_all[2][16] = {};
+    static size_t granted_all[2][16] = {};      // (one table per instantiation of this function)
     size_t *granted = &granted_all[square ? 0 : 1][ctx->device & 15];
     if (square) {
-        auto kern = k_student_rollout<K, Word, EPW, PLAIN, MODE, PARTIAL>;
+        auto kern = k_student_rollout<K, Word, EPW, PLAIN, MODE, PARTIAL, BIG>;
         if (!allow_large_lds(kern, shmem, granted)) return MAZE_EHIP;
         hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
                            d_done, d_obs, pace_fp);
     } else {
-        auto kern = k_student_rollout<K, Word, EPW, false, MODE, PARTIAL>;
+        auto kern = k_student_rollout<K, Word, EPW, false, MODE, PARTIAL, BIG>;
         if (!allow_large_lds(kern, shmem, granted)) return MAZE_EHIP;
         hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
                            d_done, d_obs, pace_fp);
