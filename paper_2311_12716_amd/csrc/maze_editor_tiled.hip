@@ -103,9 +103,9 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
         const int e_first = (16 * m0) / SB, s_first = 16 * m0 - e_first * SB;
         const size_t step_obs = (size_t)p.N * SB;
         int8_t *out_block = obs + (size_t)env0 * SB;
-        // windows of this lane per step, and whether the lines fall the same way at every step
-        // (then a window whose 128-byte line lies inside the workgroup's chunk is stored in
-        // the streaming form)
+        // rounds of windows per step, and whether the lines fall the same way at every step (then
+        // a window whose 128-byte line is written whole by one store instruction of this wave --
+        // 64 windows, 1 KB -- is stored in the streaming form)
         const int max_rounds = (nwin + NS * 64 - 1) / (NS * 64);
         const bool steady = step_obs % 128 == 0;
         const uintptr_t chunk_lo = (uintptr_t)out_block, chunk_hi = chunk_lo + (size_t)block_bytes;
@@ -129,7 +129,9 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
                 v.z = expand_nibble((bits >> 8) & 15);   v.w = expand_nibble((bits >> 12) & 15);
                 const int valid = block_bytes - 16 * m;
                 const uintptr_t line = (chunk_lo + 16 * (size_t)m) & ~(uintptr_t)127;
-                if (steady && valid >= 16 && line >= chunk_lo && line + 128 <= chunk_hi)
+                const uintptr_t piece_lo = chunk_lo + 16 * (size_t)(m - lane);
+                const uintptr_t piece_hi = piece_lo + 1024 < chunk_hi ? piece_lo + 1024 : chunk_hi;
+                if (steady && valid >= 16 && line >= piece_lo && line + 128 <= piece_hi)
                     store16_stream(out_block + 16 * (size_t)m, v);
                 else if (valid >= 16) store16(out_block + 16 * (size_t)m, v);
                 else store_bytes(out_block + 16 * (size_t)m, v, valid);
