@@ -70,6 +70,10 @@ extern "C" int editor_create(editor_ctx **out, int N, int H, int W, int n_walls,
     if (hipDeviceGetAttribute(&c->cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess ||
         hipDeviceGetAttribute(&c->clock_khz, hipDeviceAttributeWallClockRate, c->device) != hipSuccess)
         c->clock_khz = 0;                         // unknown: the store waves are not paced
+    int lds = 0;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, c->device) != hipSuccess)
+        lds = 64 * 1024;
+    c->lds_per_cu = (size_t)lds;
     *out = c;
     return MAZE_OK;
 }

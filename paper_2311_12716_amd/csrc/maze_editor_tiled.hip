@@ -11,8 +11,11 @@
 //     round j takes stream bits [16*(64*j+l), +16) -- they may straddle two envs --
 //     and writes 16 bytes, so one store instruction of a wave writes 1 KB of
 //     contiguous output.
-// Two barriers per step separate editing from reading; the edit phase is a few
-// dozen instructions, the store phase moves 3*H*W*128 bytes.
+// The streams are kept twice, and the two copies alternate: while the store waves expand
+// copy s & 1 -- the grid after step s -- the edit waves bring the other copy up to step
+// s + 1 (it lags one edit behind, so they apply the previous placement and the new one).
+// One barrier per step; the store waves never wait for an edit, so the output stream has
+// no gap at the step boundaries.
 #include "maze_internal.h"
 #include "maze_store_device.h"
 
@@ -37,7 +40,7 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
     EditorDev p, const int32_t *__restrict__ actions, int n_steps, int8_t *__restrict__ obs,
     int32_t *__restrict__ t_out, uint8_t *__restrict__ done, uint32_t pace_fp)
 {
-    extern __shared__ uint32_t lds[];            // [EPW][REC], REC = SW + 1 (last dword stays 0)
+    extern __shared__ uint32_t lds[];            // [2][EPW][REC], REC = SW + 1 (last dword stays 0)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int env0 = xcd_contiguous(blockIdx.x, gridDim.x) * EPW;
@@ -45,10 +48,14 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
     const int SB = 3 * p.cells;                  // stream bits = obs bytes per env
     const int count = min(EPW, p.N - env0);      // envs of this workgroup (the last one may be partly filled)
 
-    // stage the streams (and zero the pad dwords; streams of absent envs read as empty)
-    for (int i = tid; i < EPW * REC; i += 64 * NWAVES) {
+    const int COPY = EPW * REC;                  // dwords of one copy of the streams
+    // stage the streams into both copies (and zero the pad dwords; streams of absent envs
+    // read as empty)
+    for (int i = tid; i < COPY; i += 64 * NWAVES) {
         int e = i / REC, o = i - e * REC;
-        lds[i] = (o < SW && e < count) ? p.stream[(size_t)(env0 + e) * SW + o] : 0u;
+        const uint32_t v = (o < SW && e < count) ? p.stream[(size_t)(env0 + e) * SW + o] : 0u;
+        lds[i] = v;
+        lds[COPY + i] = v;
     }
     __syncthreads();
 
@@ -57,37 +64,48 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
         const int e = wave * 64 + lane;
         const bool present = e < count;
         const int n = env0 + (present ? e : 0);  // absent lanes repeat env 0's reads, write nothing
-        uint32_t *rec = lds + e * REC;
+        uint32_t *rec0 = lds + e * REC;          // this env's record in copy 0; copy 1 is COPY further
         int32_t t = p.t[n], ac = p.agent_cell[n], gc = p.goal_cell[n];
         const int32_t *act = actions + n;
         int32_t a_next = act[0];
+        int prev_clear = -1, prev_set = -1;      // the placement the other copy has not seen yet
         for (int s = 0; s < n_steps; ++s) {
             const int32_t action = a_next;
             if (s + 1 < n_steps) a_next = act[(size_t)(s + 1) * p.N];
             const int a = min(max(action, 0), p.cells - 1);
+            int clear = -1, set = -1;
             if (t < p.n_walls) {
-                lds_set_bit(rec, 3 * a);
+                set = 3 * a;
             } else if (t == p.n_walls) {
                 ac = a;
-                lds_clear_bit(rec, 3 * a);
-                lds_set_bit(rec, 3 * a + 2);
+                clear = 3 * a;
+                set = 3 * a + 2;
             } else if (t == p.n_walls + 1) {
                 const int j = (a == ac) ? ((a + 1 == p.cells) ? 0 : a + 1) : a;
                 gc = j;
-                lds_clear_bit(rec, 3 * j);
-                lds_set_bit(rec, 3 * j + 1);
+                clear = 3 * j;
+                set = 3 * j + 1;
             }
+            // copy s & 1 becomes the grid after step s: the placement it missed, then this one
+            // (in this order: a later placement may clear what an earlier one set)
+            uint32_t *rec = rec0 + (s & 1) * COPY;
+            if (prev_clear >= 0) lds_clear_bit(rec, prev_clear);
+            if (prev_set >= 0) lds_set_bit(rec, prev_set);
+            if (clear >= 0) lds_clear_bit(rec, clear);
+            if (set >= 0) lds_set_bit(rec, set);
+            prev_clear = clear;
+            prev_set = set;
             if (t < p.n_walls + 2) t += 1;
             if (t_out && present) t_out[(size_t)s * p.N + n] = t;
             if (done && present) done[(size_t)s * p.N + n] = (t == p.n_walls + 2) ? 1 : 0;
-            __syncthreads();                     // edits of step s visible
-            __syncthreads();                     // stores of step s have read the streams
+            __syncthreads();                     // copy s & 1 is ready; the other is free to edit
         }
-        // write the state back
+        // write the state back (the copy of the last step is complete)
         if (present) {
             p.t[n] = t;
             p.agent_cell[n] = ac;
             p.goal_cell[n] = gc;
+            const uint32_t *rec = rec0 + ((n_steps - 1) & 1) * COPY;
             for (int o = 0; o < SW; ++o) p.stream[(size_t)n * SW + o] = rec[o];
         }
     } else {
@@ -112,13 +130,14 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
         StorePacer pacer;                         // (see maze_store_device.h)
         pacer.init(pace_fp);
         for (int s = 0; s < n_steps; ++s) {
-            __syncthreads();                     // edits of step s visible
+            __syncthreads();                     // copy s & 1 holds the grid after step s
+            const uint32_t *copy = lds + (s & 1) * COPY;
             const uint32_t units = pacer.begin(1, (uint32_t)max_rounds * 63u);
             const uint32_t per_round = units / (uint32_t)max_rounds, extra = units % (uint32_t)max_rounds;
             int e0 = e_first, bs = s_first;
             uint32_t round = 0;
             for (int m = m0; m < nwin; m += NS * 64, ++round) {
-                const uint32_t *r0 = lds + e0 * REC;
+                const uint32_t *r0 = copy + e0 * REC;
                 const int rem = SB - bs;
                 const bool spill = rem < 16;     // window runs into the next env
                 uint32_t lo = r0[bs >> 5], hi = r0[(bs >> 5) + 1];
@@ -142,7 +161,6 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
             }
             pacer.end();
             out_block += step_obs;
-            __syncthreads();                     // reads done before the next edit
         }
     }
 }
@@ -157,8 +175,17 @@ int editor_tiled_launch(const editor_ctx *ctx, const int32_t *d_actions, int n_s
     const EditorDev &p = ctx->dev;
     *covered = 0;
     if (!d_obs) return 0;
-    size_t shmem = 4 * (size_t)EPW * (p.SW + 1);
-    if (shmem > 60 * 1024) return 0;
+    // two copies of the streams of 128 envs; above the 64 KB default the kernel's LDS limit is
+    // raised once per device; streams too large for that go to the per-cell kernel
+    const size_t shmem = 2 * 4 * (size_t)EPW * (p.SW + 1);
+    if (shmem > 120 * 1024 || shmem + 1024 > ctx->lds_per_cu) return 0;
+    static size_t granted[16] = {};
+    if (shmem > 64 * 1024 && shmem > granted[ctx->device & 15]) {
+        if (hipFuncSetAttribute((const void *)k_editor_tiled, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)shmem) != hipSuccess)
+            return 0;
+        granted[ctx->device & 15] = shmem;
+    }
     if (3 * p.cells < 16) return 0;              // a 16-bit window must not span more than two envs
     const int groups = (p.N + EPW - 1) / EPW;
     // store waves paced like the student rollout's: the workgroups resident at once (one per

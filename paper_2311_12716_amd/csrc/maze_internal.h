@@ -77,8 +77,8 @@ static inline int maze_same_device(int ctx_device)
 // 7300), so the constant stays below the lowest such point.
 #define MAZE_PACED_GBS 6900.0
 // The editor's stream (64896 B per workgroup and step at 13 x 13) turns earlier: config 4 takes
-// 163 us unpaced and at 6900, 144 to 158 at 6200 to 6600 (the faster state is not always
-// reached), 156 at 6000, 229 at 4000 (there the schedule alone sets the time).
+// 163 us unpaced and at 6900 or 7200, 142 at 6700 (but 163 for the first dozens of launches),
+// 146.5 at 6400, 155 at 6000 (there and below the schedule alone sets the time).
 #define MAZE_PACED_GBS_EDITOR 6400.0
 
 // Time one step of a launch should take, in ticks of the device's constant-rate clock with 8
@@ -119,5 +119,6 @@ struct editor_ctx {
     int device;
     int cus;                // compute units and clock rate of the device (pacing of the store waves)
     int clock_khz;
+    size_t lds_per_cu;      // LDS of a compute unit (the tiled kernel keeps two copies of 128 envs' streams)
     size_t workspace_bytes;
 };
