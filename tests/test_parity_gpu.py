@@ -324,7 +324,12 @@ def test_set_state_matches_the_oracle(H, W, k):
 
 
 @pytest.mark.parametrize("N,H,W,nw,T", [(1, 13, 13, 50, 52), (65, 5, 8, 12, 20), (300, 13, 13, 0, 5),
-                                        (100, 2, 1, 3, 7), (130, 64, 64, 40, 44), (64, 9, 4, 20, 30)])
+                                        (100, 2, 1, 3, 7), (130, 64, 64, 40, 44), (64, 9, 4, 20, 30),
+                                        # two copies of the streams: 58 KB (default LDS limit), 86 and
+                                        # 113 KB (raised limit), 120 KB (the limit itself), 123 KB (too
+                                        # large: per-cell kernel)
+                                        (200, 24, 25, 30, 34), (140, 30, 30, 30, 35), (129, 35, 34, 20, 24),
+                                        (70, 36, 35, 20, 23), (70, 37, 35, 20, 23)])
 def test_editor_shapes_and_overrun(N, H, W, nw, T):
     rng = np.random.default_rng(N + H)
     # out-of-range actions included: they are clamped
