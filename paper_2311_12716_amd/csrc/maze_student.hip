@@ -124,137 +124,7 @@ extern "C" int maze_set_obs_mode(maze_ctx *ctx, int encoding, int occlusion)
 }
 
 // ------------------------------------------------------------- level packing
-// G lanes per env (16, 32 or 64: small grids share a wave, so that fewer, fuller waves
-// are launched).  The H*W wall bytes of an env are turned into two bitmaps with wave
-// ballots -- row-major (bit y*W + x) and column-major (bit x*H + y) -- G cells of every
-// env of the wave per ballot, kept in the env's slice of LDS.  Every row of the four
-// heading frames is then one field of one of the bitmaps (reversed for the two frames
-// that look against the axis), shifted into the ring of border walls.  Five lanes per
-// env also pack the start pose and the goal's position in the four frames.
 constexpr int PACK_WAVES = 4;                 // waves per workgroup
-
-// floor(n / d) for n < 2^16, d < 2^16 as one multiply: magic = ceil(2^32 / d) (0 stands for d = 1).
-__device__ __forceinline__ int div_magic(int n, uint32_t magic)
-{
-    return magic ? (int)__umulhi((uint32_t)n, magic) : n;
-}
-
-static uint32_t magic_of(int d) { return d == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); }
-
-__device__ __forceinline__ uint64_t bitmap_field(const uint32_t *bm, int offset, int len)
-{
-    const int w = offset >> 5, sh = offset & 31;
-    const uint64_t lo = ((uint64_t)bm[w + 1] << 32) | bm[w];
-    const uint64_t hi = bm[w + 2];
-    uint64_t v = lo >> sh;
-    if (sh) v |= hi << (64 - sh);
-    return len >= 64 ? v : (v & (((uint64_t)1 << len) - 1));
-}
-
-// G-bit piece number c of a bitmap
-template <int G>
-__device__ __forceinline__ void store_piece(uint32_t *bm, int c, uint64_t piece)
-{
-    if (G == 16) ((uint16_t *)bm)[c] = (uint16_t)piece;
-    else if (G == 32) bm[c] = (uint32_t)piece;
-    else { bm[2 * c] = (uint32_t)piece; bm[2 * c + 1] = (uint32_t)(piece >> 32); }
-}
-
-// MAXC = largest H*W this instantiation takes; a bitmap has MAXC/32 dwords + 4 of zero tail.
-template <typename Word, int G, int MAXC>
-__global__ __launch_bounds__(64 * PACK_WAVES) void k_pack_levels(
-    StudentDev p, uint32_t magic_h, uint32_t magic_sp, const int8_t *__restrict__ walls,
-    const int32_t *__restrict__ agent_xy, const int8_t *__restrict__ agent_dir,
-    const int32_t *__restrict__ goal_xy)
-{
-    constexpr int EPV = 64 / G;                  // envs per wave
-    constexpr int BM = MAXC / 32 + 4;
-    __shared__ uint32_t lds[PACK_WAVES * EPV][2][BM];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int sub = lane / G, l = lane - sub * G;
-    const int n_raw = (blockIdx.x * PACK_WAVES + wave) * EPV + sub;
-    const bool live = n_raw < p.N;
-    const int n = live ? n_raw : p.N - 1;        // idle lanes repeat the last env, store nothing
-    uint32_t *bm_rm = lds[wave * EPV + sub][0], *bm_cm = lds[wave * EPV + sub][1];
-    // the five pose lanes request their inputs now: the round trip overlaps the wall bytes'
-    const int32_t *pos_src = l < 4 ? goal_xy : agent_xy;
-    const int pos_x = l < 5 ? pos_src[2 * n] : 0, pos_y = l < 5 ? pos_src[2 * n + 1] : 0;
-    const int start_dir = agent_dir[n] & 3;
-    const int cells = p.H * p.W;
-    const int8_t *g = walls + (size_t)n * cells;
-    for (int i = l; i < 2 * BM; i += G) bm_rm[i] = 0;        // both bitmaps (they are adjacent)
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const int chunks = (cells + G - 1) / G;
-    const uint64_t sub_mask = G == 64 ? ~(uint64_t)0 : (((uint64_t)1 << G) - 1);
-    // UNR chunks at a time, all their loads issued before the first ballot (one memory round
-    // trip per group; measured: 16 at a time is slower than 4)
-    constexpr int UNR = 4;
-    for (int c0 = 0; c0 < chunks; c0 += UNR) {
-        bool rm[UNR], cm[UNR];
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const int idx = (c0 + u) * G + l;
-            const bool valid = idx < cells;
-            const int x = valid ? div_magic(idx, magic_h) : 0, y = valid ? idx - x * p.H : 0;
-            rm[u] = valid && g[valid ? idx : 0] != 0;
-            cm[u] = valid && g[y * p.W + x] != 0;
-        }
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const int c = c0 + u;
-            const uint64_t m_rm = (__ballot(rm[u]) >> (sub * G)) & sub_mask;
-            const uint64_t m_cm = (__ballot(cm[u]) >> (sub * G)) & sub_mask;
-            if (l == 0 && c < chunks) {
-                store_piece<G>(bm_rm, c, m_rm);
-                store_piece<G>(bm_cm, c, m_cm);
-            }
-        }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    Word *out = (Word *)p.grids + (size_t)n * 4 * p.SP;
-    for (int task = l; task < 4 * p.SP; task += G) {
-        const int d = div_magic(task, magic_sp), row = task - d * p.SP;
-        const int rows = (d & 1) ? p.HP : p.WP;  // shape of frame d
-        const int len = (d & 1) ? p.W : p.H;     // interior cells per row of frame d
-        uint64_t word = ~(uint64_t)0;            // border rows and rows beyond the frame: solid
-        const int r = row - p.P;                 // interior line of the frame
-        if (row < rows && r >= 0 && r < rows - 2 * p.P) {
-            // frames 3 and 1 read lines of the row-major bitmap (W cells), frames 0 and 2 lines
-            // of the column-major one (H cells); frames 1 and 2 run against the axis (reversed
-            // bits), frames 1 and 0 take the lines in reverse order.  One field read per lane.
-            const bool col_major = !(d & 1);
-            const uint32_t *bm = col_major ? bm_cm : bm_rm;
-            const int lines = col_major ? p.W : p.H;
-            const int line = (d == 1 || d == 0) ? lines - 1 - r : r;
-            uint64_t f = bitmap_field(bm, line * len, len);
-            const uint64_t rev = __brevll(f) >> (64 - len);
-            f = (d == 1 || d == 2) ? rev : f;
-            const uint64_t field_mask = (((uint64_t)1 << len) - 1) << p.P;
-            word = (f << p.P) | ~field_mask;
-        }
-        if (live) out[task] = (Word)word;
-    }
-    if (l < 5 && live) {
-        const int X = min(max(pos_x, 0), p.W - 1) + p.P;
-        const int Y = min(max(pos_y, 0), p.H - 1) + p.P;
-        const int d = l < 4 ? l : start_dir;
-        int xd, yd;
-        padded_to_frame(p, d, X, Y, xd, yd);
-        const uint32_t v = (uint32_t)xd | ((uint32_t)yd << 8);
-        if (l < 4) {
-            p.goalrot[4 * n + l] = v;
-        } else {
-            const uint32_t s = v | ((uint32_t)d << 16);
-            p.start[n] = s;
-            p.pose[n] = s;
-            p.tcount[n] = 0;
-        }
-    }
-}
 
 // Level packing for grids whose padded rows fit 32-bit words (every 13 x 13 configuration).
 // G = 16 or 32 lanes per env, max(H, W) <= G: lane l assembles row l of the wall grid as a
@@ -384,26 +254,98 @@ __global__ __launch_bounds__(64 * PACK_WAVES) void k_pack_levels_rows(
     }
 }
 
-template <typename Word>
-static void launch_pack(const StudentDev &p, const int8_t *d_walls, const int32_t *d_agent_xy,
-                        const int8_t *d_agent_dir, const int32_t *d_goal_xy, hipStream_t st)
+// The same for padded rows of 33 to 64 bits (grids up to 60 x 60): one env per wave, lane l takes
+// row l and column l, a line of bits is two 32-bit halves; the 64 x 64 bit matrix is transposed
+// by one exchange across the wave's halves (blocks of 32) and the five butterfly stages on
+// either half.
+__global__ __launch_bounds__(64 * PACK_WAVES) void k_pack_levels_rows64(
+    StudentDev p, const int8_t *__restrict__ walls, const int32_t *__restrict__ agent_xy,
+    const int8_t *__restrict__ agent_dir, const int32_t *__restrict__ goal_xy)
 {
-    const int cells = p.H * p.W;
-    const dim3 block(64 * PACK_WAVES);
-    const uint32_t mh = magic_of(p.H), msp = magic_of(p.SP);
-    auto grid_for = [&](int envs_per_wave) {
-        const int per_block = PACK_WAVES * envs_per_wave;
-        return dim3((p.N + per_block - 1) / per_block);
-    };
-    if (cells <= 256)
-        hipLaunchKernelGGL((k_pack_levels<Word, 16, 256>), grid_for(4), block, 0, st, p, mh, msp, d_walls,
-                           d_agent_xy, d_agent_dir, d_goal_xy);
-    else if (cells <= 1024)
-        hipLaunchKernelGGL((k_pack_levels<Word, 32, 1024>), grid_for(2), block, 0, st, p, mh, msp, d_walls,
-                           d_agent_xy, d_agent_dir, d_goal_xy);
-    else
-        hipLaunchKernelGGL((k_pack_levels<Word, 64, 4096>), grid_for(1), block, 0, st, p, mh, msp, d_walls,
-                           d_agent_xy, d_agent_dir, d_goal_xy);
+    constexpr int IN_DWORDS = 64 * 64 / 4;           // wall bytes of an env, at most
+    constexpr int OUT_DWORDS = 4 * 64 * 2;           // its frames, at most (SP <= 64 words of 64 bits)
+    __shared__ uint32_t in_lds[PACK_WAVES][IN_DWORDS];
+    __shared__ __align__(16) uint32_t out_lds[PACK_WAVES][OUT_DWORDS];
+    const int l = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = blockIdx.x * PACK_WAVES + wave;
+    if (n >= p.N) return;                            // (no workgroup barrier below)
+    const int32_t *pos_src = l < 4 ? goal_xy : agent_xy;
+    const int pos_x = l < 5 ? pos_src[2 * n] : 0, pos_y = l < 5 ? pos_src[2 * n + 1] : 0;
+    const int start_dir = agent_dir[n] & 3;
+    const int H = p.H, W = p.W, P = p.P, SP = p.SP, cells = H * W;
+    const int8_t *src = walls + (size_t)n * cells;
+    uint32_t *in = in_lds[wave];
+    for (int i = l; 4 * i < cells; i += 64) {
+        uint32_t v = 0;
+        if (4 * i + 4 <= cells) {
+            __builtin_memcpy(&v, src + 4 * i, 4);
+        } else {
+            for (int b = 0; 4 * i + b < cells; ++b) v |= (uint32_t)(uint8_t)src[4 * i + b] << (8 * b);
+        }
+        in[i] = v;
+    }
+    wave_lds_sync();
+    uint32_t rlo = 0, rhi = 0;                       // row l: bit x = wall(x, l), x < 32 in rlo
+    if (l < H) {
+        const uint8_t *row = (const uint8_t *)in + l * W;
+        for (int x0 = 0; x0 < W; x0 += 8) {
+            uint32_t b[8], part = 0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) b[u] = row[min(x0 + u, W - 1)];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) part |= (b[u] ? 1u : 0u) << u;
+            if (x0 < 32) rlo |= part << x0;
+            else rhi |= part << (x0 - 32);
+        }
+        // (the last group repeated the row's last cell beyond its end: cut that off)
+        if (W < 32) { rlo &= (1u << W) - 1u; rhi = 0; }
+        else if (W < 64) rhi &= (1u << (W - 32)) - 1u;
+    }
+    // column l after the transpose: bit y = wall(l, y)
+    uint32_t clo = rlo, chi = rhi;
+    {
+        const uint32_t give = (l & 32) ? clo : chi;
+        const uint32_t got = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (l ^ 32), (int)give);
+        if (l & 32) clo = got; else chi = got;
+    }
+    clo = transpose_stage<16>(clo, l); chi = transpose_stage<16>(chi, l);
+    clo = transpose_stage<8>(clo, l);  chi = transpose_stage<8>(chi, l);
+    clo = transpose_stage<4>(clo, l);  chi = transpose_stage<4>(chi, l);
+    clo = transpose_stage<2>(clo, l);  chi = transpose_stage<2>(chi, l);
+    clo = transpose_stage<1>(clo, l);  chi = transpose_stage<1>(chi, l);
+    const uint64_t r = ((uint64_t)rhi << 32) | rlo, c = ((uint64_t)chi << 32) | clo;
+    uint64_t *out = (uint64_t *)out_lds[wave];
+    for (int i = l; i < 4 * SP; i += 64) out[i] = ~(uint64_t)0;
+    wave_lds_sync();
+    if (l < H) {                                     // (W, H <= 60: every shift below is < 64)
+        const uint64_t field = (((uint64_t)1 << W) - 1u) << P;
+        out[3 * SP + P + l] = (r << P) | ~field;
+        out[1 * SP + (p.HP - 1 - P - l)] = ((__brevll(r) >> (64 - W)) << P) | ~field;
+    }
+    if (l < W) {
+        const uint64_t field = (((uint64_t)1 << H) - 1u) << P;
+        out[0 * SP + (p.WP - 1 - P - l)] = (c << P) | ~field;
+        out[2 * SP + P + l] = ((__brevll(c) >> (64 - H)) << P) | ~field;
+    }
+    wave_lds_sync();
+    uint4 *dst = (uint4 *)((uint64_t *)p.grids + (size_t)n * 4 * SP);
+    for (int i = l; i < 2 * SP; i += 64) dst[i] = ((const uint4 *)out)[i];
+    if (l < 5) {
+        const int X = min(max(pos_x, 0), W - 1) + P;
+        const int Y = min(max(pos_y, 0), H - 1) + P;
+        const int d = l < 4 ? l : start_dir;
+        int xd, yd;
+        padded_to_frame(p, d, X, Y, xd, yd);
+        const uint32_t v = (uint32_t)xd | ((uint32_t)yd << 8);
+        if (l < 4) {
+            p.goalrot[4 * n + l] = v;
+        } else {
+            const uint32_t st = v | ((uint32_t)d << 16);
+            p.start[n] = st;
+            p.pose[n] = st;
+            p.tcount[n] = 0;
+        }
+    }
 }
 
 extern "C" int maze_reset_to_levels(maze_ctx *ctx, const int8_t *d_walls,
@@ -414,15 +356,17 @@ extern "C" int maze_reset_to_levels(maze_ctx *ctx, const int8_t *d_walls,
     MAZE_DEVICE_CHECK(ctx);
     hipStream_t st = (hipStream_t)stream;
     const StudentDev &p = ctx->dev;
+    const dim3 block(64 * PACK_WAVES);
+    auto blocks = [&](int envs_per_wave) {
+        const int per_block = PACK_WAVES * envs_per_wave;
+        return dim3((p.N + per_block - 1) / per_block);
+    };
     if (ctx->word64) {
-        launch_pack<uint64_t>(p, d_walls, d_agent_xy, d_agent_dir, d_goal_xy, st);
+        // 64-bit rows: SP <= 64, so max(H, W) <= 60
+        hipLaunchKernelGGL(k_pack_levels_rows64, blocks(1), block, 0, st, p, d_walls, d_agent_xy,
+                           d_agent_dir, d_goal_xy);
     } else {
         // 32-bit rows: SP <= 32, so max(H, W) <= 28
-        const dim3 block(64 * PACK_WAVES);
-        auto blocks = [&](int envs_per_wave) {
-            const int per_block = PACK_WAVES * envs_per_wave;
-            return dim3((p.N + per_block - 1) / per_block);
-        };
         if (p.H <= 16 && p.W <= 16)
             hipLaunchKernelGGL(k_pack_levels_rows<16>, blocks(4), block, 0, st, p, d_walls, d_agent_xy,
                                d_agent_dir, d_goal_xy);
