@@ -75,3 +75,45 @@ def test_replayed_step_and_rollout_match_the_oracle():
         assert (nwalls.cpu().numpy() == onw).all() and (plen.cpu().numpy() == opl).all()
         t += 8
         assert scratch > 0
+
+
+def test_replayed_pass_of_the_throughput_configuration():
+    """Reset to levels + first render + the 256-step rollout of config 3 -- the launch whose store
+    waves keep a clock schedule -- captured once and replayed; every replay against the oracle."""
+    w = wl.config(3)
+    env = gpu_student(w)
+    lv = (to_gpu(w.walls), to_gpu(w.agent_xy), to_gpu(w.agent_dir), to_gpu(w.goal_xy))
+    acts = to_gpu(w.actions)
+    N, T, k = w.N, w.T, w.view
+    obs0 = torch.empty((N, k, k, 3), dtype=torch.int8, device=DEV)
+    r = torch.empty((T, N), dtype=torch.float32, device=DEV)
+    d = torch.empty((T, N), dtype=torch.uint8, device=DEV)
+    obs = torch.empty((T, N, k, k, 3), dtype=torch.int8, device=DEV)
+
+    def one_pass():
+        env.reset_to_levels(*lv)
+        env.render_obs(obs0)
+        env.step(acts, r, d, obs)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        one_pass()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one_pass()
+    o = cpu_student(w)
+    want_obs0 = o.render_obs()
+    orr, od, oobs = o.step(w.actions, T)
+    for rep in range(3):
+        note(f"pass replay {rep}")
+        obs.zero_()
+        r.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (obs0.cpu().numpy() == want_obs0).all()
+        assert (d.cpu().numpy() == od).all() and np.abs(r.cpu().numpy() - orr).max() <= 1e-6
+        assert (obs.cpu().numpy() == oobs).all()
+        assert torch.rand((1 << 20,), device=DEV).sum().item() > 0       # unrelated eager work
