@@ -294,13 +294,13 @@ def main():
                                         "note": "maze_step(n=1) writing obs: one launch per step"}
         # observation variants (occluded view, type/colour/state bytes)
         env.set_obs_mode(1, 1)
-        ms, mn = time_calls(torch, lambda: env.step(actions, reward, done, obs), 20, warmup=5)
+        ms, mn = time_calls(torch, lambda: env.step(actions, reward, done, obs), 30, warmup=30)
         rows["student_rollout_c3_occluded_typed_obs"] = {
             "ms": ms, "env-steps/s": N * T / ms * 1e3, "GB/s": 81.0 * N * T / ms / 1e6,
             "note": "maze_set_obs_mode(1, 1): occlusion in the records stage, typed bytes in the store stage"}
         for mode, name in (((1, 0), "typed_obs"), ((0, 1), "occluded_obs")):
             env.set_obs_mode(*mode)
-            ms, mn = time_calls(torch, lambda: env.step(actions, reward, done, obs), 20, warmup=5)
+            ms, mn = time_calls(torch, lambda: env.step(actions, reward, done, obs), 30, warmup=30)
             rows["student_rollout_c3_" + name] = {
                 "ms": ms, "env-steps/s": N * T / ms * 1e3, "GB/s": 81.0 * N * T / ms / 1e6,
                 "note": "maze_set_obs_mode(%d, %d)" % mode}
@@ -371,7 +371,7 @@ def main():
         def editor_pass():
             ed.reset(edir)
             ed.step(eact, eobs, et, edn)
-        ms, mn = time_calls(torch, editor_pass, 20, warmup=5)
+        ms, mn = time_calls(torch, editor_pass, 30, warmup=30)
         ebytes = 516.0 * ew.N * ew.T   # 4 action + 507 obs + 4 t + 1 done
         rows["editor_c4"] = {"ms": ms, "editor-steps/s": ew.N * ew.T / ms * 1e3,
                              "GB/s": ebytes / ms / 1e6, "frac_of_hbm_peak": ebytes / ms / 1e6 / HBM_PEAK_GBS}
@@ -403,7 +403,7 @@ def main():
         r5 = torch.empty((w5.T, w5.N), dtype=torch.float32, device=dev)
         d5 = torch.empty((w5.T, w5.N), dtype=torch.uint8, device=dev)
         o5 = torch.empty((w5.T, w5.N, 7, 7, 3), dtype=torch.int8, device=dev)
-        ms, mn = time_calls(torch, lambda: env5.step(a5, r5, d5, o5), 20, warmup=5)
+        ms, mn = time_calls(torch, lambda: env5.step(a5, r5, d5, o5), 30, warmup=30)
         b5 = 153.0 * w5.N * w5.T
         rows["student_rollout_c5"] = {"ms": ms, "env-steps/s": w5.N * w5.T / ms * 1e3,
                                       "GB/s": b5 / ms / 1e6, "frac_of_hbm_peak": b5 / ms / 1e6 / HBM_PEAK_GBS}

@@ -27,6 +27,12 @@
 // Only the dynamics wave carries a dependency from step to step, so the time per
 // step is that wave's short chain; the store waves never load from global memory
 // and the dynamics wave touches it once every 16 steps (actions, staged in LDS).
+//
+// Large launches are bound by how the memory system takes the observation stream, and
+// for them the store stage does two more things (maze_store_device.h): lines that one
+// store instruction writes whole go out as streaming stores, and the store waves keep
+// a clock schedule just under the write rate the memory sustains (StorePacer) instead
+// of storing as fast as the queues accept.
 #pragma once
 
 #include "maze_internal.h"
@@ -112,8 +118,8 @@ struct Lds {
     __host__ static size_t bytes_without_grids() { return 4 * (size_t)GRID0; }
 };
 
-// The K wall words of an env's view (row 0 farthest).  From LDS or, for grids too
-// large to stage, from the packed grids in global memory.
+// The K wall words of an env's view (row 0 farthest): from the grids staged in LDS (the
+// rollout) or from the packed grids in global memory (the single-step kernel).
 template <int K, typename Word, bool GRID_LDS>
 __device__ __forceinline__ void load_view_rows(const uint32_t *lds_env, const Word *glob_env, int SP,
                                                int d, int yd, Word (&rows)[K])
