@@ -151,7 +151,7 @@ __global__ __launch_bounds__(64 * NWAVES) void k_editor_tiled(
                 const uintptr_t piece_lo = chunk_lo + 16 * (size_t)(m - lane);
                 const uintptr_t piece_hi = piece_lo + 1024 < chunk_hi ? piece_lo + 1024 : chunk_hi;
                 if (steady && valid >= 16 && line >= piece_lo && line + 128 <= piece_hi)
-                    store16_stream(out_block + 16 * (size_t)m, v);
+                    store16_stream(out_block, 16u * (uint32_t)m, v);
                 else if (valid >= 16) store16(out_block + 16 * (size_t)m, v);
                 else store_bytes(out_block + 16 * (size_t)m, v, valid);
                 bs += adv_r;

@@ -17,21 +17,33 @@ __device__ __forceinline__ uint32_t expand_nibble(uint32_t nib)
 __device__ __forceinline__ void store16(int8_t *dst, const uint4 &v) { __builtin_memcpy(dst, &v, 16); }
 
 // The same store for output that is a pure stream -- nothing on the chip reads it back -- and
-// whose 128-byte line is written completely by this workgroup: non-temporal, system scope
-// (written through, nothing of it kept).  Each of the 8 XCDs has an L2 of its own, so a
-// kernel's output has to leave them before the next kernel starts; without the hint the
-// rollout's output collects there as dirty lines and is written back when the kernel ends.
-// Measured on config 3, 256-step rollout, launches back to back: plain stores 133.5 us,
-// nt 127.1, sc0 sc1 nt 125.2, sc0 sc1 alone 134.3 (the compiler's non-temporal store gives nt
-// alone, hence the instruction written out).  Lines that two workgroups share must not carry
-// the hint: they would leave the L2 half written and be merged in memory (config 5, whose
-// 4704-byte chunks end inside lines: 129 -> 152 us with nt on every store; the same on the
-// rollout's 4-byte reward and 1-byte done stores: 127 -> 135 us).
+// whose 128-byte line is written completely by one store instruction of a wave:
+// non-temporal, system scope (written through, nothing of it kept).  Each of the 8 XCDs has
+// an L2 of its own, so a kernel's output has to leave them before the next kernel starts;
+// without the hint the rollout's output collects there as dirty lines and is written back
+// when the kernel ends.  Measured on config 3, 256-step rollout, launches back to back: plain
+// stores 133.5 us, nt 127.1, sc0 sc1 nt 125.2, sc0 sc1 alone 134.3.  Lines that two store
+// instructions share must not carry the hint: they would leave the L2 half written and be
+// merged in memory (config 5, whose 4704-byte chunks end inside lines: 129 -> 152 us with nt
+// on every store; the same on the rollout's 4-byte reward and 1-byte done stores: 127 -> 135).
+//
+// base: the same for every lane of the wave (a workgroup's block of a step); offset: this
+// lane's byte offset in it, at any alignment.  A raw buffer store whose descriptor spans
+// [base, base + 2^32) and whose cache bits are an argument (buffer_store_dwordx4 ... offen
+// sc0 nt sc1).  It is a builtin, not inline assembly, on purpose: the compiler places the
+// wait states a 16-byte store needs before its data registers may be overwritten only for
+// instructions it knows, and a store written as assembly text had later lanes' data
+// overwritten in flight.
 typedef uint32_t maze_u4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void store16_stream(int8_t *dst, const uint4 &v)
+__device__ __forceinline__ void store16_stream(int8_t *base, uint32_t offset, const uint4 &v)
 {
+    const uint64_t b = (uint64_t)(uintptr_t)base;
+    const uint64_t uniform = ((uint64_t)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+                             (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(uintptr_t)uniform, 0, -1, 0x00020000);
     const maze_u4 t = {v.x, v.y, v.z, v.w};
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(dst), "v"(t) : "memory");
+    __builtin_amdgcn_raw_buffer_store_b128(t, rsrc, (int)offset, 0, 0x13);      // sc0 | nt | sc1
 }
 __device__ __forceinline__ uint4 load16(const int8_t *src)
 {

@@ -288,11 +288,12 @@ __device__ __forceinline__ Window make_window(int lane, int round)
     return w;
 }
 
-__device__ __forceinline__ void store_window(int8_t *dst, const uint4 &a, const Window &w)
+// block: the workgroup's output block of this step (the same for all lanes)
+__device__ __forceinline__ void store_window(int8_t *block, const uint4 &a, const Window &w)
 {
-    if (w.stream) store16_stream(dst, a);
-    else if (w.valid >= 16) store16(dst, a);
-    else store_bytes(dst, a, w.valid);
+    if (w.stream) store16_stream(block, w.out, a);
+    else if (w.valid >= 16) store16(block + w.out, a);
+    else store_bytes(block + w.out, a, w.valid);
 }
 
 // Expand one 16-bit window of the concatenated streams into 16 output bytes.
@@ -305,7 +306,7 @@ __device__ __forceinline__ void consume_window(const uint32_t *recs, const Windo
     uint4 a;
     a.x = expand_nibble(bits & 15);          a.y = expand_nibble((bits >> 4) & 15);
     a.z = expand_nibble((bits >> 8) & 15);   a.w = expand_nibble((bits >> 12) & 15);
-    store_window(block + w.out, a, w);
+    store_window(block, a, w);
 }
 
 // The same window written in the (type, colour, state) encoding.  The one-hot stream holds,
@@ -335,7 +336,7 @@ __device__ __forceinline__ void consume_window_typed(const uint32_t *recs, const
                  (expand_nibble((p2 >> sh) & 15) << 2) | (expand_nibble((p3 >> sh) & 15) << 3);
     }
     const uint4 a = make_uint4(out[0], out[1], out[2], out[3]);
-    store_window(block + w.out, a, w);
+    store_window(block, a, w);
 }
 
 // The typed bytes of one output dword depend on the phase of its first byte (which of type,
@@ -373,7 +374,7 @@ __device__ __forceinline__ void consume_window_typed(const uint32_t *recs, const
     a.y = typed_table[w.typed_row[1] + ((from_below >> 4) & 127)];
     a.z = typed_table[w.typed_row[2] + ((from_below >> 8) & 127)];
     a.w = typed_table[w.typed_row[3] + ((from_below >> 12) & 127)];
-    store_window(block + w.out, a, w);
+    store_window(block, a, w);
 }
 
 // Which cells of the view are seen (occluded view): rows are settled from the agent's row

@@ -22,6 +22,8 @@ namespace {
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 constexpr int STORE_WAVES = 10, STEPS_PER_BARRIER = 8;
 
+// The data registers of every store here hold one constant that is never rewritten, so the
+// assembly form needs no more than its own wait states after it.
 template <int NT>
 __device__ __forceinline__ void put(char *p, u4 v)
 {

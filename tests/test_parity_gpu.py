@@ -273,6 +273,25 @@ def test_unaligned_buffers():
     assert_state_equal(env, o)
 
 
+@pytest.mark.parametrize("N,T", [(16384, 9), (32768, 17)])
+def test_unaligned_buffers_with_large_workgroups(N, T):
+    """The same with 64 and 128 envs per workgroup, whose whole-line windows go out as streaming
+    stores: here every 16-byte piece of them sits at an address 3 bytes off a multiple of 16."""
+    w = wl.student_random(f"unaligned-{N}", 67, N=N, T=T, n_walls=50, max_steps=30)
+    env, o = gpu_student(w), cpu_student(w)
+    k = w.view
+    big_obs = torch.empty(T * N * k * k * 3 + 64, dtype=torch.int8, device=DEV)
+    obs = big_obs[3:3 + T * N * k * k * 3].view(T, N, k, k, 3)
+    big_act = torch.empty(T * N + 64, dtype=torch.int8, device=DEV)
+    acts = big_act[5:5 + T * N].view(T, N)
+    acts.copy_(to_gpu(w.actions))
+    big_obs.fill_(77)
+    r, d, obs = env.step(acts, obs=obs)
+    assert_rollout_equal((r, d, obs), o.step(w.actions, T), "unaligned, large workgroups")
+    assert_state_equal(env, o)
+    assert bool((big_obs[:3] == 77).all()) and bool((big_obs[3 + T * N * k * k * 3:] == 77).all())
+
+
 def test_reset_to_new_levels_replaces_everything():
     w1 = wl.student_random("first", 1, N=500, T=50, n_walls=50)
     w2 = wl.student_random("second", 2, N=500, T=50, n_walls=10)
