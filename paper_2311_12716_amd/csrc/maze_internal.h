@@ -69,13 +69,19 @@ static inline int maze_same_device(int ctx_device)
         if (rc__ != MAZE_OK) return rc__;               \
     } while (0)
 
-// The write rate the store waves of a large launch are paced to (see StorePacer).  Config 3
-// (256 workgroups x 9600 B per step), 256-step rollout, launches back to back: unpaced 125 us;
-// paced to 6700 GB/s 113.1, 6900: 110.2, 7100: 107.5, 7300: 104.8 -- but past a shape-dependent
-// point the stream falls back to the unpaced rate (view 7 on 20 x 20 grids: 115 us at 6700 and
-// 6900, 124 at 7100, 126 unpaced; typed observation and 65536 envs: fine at 7100, back at
-// 7300), so the constant stays below the lowest such point.
-#define MAZE_PACED_GBS 6900.0
+// The write rate the store waves of a large launch are paced to (see StorePacer).  Rollout
+// launches back to back, us per launch, by rate in GB/s (unpaced: config 3 takes 125):
+//                                            6900   7000   7100   7200   7300   7500
+//   config 3 (256 workgroups x 9600 B/step)  110.7  109.2  108.1  106.6  105.4  103.5
+//   65536 envs x 128 steps                   119.1  117.3  117.4  117.8  121.7  125.0
+//   view 7 on 20 x 20 grids, 128 steps       113.4  112.8  112.2  112.3  112.7  119.3
+//   config 5                                 104.7  103.5  102.5  101.8  101.9  101.7
+//   config 3, typed observation              111.8  116.8  118.1  118.5  118.6  117.0
+// Past a shape-dependent point the stream falls back towards the unpaced rate, so each constant
+// stays below the lowest such point of its kind of launch; the typed observation's store waves
+// look every byte up in a table and have less time to spare per block.
+#define MAZE_PACED_GBS 7200.0
+#define MAZE_PACED_GBS_TYPED 6900.0
 // The editor's stream (64896 B per workgroup and step at 13 x 13) turns earlier: config 4 takes
 // 163 us unpaced and at 6900 or 7200, 142 at 6700 (but 163 for the first dozens of launches),
 // 146.5 at 6400, 155 at 6000 (there and below the schedule alone sets the time).

@@ -1020,8 +1020,8 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
     const dim3 grid(groups), block(64 * V::WAVES);
     // Pacing of the store waves (see the kernel's stores stage): the time one step of the launch
     // should take if the workgroups resident at once write their chunks, reward and done at
-    // MAZE_PACED_GBS.  Paced are launches that write more than twice
-    // what the 256 MB memory-side cache holds (a smaller output is absorbed there and leaves
+    // MAZE_PACED_GBS (MAZE_PACED_GBS_TYPED for the typed observation).  Paced are launches that
+    // write more than twice what the 256 MB memory-side cache holds (a smaller output is absorbed there and leaves
     // the chip later: 16384 envs x 256 steps take 52 us unpaced, 57 paced) and do not build the
     // occluded view (there the records stage sets the pace: 117 us unpaced, 120 paced).
     const double out_bytes = (double)(n_end - n_begin) * n_steps * (V::SB + 5);
@@ -1029,7 +1029,8 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
     if (!p.obs_occlusion) {
         const size_t per_cu = max((size_t)1, min(lds_budget(ctx) / shmem, (size_t)(32 / V::WAVES)));
         const double resident = (double)min((long long)groups, (long long)ctx->cus * (long long)per_cu);
-        pace_fp = maze_pace_fp(ctx->clock_khz, resident * EPW * (V::SB + 6), out_bytes, MAZE_PACED_GBS);
+        pace_fp = maze_pace_fp(ctx->clock_khz, resident * EPW * (V::SB + 6), out_bytes,
+                               p.obs_encoding ? MAZE_PACED_GBS_TYPED : MAZE_PACED_GBS);
     }
     // Workgroups of 32 envs: launches too large for the memory-side cache go to the flavour with
     // streaming stores and pacing, the others (bound by latency: 4096 envs x 256 steps take 39.6 us
