@@ -54,7 +54,23 @@ def event_ms(pairs):
     return [a.elapsed_time(b) for a, b in pairs]
 
 
-def time_calls(torch, fn, iters, warmup=2):
+def spin_up(torch, fn, ms):
+    """Run fn untimed for about `ms` milliseconds of wall time; returns the number of calls.
+    After an idle spell the device runs its first ~10 ms of load 5-10 % slower and unevenly
+    (clock and power management settling: the editor kernel takes 145-170 us per launch for its
+    first 60 launches and 145.1 from then on), which would otherwise be most of a 20-step run."""
+    n = 0
+    t_end = time.perf_counter() + ms * 1e-3
+    while ms > 0 and time.perf_counter() < t_end:
+        for _ in range(8):
+            fn()
+        torch.cuda.synchronize()
+        n += 8
+    return n
+
+
+def time_calls(torch, fn, iters, warmup=2, settle_ms=20.0):
+    spin_up(torch, fn, settle_ms)
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -119,6 +135,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--spin-up-ms", type=float, default=50.0,
+                    help="run the pass untimed for this long before the W warm-up steps, so that the "
+                         "device's clocks have settled when the timed region starts (0: off)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row measurements")
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 per-cell kernels")
@@ -175,6 +194,7 @@ def main():
             b.record()
             kernel_events.append((a, b))
 
+    n_spin = spin_up(torch, lambda: one_step(False), args.spin_up_ms)
     for _ in range(args.warmup):
         one_step(False)
     torch.cuda.synchronize()
@@ -205,6 +225,9 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "spin_up": {"ms": args.spin_up_ms, "untimed_passes": n_spin,
+                    "what": "the same pass run untimed before the W warm-up steps until the device's "
+                            "clocks have settled after idling; --spin-up-ms 0 turns it off"},
         "ms_per_step": elapsed / args.steps * 1e3,
         "higher_is_better": True,
         "scaling": "weak",
