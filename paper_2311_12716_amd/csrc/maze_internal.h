@@ -82,9 +82,10 @@ static inline int maze_same_device(int ctx_device)
 // look every byte up in a table and have less time to spare per block.
 #define MAZE_PACED_GBS 7200.0
 #define MAZE_PACED_GBS_TYPED 6900.0
-// The editor's stream (64896 B per workgroup and step at 13 x 13) turns earlier: config 4 takes
-// 163 us unpaced and at 6900 or 7200, 142 at 6700 (but 163 for the first dozens of launches),
-// 146.5 at 6400, 155 at 6000 (there and below the schedule alone sets the time).
+// The editor's stream (64896 B per workgroup and step at 13 x 13) turns earlier and sharply:
+// config 4, us per reset + step after a long warm-up: 163 unpaced and at 6900 or 7200, 158 at
+// 6700, 143.4 at 6550, 146.5 at 6400, 150.9 at 6200 (there and below the schedule alone sets
+// the time); the constant keeps a margin to the turn.
 #define MAZE_PACED_GBS_EDITOR 6400.0
 
 // Time one step of a launch should take, in ticks of the device's constant-rate clock with 8
