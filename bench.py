@@ -117,6 +117,7 @@ def store_patterns(torch, env, actions, reward, done, obs, N, T, k):
         ms = (time.perf_counter() - t0) / iters * 1e3
         return {"ms": ms, "GB/s": obs_bytes / ms / 1e6}
 
+    spin_up(torch, lambda: obs.fill_(1), 30.0)       # settled clocks before the first pattern
     table = {"geometry": f"{groups} workgroups x {slab // groups} B per step, {T} steps, {obs_bytes} B",
              "torch_fill": timed(lambda: obs.fill_(1)),
              "probe_fill_4KB_blocks": timed(probe(0)),
