@@ -106,7 +106,7 @@ int maze_step(maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d_rewa
 /* How a rollout (maze_step with d_obs and n_steps > 1) of these static parameters would be
  * launched on a device with `cus` compute units and lds_per_cu bytes of LDS per unit (what
  * maze_create reads from the device properties): envs per workgroup of the main launch (128,
- * 64 or 32; 0 if the view size is not one the store-layout kernels take, the one-lane-per-env
+ * 64, 32 or 16; 0 if the view size is not one the store-layout kernels take, the one-lane-per-env
  * kernel then runs) and the LDS bytes such a workgroup needs.  Host arithmetic only, no GPU
  * is touched.  MAZE_EHIP if even 32 envs per workgroup do not fit -- the error maze_step
  * returns on such a device; argument errors as for maze_create and maze_set_obs_mode.     */

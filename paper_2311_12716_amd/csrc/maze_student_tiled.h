@@ -4,7 +4,8 @@
 // A workgroup owns EPW consecutive envs for the whole rollout: 128 when the batch is
 // large enough to fill the GPU that way (128 * 3k^2 bytes per step is a whole number
 // of 128-byte lines, so no line of the output is shared between workgroups), 64 or
-// 32 for smaller batches or grids whose LDS copy would not fit.  Per step one lane
+// 32 for smaller batches or grids whose LDS copy would not fit, 16 when even those
+// would leave compute units without a workgroup.  Per step one lane
 // per env advances the env (state in registers, wall rows from LDS) and its
 // observation is built as a BIT STREAM -- bit i of the stream is byte i of the env's
 // k*k*3 observation, which is 0 or 1 -- and left in LDS.  The EPW streams,
@@ -16,9 +17,11 @@
 //
 // The per-step work is a four-stage pipeline over the waves of the workgroup,
 // advanced by one barrier per block of SPB steps:
-//   first  ("dynamics") block b  : action, move (one wall word: the row ahead),
-//                                  goal/done/reset; publish pose, goal offset, outcome
-//   next   ("views")    block b-1: K wall rows of the view -> K x K view bits
+//   first  ("dynamics") block b  : action, move (one wall word: the row of the cell ahead),
+//                                  goal/done/reset, in the grid's own coordinates; publish
+//                                  position, forward vector, outcome
+//   next   ("views")    block b-1: position and goal offset in the heading's frame; K wall
+//                                  rows of that frame -> K x K view bits
 //   next   ("records")  block b-2: view bits -> stream record (row lookup table),
 //                                  goal cell patched in; store reward and done
 //   rest   ("stores")   block b-3: expand records to bytes, store obs
@@ -102,7 +105,7 @@ struct Lds {
     static constexpr int VIS_N = MODE == 1 ? (1 << (2 * K)) / 2 : 0;
     static constexpr int ACT = VIS + VIS_N;                        // [2][ACT_BLOCK][EPW] action bytes
     static constexpr int ACT_ROW = EPW;                            // bytes per step
-    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][3][EPW] position, goal offset, outcome + heading
+    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][3][EPW] position, forward vector, outcome
     static constexpr int ST_SIZE = 3 * EPW;
     static constexpr int VW = ST + 2 * SPB * ST_SIZE;              // [2][SPB][WV+2][EPW] view bits, goal, out
     static constexpr int VW_SIZE = (V::WV + 2) * EPW;
@@ -507,111 +510,114 @@ __device__ __forceinline__ void stage_grids(const StudentDev &p, uint32_t *lds, 
 }
 
 // ------------------------------------------------------------------ rollout
-// Wall word of row `row` of heading frame `dir` of one env.
-template <typename Word>
-__device__ __forceinline__ Word wall_row(const uint32_t *lds_env, int SP, int dir, int row)
-{
-    const int r = (int)__umul24((unsigned)dir, (unsigned)SP) + row;
-    if (sizeof(Word) == 4) return (Word)lds_env[r];
-    return (Word)(((uint64_t)lds_env[2 * r + 1] << 32) | lds_env[2 * r]);
-}
-
 // Two 16-bit numbers in one register; arithmetic on them compiles to packed instructions
 // (one multiply-add turns a pair, the swap of its halves is an operand modifier).
 typedef short pair16 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ pair16 as_pair(uint32_t v) { return __builtin_bit_cast(pair16, v); }
 __device__ __forceinline__ uint32_t as_word(pair16 v) { return __builtin_bit_cast(uint32_t, v); }
 
-// Per-lane state of the dynamics stage (one env per lane).
-template <typename Word>
+// Per-lane state of the dynamics stage (one env per lane).  The stage works in the padded
+// grid's own coordinates -- a move is one add, the wall test one word of the unrotated grid
+// -- and leaves the change to the heading's frame, which only the view needs, to the views
+// stage, where nothing waits for the previous step.
 struct DynState {
-    uint32_t pos;             // Xd | Yd << 16: position in the frame of the heading
-    uint32_t goal;            // goal relative to the agent: cells ahead | cells to the right << 16
-    int d;                    // heading
+    uint32_t pos;             // X | Y << 16, padded-grid coordinates
+    uint32_t dv;              // one step forward, (dx, dy) as two 16-bit numbers
     uint32_t t;               // steps since the episode began
-    // The word of the row just ahead of the agent (row yd-1 of its frame) decides whether a
-    // forward step is blocked.  It is fetched one step early: as soon as the action is known
-    // the row ahead of the pose the action leads to -- taking a forward step as successful --
-    // is requested (`spec`), and the choice between that word, the previous one (the forward
-    // step hit a wall: pose unchanged) and the start pose's word (episode ended) is made at
-    // the top of the next step, when the LDS read has long returned.
-    Word ahead_keep, spec;
-    bool use_start, use_keep;
     uint32_t act_off, a_next; // action ring cursor (bytes) and the next step's action
 };
 
-template <typename Word>
 struct DynConst {
-    uint32_t start_pos, start_goal;    // start position and the goal's offset from it, packed as above
-    int sd;                            // start heading
-    Word ahead_start;                  // row ahead of the start pose
+    uint32_t start_pos, start_dv;      // the level's start pose, packed as above
+    uint32_t goal_pos;                 // the goal cell, packed like pos
     uint32_t tmax;
-    int HPm1, WPm1, SP;
-    const uint32_t *lds_env;           // this env's staged grids
+    const uint32_t *rows;              // this env's unrotated grid (frame 3) in LDS
     const uint8_t *act_lds;            // this env's column of the action ring
     uint32_t act_mask, act_row;        // ring size - 1 and row pitch, bytes
 };
 
-// Dynamics stage -> views stage, three dwords per env and step:
-//   position (Xd | Yd << 16), goal offset (ahead | right << 16),
-//   outcome: step count if the goal was reached (else 0) | heading << 29 | done << 31.
-constexpr uint32_t ST_HEADING_SHIFT = 29;
-constexpr uint32_t ST_OUTCOME_MASK = ~(3u << ST_HEADING_SHIFT);
+// Word of row `y` of an env's unrotated grid.
+template <typename Word>
+__device__ __forceinline__ Word grid_row(const uint32_t *rows, uint32_t y)
+{
+    if (sizeof(Word) == 4) return (Word)rows[y];
+    return (Word)(((uint64_t)rows[2 * y + 1] << 32) | rows[2 * y]);
+}
 
-// One env step of the dynamics stage; publishes position, goal offset and outcome to st[].
-// Position and goal offset are pairs of 16-bit numbers: a right turn maps (Xd,Yd) to
-// (Yd, bits-1-Xd) and the goal vector (ahead, right) to (right, -ahead), a left turn to
-// (rows-1-Yd, Xd) and (-right, ahead) -- each one packed multiply-add of the swapped pair.
-template <typename Word, int EPW, bool SQUARE>
-__device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word> &c, uint32_t *st)
+// Forward vectors of the headings 0..3 (+x, +y, -x, -y) as (dx, dy) pairs of 16-bit numbers.
+__device__ __forceinline__ uint32_t heading_vector(int d)
+{
+    return d == 0 ? 0x00000001u : d == 1 ? 0x00010000u : d == 2 ? 0x0000FFFFu : 0xFFFF0000u;
+}
+
+// Dynamics stage -> views stage, three dwords per env and step:
+//   position (X | Y << 16), forward vector (dx | dy << 16),
+//   outcome: step count if the goal was reached (else 0) | done << 31.
+// One env step of the dynamics stage.  The row of the cell ahead is requested first, before
+// the action is looked at (a turn does not use it); a right turn maps the forward vector
+// (dx, dy) to (-dy, dx), a left turn to (dy, -dx): one packed multiply of the swapped pair.
+// (Fetching that row a step early, for the pose the action leads to, and the action two steps
+// early, as an earlier form of this stage did, gains nothing here: a step is ~31 instructions
+// of which most wait for the one before, and a dependent instruction issues 9 cycles after its
+// producer on this chip, an LDS read returns after 60.)
+template <typename Word, int EPW>
+__device__ __forceinline__ void dyn_step(DynState &s, const DynConst &c, uint32_t *st)
 {
     const uint32_t a = s.a_next;
     s.act_off = (s.act_off + c.act_row) & c.act_mask;
     s.a_next = c.act_lds[s.act_off];        // next step's action (staged >= half a block ago)
+    const pair16 dv = as_pair(s.dv), swapped = dv.yx;
+    const uint32_t ahead = as_word(as_pair(s.pos) + dv);
+    const Word row = grid_row<Word>(c.rows, ahead >> 16);
     const bool tl = (a == 0), tr = (a == 1), f2 = (a == 2);
-    int rows_m1 = c.WPm1, bits_m1 = c.WPm1;
-    if (!SQUARE) {
-        const bool odd = s.d & 1;
-        rows_m1 = odd ? c.HPm1 : c.WPm1;
-        bits_m1 = odd ? c.WPm1 : c.HPm1;
-    }
-    // position the action leads to if a forward step succeeds; request its row ahead
-    const pair16 pos = as_pair(s.pos), swapped = pos.yx;
-    const pair16 right = swapped * (pair16){1, -1} + (pair16){0, (short)bits_m1};
-    const pair16 left = swapped * (pair16){-1, 1} + (pair16){(short)rows_m1, 0};
-    const pair16 ahead_pos = pos - (pair16){0, (short)(f2 ? 1 : 0)};
-    pair16 next = tr ? right : ahead_pos;
-    next = tl ? left : next;
-    const int nd = (s.d + (tl ? 3 : 0) + (tr ? 1 : 0)) & 3;
-    const Word ahead = s.use_start ? c.ahead_start : (s.use_keep ? s.ahead_keep : s.spec);
-    s.spec = wall_row<Word>(c.lds_env, c.SP, nd, (int)(as_word(next) >> 16) - 1);
-    // the wall test for the current pose
-    const int xd = (int)(s.pos & 0xFFFFu);
-    const int blocked = sizeof(Word) == 4 ? (int)__builtin_amdgcn_ubfe((uint32_t)ahead, xd, 1)
-                                          : (int)((ahead >> xd) & 1);
-    const bool stay = f2 & (blocked != 0);          // forward into a wall: nothing moves
-    const int fw = f2 ? (blocked ^ 1) : 0;
-    const uint32_t moved = stay ? s.pos : as_word(next);
+    const uint32_t right = as_word(swapped * (pair16){-1, 1}), left = as_word(swapped * (pair16){1, -1});
+    uint32_t ndv = tr ? right : s.dv;
+    ndv = tl ? left : ndv;
+    // (a bit-field extract takes its position from the low 5 bits: the X half of `ahead`)
+    const uint32_t blocked = sizeof(Word) == 4 ? __builtin_amdgcn_ubfe((uint32_t)row, ahead, 1)
+                                               : (uint32_t)(row >> (ahead & 63u)) & 1u;
+    const bool go = f2 & (blocked == 0);
+    const uint32_t moved = go ? ahead : s.pos;
     const uint32_t t1 = s.t + 1;
-    const pair16 goal = as_pair(s.goal), gswapped = goal.yx;
-    // (all three alternatives first, then plain selects: a conditional expression with work in
-    // its arms compiles to a branch)
-    const pair16 goal_right = gswapped * (pair16){1, -1}, goal_left = gswapped * (pair16){-1, 1};
-    const pair16 goal_ahead = goal - (pair16){(short)fw, 0};
-    pair16 ngoal = tr ? goal_right : goal_ahead;
-    ngoal = tl ? goal_left : ngoal;
-    const bool reached = as_word(ngoal) == 0;
+    const bool reached = moved == c.goal_pos;
     const bool fin = reached | (t1 >= c.tmax);
     s.pos = fin ? c.start_pos : moved;
-    s.goal = fin ? c.start_goal : as_word(ngoal);
-    s.d = fin ? c.sd : nd;
+    s.dv = fin ? c.start_dv : ndv;
     s.t = fin ? 0u : t1;
-    s.use_start = fin;
-    s.use_keep = stay;
-    s.ahead_keep = ahead;
     st[0] = s.pos;
-    st[EPW] = s.goal;
-    st[2 * EPW] = (reached ? t1 : 0u) | ((uint32_t)s.d << ST_HEADING_SHIFT) | (fin ? 0x80000000u : 0u);
+    st[EPW] = s.dv;
+    st[2 * EPW] = (reached ? t1 : 0u) | (fin ? 0x80000000u : 0u);
+}
+
+// What the views stage makes of a published pose: the heading, the position in the heading's
+// frame (Xd | Yd << 16) and the goal's offset in that frame (cells ahead | cells to the
+// right << 16).  g0..g3: the goal cell in each frame, packed like the position.
+// (All alternatives first, then plain selects on values: a conditional expression with work
+// in its arms compiles to a branch, an array indexed by the heading to a stack slot.)
+struct FramePose { int d; uint32_t pos, goal; };
+__device__ __forceinline__ FramePose to_frame(uint32_t pos, uint32_t dv, uint32_t g0, uint32_t g1, uint32_t g2,
+                                              uint32_t g3, int HPm1, int WPm1)
+{
+    const bool h0 = dv == 0x00000001u, h1 = dv == 0x00010000u, h2 = dv == 0x0000FFFFu;
+    const pair16 p = as_pair(pos), swapped = p.yx;
+    // frame 0: (Y, WP-1-X); frame 1: (WP-1-X, HP-1-Y); frame 2: (HP-1-Y, X); frame 3: (X, Y)
+    const uint32_t f0 = as_word(swapped * (pair16){1, -1} + (pair16){0, (short)WPm1});
+    const uint32_t f1 = as_word((pair16){(short)WPm1, (short)HPm1} - p);
+    const uint32_t f2 = as_word(swapped * (pair16){-1, 1} + (pair16){(short)HPm1, 0});
+    FramePose r;
+    int d = h2 ? 2 : 3;
+    d = h1 ? 1 : d;
+    r.d = h0 ? 0 : d;
+    uint32_t fp = h2 ? f2 : pos;
+    fp = h1 ? f1 : fp;
+    r.pos = h0 ? f0 : fp;
+    uint32_t g = h2 ? g2 : g3;
+    g = h1 ? g1 : g;
+    g = h0 ? g0 : g;
+    // (gxd - xd, gyd - yd) -> ahead = yd - gyd, right = gxd - xd
+    const pair16 diff = as_pair(g) - as_pair(r.pos);
+    r.goal = as_word(diff.yx * (pair16){-1, 1});
+    return r;
 }
 
 // Each role runs its own loop over blocks of SPB steps; every wave passes exactly
@@ -652,7 +658,7 @@ __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word>
 // BIG (workgroups of 32 envs only; the larger ones always have it): the flavour for launches whose
 // output is too large for the memory-side cache to absorb, with streaming stores and paced
 // store waves.  Small launches are bound by latency and keep the plain store stage.
-template <int K, typename Word, int EPW, bool SQUARE, int MODE = 0, bool PARTIAL = false, bool BIG = false>
+template <int K, typename Word, int EPW, int MODE = 0, bool PARTIAL = false, bool BIG = false>
 __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     StudentDev p, int n_begin, int n_end, const int8_t *__restrict__ actions, int n_steps,
     float *__restrict__ reward, uint8_t *__restrict__ done, int8_t *__restrict__ obs, uint32_t pace_fp)
@@ -662,11 +668,12 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     constexpr int NT = 64 * V::WAVES;
     constexpr bool LARGE = EPW >= 64 || BIG;
     constexpr int ACT_BLOCK = V::ACT_BLOCK;
-    constexpr int UGV = step_group(K * WordOps<Word>::DW + 3, 40);   // views: wall rows + state
+    constexpr int UGV = step_group(K * WordOps<Word>::DW + 4, 40);   // views: wall rows + pose in frame + outcome
     // records: table words + view (+ the seen cells and the chain state of the occluded view)
     constexpr int UGR = step_group(K + V::WV + 2 + (MODE == 1 ? V::WV + 2 : 0), 48);
-    // steps per pass of a views / records wave: two when the wave would be half empty
-    constexpr int UPL = (V::LA == 32 && SPB % 2 == 0) ? 2 : 1;
+    // steps per pass of a views / records wave: the wave's 64 lanes take 64 / LA steps of a
+    // block at once when the workgroup has fewer than 64 envs
+    constexpr int UPL = SPB % (64 / V::LA) == 0 ? 64 / V::LA : 1;
     constexpr int UGVP = UGV > SPB / UPL ? SPB / UPL : UGV;
     constexpr int UGRP = UGR > SPB / UPL ? SPB / UPL : UGR;
     extern __shared__ uint32_t lds[];
@@ -692,24 +699,22 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         const int e = wave * 64 + (active ? lane : 0);   // env within the workgroup
         const int n = env0 + e;
         const int last = n_steps - 1;
-        DynState<Word> s;
-        DynConst<Word> c;
-        const uint32_t pose = p.pose[n], start = p.start[n];
-        const int xd0 = pose & 255, yd0 = (pose >> 8) & 255, sxd = start & 255, syd = (start >> 8) & 255;
-        s.pos = (uint32_t)xd0 | ((uint32_t)yd0 << 16);
-        s.d = (pose >> 16) & 3;
+        DynState s;
+        DynConst c;
+        // poses are kept in the frame of their heading between launches (pose = Xd | Yd << 8 |
+        // d << 16); frame 3 is the padded grid itself
+        const uint32_t pose = p.pose[n], start = p.start[n], goal3 = p.goalrot[4 * (size_t)n + 3];
+        int X, Y;
+        frame_to_padded(p, (pose >> 16) & 3, pose & 255, (pose >> 8) & 255, X, Y);
+        s.pos = (uint32_t)X | ((uint32_t)Y << 16);
+        s.dv = heading_vector((pose >> 16) & 3);
         s.t = p.tcount[n];
-        c.start_pos = (uint32_t)sxd | ((uint32_t)syd << 16);
-        c.sd = (start >> 16) & 3;
-        // goal relative to the agent in the agent's own frame; turning rotates this vector,
-        // moving forward shortens its first component
-        const uint32_t g_now = p.goalrot[4 * (size_t)n + s.d], g_start = p.goalrot[4 * (size_t)n + c.sd];
-        s.goal = (uint32_t)((yd0 - (int)(g_now >> 8)) & 0xFFFF) | ((uint32_t)((int)(g_now & 255) - xd0) << 16);
-        c.start_goal = (uint32_t)((syd - (int)(g_start >> 8)) & 0xFFFF) |
-                       ((uint32_t)((int)(g_start & 255) - sxd) << 16);
+        frame_to_padded(p, (start >> 16) & 3, start & 255, (start >> 8) & 255, X, Y);
+        c.start_pos = (uint32_t)X | ((uint32_t)Y << 16);
+        c.start_dv = heading_vector((start >> 16) & 3);
+        c.goal_pos = (goal3 & 255u) | ((goal3 >> 8) << 16);
         c.tmax = (uint32_t)p.max_steps;
-        c.HPm1 = p.HP - 1; c.WPm1 = p.WP - 1; c.SP = SP;
-        c.lds_env = lds + L::GRID0 + e * L::grid_stride(SP);
+        c.rows = lds + L::GRID0 + e * L::grid_stride(SP) + 3 * SP * WordOps<Word>::DW;
         c.act_lds = (const uint8_t *)(lds + L::ACT) + e;
         c.act_row = L::ACT_ROW;
         c.act_mask = 2 * ACT_BLOCK * L::ACT_ROW - 1;
@@ -724,10 +729,6 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         *(uint4 *)act_stage = load_actions<PARTIAL>(act_lane, stage_row, last, N, act_valid);
         uint4 act_regs = load_actions<PARTIAL>(act_lane, ACT_BLOCK + stage_row, last, N, act_valid);
         __syncthreads();                                             // barrier 0 (set-up)
-        c.ahead_start = wall_row<Word>(c.lds_env, SP, c.sd, syd - 1);
-        s.ahead_keep = wall_row<Word>(c.lds_env, SP, s.d, yd0 - 1);
-        s.spec = s.ahead_keep;
-        s.use_start = false; s.use_keep = true;
         s.act_off = 0;
         s.a_next = c.act_lds[0];
         uint32_t *st_e = lds + L::ST + e;
@@ -737,7 +738,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                 if (!MAZE_STEP_ON(u)) continue;
                 // (idle lanes of a partly filled wave repeat env 0 of the workgroup: the same
                 // values to the same addresses; stepping all lanes keeps the flags plain masks)
-                dyn_step<Word, EPW, SQUARE>(s, c, st_e + (par * SPB + u) * L::ST_SIZE);
+                dyn_step<Word, EPW>(s, c, st_e + (par * SPB + u) * L::ST_SIZE);
                 // stage the next block of actions half way through the current one
                 if ((i & (ACT_BLOCK - 1)) == ACT_BLOCK / 2) {
                     const int nb = i / ACT_BLOCK + 1;
@@ -746,7 +747,10 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                 }
             })
         if (active) {
-            p.pose[n] = (s.pos & 255u) | ((s.pos >> 16) << 8) | ((uint32_t)s.d << 16);
+            const int d = s.dv == heading_vector(0) ? 0 : s.dv == heading_vector(1) ? 1 : s.dv == heading_vector(2) ? 2 : 3;
+            int xd, yd;
+            padded_to_frame(p, d, (int)(s.pos & 0xFFFFu), (int)(s.pos >> 16), xd, yd);
+            p.pose[n] = (uint32_t)xd | ((uint32_t)yd << 8) | ((uint32_t)d << 16);
             p.tcount[n] = s.t;
         }
         __syncthreads();
@@ -754,37 +758,46 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         __syncthreads();
     } else if (wave < 2 * V::NDYN) {
         // =================================================================== views
-        // With 32 envs per workgroup the wave's upper half takes every other step of a block
-        // (UPL steps per pass), so the stage issues half the instructions per step.
-        const int half = UPL == 2 ? lane >> 5 : 0;
-        const int el = UPL == 2 ? (lane & 31) : lane;
+        // With fewer than 64 envs per workgroup the wave's lanes beyond the first LA take the
+        // next steps of a block (UPL steps per pass: `half` is the step within the pass), so
+        // the stage issues 1 / UPL of the instructions per step.
+        const int half = UPL > 1 ? lane / V::LA : 0;
+        const int el = UPL > 1 ? lane % V::LA : lane;
         const bool active = el < live_lanes;
         const int e = (wave - V::NDYN) * 64 + (active ? el : 0);
         const uint32_t *lds_env = lds + L::GRID0 + e * L::grid_stride(SP);
         const uint32_t *st_lane = lds + L::ST + half * L::ST_SIZE + e;
         uint32_t *vw_lane = lds + L::VW + half * L::VW_SIZE + e;
+        // the goal cell in each heading's frame, Xd | Yd << 16
+        const uint4 gr = *(const uint4 *)(p.goalrot + 4 * (size_t)(env0 + e));
+        uint32_t goal0 = (gr.x & 255u) | ((gr.x >> 8) << 16), goal1 = (gr.y & 255u) | ((gr.y >> 8) << 16);
+        uint32_t goal2 = (gr.z & 255u) | ((gr.z >> 8) << 16), goal3 = (gr.w & 255u) | ((gr.w >> 8) << 16);
+        // (the compiler is not to know that the four were one vector: it would turn the selects
+        // between them into an indexed read of a copy on the stack)
+        asm volatile("" : "+v"(goal0), "+v"(goal1), "+v"(goal2), "+v"(goal3));
+        const int HPm1 = p.HP - 1, WPm1 = p.WP - 1;
         __syncthreads();                                             // barrier 0 (set-up)
         __syncthreads();                                             // block 0 published
         MAZE_FOR_EACH_BLOCK(
             if (active) {
                 _Pragma("unroll") for (int u0 = 0; u0 < SPB / UPL; u0 += UGVP) {
-                    uint32_t pose[UGVP], g[UGVP], out[UGVP];
+                    FramePose f[UGVP];
+                    uint32_t out[UGVP];
                     Word rows[UGVP][K];
                     _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half)) {
                         const uint32_t *st = st_lane + (par * SPB + (u0 + w) * UPL) * L::ST_SIZE;
-                        pose[w] = st[0]; g[w] = st[EPW]; out[w] = st[2 * EPW];
+                        f[w] = to_frame(st[0], st[EPW], goal0, goal1, goal2, goal3, HPm1, WPm1);
+                        out[w] = st[2 * EPW];
                     }
                     _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half))
-                        load_view_rows<K, Word, true>(lds_env, nullptr, SP,
-                                                          (out[w] >> ST_HEADING_SHIFT) & 3, pose[w] >> 16,
-                                                          rows[w]);
+                        load_view_rows<K, Word, true>(lds_env, nullptr, SP, f[w].d, f[w].pos >> 16, rows[w]);
                     _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half)) {
                         uint32_t vw[V::WV];
-                        pack_view<K, Word>(rows[w], pose[w] & 0xFFFF, vw);
+                        pack_view<K, Word>(rows[w], f[w].pos & 0xFFFF, vw);
                         uint32_t *v = vw_lane + (par * SPB + (u0 + w) * UPL) * L::VW_SIZE;
                         _Pragma("unroll") for (int q = 0; q < V::WV; ++q) v[q * EPW] = vw[q];
-                        v[V::WV * EPW] = g[w];
-                        v[(V::WV + 1) * EPW] = out[w] & ST_OUTCOME_MASK;
+                        v[V::WV * EPW] = f[w].goal;
+                        v[(V::WV + 1) * EPW] = out[w];
                     }
                 }
             })
@@ -792,8 +805,8 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         __syncthreads();
     } else if (wave < 3 * V::NDYN) {
         // ================================================================= records
-        const int half = UPL == 2 ? lane >> 5 : 0;
-        const int el = UPL == 2 ? (lane & 31) : lane;
+        const int half = UPL > 1 ? lane / V::LA : 0;
+        const int el = UPL > 1 ? lane % V::LA : lane;
         const bool active = el < live_lanes;
         const int e = (wave - 2 * V::NDYN) * 64 + (active ? el : 0);
         float *rw = reward + env0 + e + (size_t)half * N;
@@ -1040,24 +1053,13 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
             return launch_rollout<K, Word, EPW, MODE, PARTIAL, true>(ctx, n_begin, n_envs, d_actions, n_steps,
                                                                      d_reward, d_done, d_obs, st);
     }
-    // the square-grid flavour exists for the plain kernel only
-    constexpr bool PLAIN = MODE == 0 && !PARTIAL;
-    const bool square = p.HP == p.WP && PLAIN;
-    // largest LDS size granted so far, per kernel flavour and device (the attribute belongs to
-    // the kernel on one device); a race between host threads only repeats the call
-    static size_t granted_all[2][16] = {};      // (one table per instantiation of this function)
-    size_t *granted = &granted_all[square ? 0 : 1][ctx->device & 15];
-    if (square) {
-        auto kern = k_student_rollout<K, Word, EPW, PLAIN, MODE, PARTIAL, BIG>;
-        if (!allow_large_lds(kern, shmem, granted)) return MAZE_EHIP;
-        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
-                           d_done, d_obs, pace_fp);
-    } else {
-        auto kern = k_student_rollout<K, Word, EPW, false, MODE, PARTIAL, BIG>;
-        if (!allow_large_lds(kern, shmem, granted)) return MAZE_EHIP;
-        hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
-                           d_done, d_obs, pace_fp);
-    }
+    // largest LDS size granted so far, per device (the attribute belongs to the kernel on one
+    // device); a race between host threads only repeats the call
+    static size_t granted_all[16] = {};         // (one table per instantiation of this function)
+    auto kern = k_student_rollout<K, Word, EPW, MODE, PARTIAL, BIG>;
+    if (!allow_large_lds(kern, shmem, &granted_all[ctx->device & 15])) return MAZE_EHIP;
+    hipLaunchKernelGGL(kern, grid, block, shmem, st, p, n_begin, n_end, d_actions, n_steps, d_reward,
+                       d_done, d_obs, pace_fp);
     return n_end - n_begin;
 }
 
@@ -1089,9 +1091,11 @@ int plan_k(int N, int SP, bool variant, bool occlusion, int cus, size_t budget, 
     const size_t b128 = variant ? Lds<K, Word, 128, 1>::bytes(SP) : Lds<K, Word, 128>::bytes(SP);
     const size_t b64 = variant ? Lds<K, Word, 64, 1>::bytes(SP) : Lds<K, Word, 64>::bytes(SP);
     const size_t b32 = variant ? Lds<K, Word, 32, 1>::bytes(SP) : Lds<K, Word, 32>::bytes(SP);
+    const size_t b16 = variant ? Lds<K, Word, 16, 1>::bytes(SP) : Lds<K, Word, 16>::bytes(SP);
     if (b32 > budget) return MAZE_EHIP;
     if (!occlusion && N >= 128 * (long long)cus && b128 <= budget) { *epw = 128; *lds_bytes = b128; }
     else if (N >= 64 * (long long)cus && b64 <= budget) { *epw = 64; *lds_bytes = b64; }
+    else if (N >= 16 && N <= 16 * (long long)cus) { *epw = 16; *lds_bytes = b16; }
     else { *epw = 32; *lds_bytes = b32; }
     return MAZE_OK;
 }
@@ -1143,12 +1147,17 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
         else if (epw == 64)
             covered = launch_rollout<K, Word, 64, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done,
                                                      d_obs, st);
+        else if (epw == 16)
+            covered = launch_rollout<K, Word, 16, 1>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done,
+                                                     d_obs, st);
         return launch_rest<K, Word, 1>(ctx, covered, d_actions, n_steps, d_reward, d_done, d_obs, st);
     }
     if (epw == 128)
         covered = launch_rollout<K, Word, 128>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
     else if (epw == 64)
         covered = launch_rollout<K, Word, 64>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
+    else if (epw == 16)
+        covered = launch_rollout<K, Word, 16>(ctx, 0, p.N, d_actions, n_steps, d_reward, d_done, d_obs, st);
     return launch_rest<K, Word, 0>(ctx, covered, d_actions, n_steps, d_reward, d_done, d_obs, st);
 }
 

@@ -113,8 +113,12 @@ def test_rollout_plan_and_the_lds_error_path(lib):
     assert plan(32768, 13, 13, 5, enc=1)[:2] == (0, 128)
     assert plan(32768, 13, 13, 5, occ=1)[:2] == (0, 64)
     assert plan(16384, 13, 13, 5)[:2] == (0, 64)
-    assert plan(4096, 13, 13, 5)[:2] == (0, 32)
-    assert plan(32, 13, 13, 5)[:2] == (0, 32)
+    assert plan(8192, 13, 13, 5)[:2] == (0, 32)
+    # a batch that would leave compute units idle with 32 envs per workgroup takes 16
+    assert plan(4096, 13, 13, 5)[:2] == (0, 16)
+    assert plan(4097, 13, 13, 5)[:2] == (0, 32)
+    assert plan(32, 13, 13, 5)[:2] == (0, 16)
+    assert plan(15, 13, 13, 5)[:2] == (0, 32)
     assert plan(8192, 51, 51, 7)[:2] == (0, 32)
     # fewer units: large workgroups from smaller batches on
     assert plan(8192, 13, 13, 5, cus=64)[:2] == (0, 128)
@@ -122,8 +126,10 @@ def test_rollout_plan_and_the_lds_error_path(lib):
     rc, e, b = plan(32768, 13, 13, 5, per_cu=64 * 1024)
     assert rc == 0 and e < 128 and b <= 63 * 1024
     # the largest grids with view 7 and both variants on need 126 KB for 32 envs
-    rc, e, b = plan(64, 52, 52, 7, enc=1, occ=1)
+    rc, e, b = plan(8192, 52, 52, 7, enc=1, occ=1)
     assert (rc, e) == (0, 32) and 120 * 1024 < b <= 127 * 1024
+    rc, e, b = plan(64, 52, 52, 7, enc=1, occ=1)
+    assert (rc, e) == (0, 16) and b < 100 * 1024
     assert plan(64, 52, 52, 7, enc=1, occ=1, per_cu=64 * 1024)[0] == -4      # MAZE_EHIP
     assert plan(8192, 51, 51, 7, per_cu=64 * 1024)[0] == -4
     # view sizes the store-layout kernels do not take: no error, no workgroup size

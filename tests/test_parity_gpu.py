@@ -183,9 +183,10 @@ def test_chunked_rollout_equals_one_launch():
     assert_state_equal(env, o)
 
 
-@pytest.mark.parametrize("N", [128, 256 + 32, 8192 + 64 + 5, 16384, 16384 + 32 + 16, 32768 + 96, 32768 + 128 + 40])
+@pytest.mark.parametrize("N", [16, 48 + 7, 128, 256 + 32, 4096, 4096 + 32, 8192 + 64 + 5, 16384, 16384 + 32 + 16,
+                               32768 + 96, 32768 + 128 + 40])
 def test_workgroup_size_choices(N):
-    """Batch sizes that make the launcher pick 32, 64 or 128 envs per workgroup, with tails."""
+    """Batch sizes that make the launcher pick 16, 32, 64 or 128 envs per workgroup, with tails."""
     w = wl.student_random(f"epw{N}", 4000 + N, N=N, T=37, n_walls=50, max_steps=25)
     note(w.name)
     run_fused(w)
@@ -194,8 +195,8 @@ def test_workgroup_size_choices(N):
 @pytest.mark.parametrize("T", [2, 3, 7, 8, 9, 15, 16, 17, 23, 24, 25, 31, 32, 33, 47, 48, 49, 63, 64, 65, 97])
 def test_rollout_lengths_around_block_boundaries(T):
     """Rollout lengths just below, at and above multiples of the kernel's step blocks and action
-    staging blocks, in a small batch (32 envs per workgroup) and one with 64 per workgroup."""
-    for N, k, S in ((96, 5, 13), (16384, 3, 9)):
+    staging blocks, in batches that take 16, 32 and 64 envs per workgroup."""
+    for N, k, S in ((96, 5, 13), (4096 + 64, 5, 13), (16384, 3, 9)):
         w = wl.student_random(f"T{T}-N{N}", 7000 + T + N, N=N, H=S, W=S, view=k, T=T, n_walls=S * S // 4,
                               max_steps=11)
         note(w.name)

@@ -55,6 +55,15 @@ def test_64_env_workgroups_around_block_boundaries(encoding, occlusion, T):
     run_variant(w, encoding, occlusion)
 
 
+@pytest.mark.parametrize("N,T", [(4096 + 96, 9), (4096 + 96, 40), (8192, 17), (4096, 8), (4096, 70), (48, 131)])
+@pytest.mark.parametrize("encoding,occlusion", MODES)
+def test_small_workgroups_around_block_boundaries(encoding, occlusion, N, T):
+    # more than 4096 envs: 32 envs per workgroup (views and records take two steps per pass);
+    # up to 4096: 16 per workgroup (four steps per pass, action ring refilled every 64 steps)
+    w = wl.student_random(f"variant-{N}-T{T}", 1500 + N + T, N=N, T=T, n_walls=50, max_steps=11)
+    run_variant(w, encoding, occlusion)
+
+
 @pytest.mark.parametrize("T", [8, 17, 41])
 @pytest.mark.parametrize("encoding,occlusion", MODES)
 def test_largest_workgroups_around_block_boundaries(encoding, occlusion, T):
