@@ -105,8 +105,8 @@ struct Lds {
     static constexpr int VIS_N = MODE == 1 ? (1 << (2 * K)) / 2 : 0;
     static constexpr int ACT = VIS + VIS_N;                        // [2][ACT_BLOCK][EPW] action bytes
     static constexpr int ACT_ROW = EPW;                            // bytes per step
-    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][3][EPW] position, forward vector, outcome
-    static constexpr int ST_SIZE = 3 * EPW;
+    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][EPW][4] position, forward vector, outcome, -
+    static constexpr int ST_SIZE = 4 * EPW;                        // (four dwords per env: one 16-byte access)
     static constexpr int VW = ST + 2 * SPB * ST_SIZE;              // [2][SPB][WV+2][EPW] view bits, goal, out
     static constexpr int VW_SIZE = (V::WV + 2) * EPW;
     static constexpr int REC = VW + 2 * SPB * VW_SIZE;             // [2][SPB][EPW*REC] stream records
@@ -550,9 +550,10 @@ __device__ __forceinline__ uint32_t heading_vector(int d)
     return d == 0 ? 0x00000001u : d == 1 ? 0x00010000u : d == 2 ? 0x0000FFFFu : 0xFFFF0000u;
 }
 
-// Dynamics stage -> views stage, three dwords per env and step:
+// Dynamics stage -> views stage, per env and step one 16-byte piece (written and read with one
+// LDS instruction each):
 //   position (X | Y << 16), forward vector (dx | dy << 16),
-//   outcome: step count if the goal was reached (else 0) | done << 31.
+//   outcome: step count if the goal was reached (else 0) | done << 31, one dword unused.
 // One env step of the dynamics stage.  The row of the cell ahead is requested first, before
 // the action is looked at (a turn does not use it); a right turn maps the forward vector
 // (dx, dy) to (-dy, dx), a left turn to (dy, -dx): one packed multiply of the swapped pair.
@@ -584,9 +585,7 @@ __device__ __forceinline__ void dyn_step(DynState &s, const DynConst &c, uint32_
     s.pos = fin ? c.start_pos : moved;
     s.dv = fin ? c.start_dv : ndv;
     s.t = fin ? 0u : t1;
-    st[0] = s.pos;
-    st[EPW] = s.dv;
-    st[2 * EPW] = (reached ? t1 : 0u) | (fin ? 0x80000000u : 0u);
+    *(uint4 *)st = make_uint4(s.pos, s.dv, (reached ? t1 : 0u) | (fin ? 0x80000000u : 0u), 0u);
 }
 
 // What the views stage makes of a published pose: the heading, the position in the heading's
@@ -676,7 +675,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     constexpr int UPL = SPB % (64 / V::LA) == 0 ? 64 / V::LA : 1;
     constexpr int UGVP = UGV > SPB / UPL ? SPB / UPL : UGV;
     constexpr int UGRP = UGR > SPB / UPL ? SPB / UPL : UGR;
-    extern __shared__ uint32_t lds[];
+    extern __shared__ __align__(16) uint32_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wg = xcd_contiguous(blockIdx.x, gridDim.x);
@@ -731,7 +730,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         __syncthreads();                                             // barrier 0 (set-up)
         s.act_off = 0;
         s.a_next = c.act_lds[0];
-        uint32_t *st_e = lds + L::ST + e;
+        uint32_t *st_e = lds + L::ST + 4 * e;
         MAZE_FOR_EACH_BLOCK(
             _Pragma("unroll") for (int u = 0; u < SPB; ++u) {
                 const int i = i0 + u;
@@ -766,7 +765,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         const bool active = el < live_lanes;
         const int e = (wave - V::NDYN) * 64 + (active ? el : 0);
         const uint32_t *lds_env = lds + L::GRID0 + e * L::grid_stride(SP);
-        const uint32_t *st_lane = lds + L::ST + half * L::ST_SIZE + e;
+        const uint32_t *st_lane = lds + L::ST + half * L::ST_SIZE + 4 * e;
         uint32_t *vw_lane = lds + L::VW + half * L::VW_SIZE + e;
         // the goal cell in each heading's frame, Xd | Yd << 16
         const uint4 gr = *(const uint4 *)(p.goalrot + 4 * (size_t)(env0 + e));
@@ -786,8 +785,9 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                     Word rows[UGVP][K];
                     _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half)) {
                         const uint32_t *st = st_lane + (par * SPB + (u0 + w) * UPL) * L::ST_SIZE;
-                        f[w] = to_frame(st[0], st[EPW], goal0, goal1, goal2, goal3, HPm1, WPm1);
-                        out[w] = st[2 * EPW];
+                        const uint4 pub = *(const uint4 *)st;
+                        f[w] = to_frame(pub.x, pub.y, goal0, goal1, goal2, goal3, HPm1, WPm1);
+                        out[w] = pub.z;
                     }
                     _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half))
                         load_view_rows<K, Word, true>(lds_env, nullptr, SP, f[w].d, f[w].pos >> 16, rows[w]);
@@ -1034,9 +1034,10 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
     // Pacing of the store waves (see the kernel's stores stage): the time one step of the launch
     // should take if the workgroups resident at once write their chunks, reward and done at
     // MAZE_PACED_GBS (MAZE_PACED_GBS_TYPED for the typed observation).  Paced are launches that
-    // write more than twice what the 256 MB memory-side cache holds (a smaller output is absorbed there and leaves
-    // the chip later: 16384 envs x 256 steps take 52 us unpaced, 57 paced) and do not build the
-    // occluded view (there the records stage sets the pace: 117 us unpaced, 120 paced).
+    // write more than twice what the 256 MB memory-side cache holds (a smaller output is absorbed
+    // there and leaves the chip later: 16384 envs x 256 steps take 52 us unpaced, 57 paced) and do
+    // not build the occluded view (there the records stage sets the pace: 117 us unpaced, 120
+    // paced).
     const double out_bytes = (double)(n_end - n_begin) * n_steps * (V::SB + 5);
     uint32_t pace_fp = 0;
     if (!p.obs_occlusion) {

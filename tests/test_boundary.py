@@ -125,9 +125,9 @@ def test_rollout_plan_and_the_lds_error_path(lib):
     # the same shapes with the 64 KB of an older part: smaller workgroups, still the fast kernel
     rc, e, b = plan(32768, 13, 13, 5, per_cu=64 * 1024)
     assert rc == 0 and e < 128 and b <= 63 * 1024
-    # the largest grids with view 7 and both variants on need 126 KB for 32 envs
+    # the largest grids with view 7 and both variants on need 128 KB for 32 envs
     rc, e, b = plan(8192, 52, 52, 7, enc=1, occ=1)
-    assert (rc, e) == (0, 32) and 120 * 1024 < b <= 127 * 1024
+    assert (rc, e) == (0, 32) and 120 * 1024 < b <= 129 * 1024
     rc, e, b = plan(64, 52, 52, 7, enc=1, occ=1)
     assert (rc, e) == (0, 16) and b < 100 * 1024
     assert plan(64, 52, 52, 7, enc=1, occ=1, per_cu=64 * 1024)[0] == -4      # MAZE_EHIP
