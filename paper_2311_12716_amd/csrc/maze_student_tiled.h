@@ -105,7 +105,7 @@ struct Lds {
     static constexpr int VIS_N = MODE == 1 ? (1 << (2 * K)) / 2 : 0;
     static constexpr int ACT = VIS + VIS_N;                        // [2][ACT_BLOCK][EPW] action bytes
     static constexpr int ACT_ROW = EPW;                            // bytes per step
-    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][EPW][4] position, forward vector, outcome, -
+    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][EPW][4] cell, forward vector, step count, -
     static constexpr int ST_SIZE = 4 * EPW;                        // (four dwords per env: one 16-byte access)
     static constexpr int VW = ST + 2 * SPB * ST_SIZE;              // [2][SPB][WV+2][EPW] view bits, goal, out
     static constexpr int VW_SIZE = (V::WV + 2) * EPW;
@@ -520,16 +520,27 @@ __device__ __forceinline__ uint32_t as_word(pair16 v) { return __builtin_bit_cas
 // grid's own coordinates -- a move is one add, the wall test one word of the unrotated grid
 // -- and leaves the change to the heading's frame, which only the view needs, to the views
 // stage, where nothing waits for the previous step.
+template <typename Word>
 struct DynState {
     uint32_t pos;             // X | Y << 16, padded-grid coordinates
     uint32_t dv;              // one step forward, (dx, dy) as two 16-bit numbers
     uint32_t t;               // steps since the episode began
+    // The row of the cell ahead decides whether a forward step is blocked.  It is fetched one
+    // step early: as soon as the action is known, the row ahead of the pose the action leads
+    // to -- taking a forward step as successful -- is requested (`spec`), and the choice
+    // between that word, the previous one (the forward step hit a wall: pose unchanged) and
+    // the start pose's word (episode ended) is made at the top of the next step, when the LDS
+    // read has returned.
+    Word row_keep, spec;
+    bool use_start, use_keep;
     uint32_t act_off, a_next; // action ring cursor (bytes) and the next step's action
 };
 
+template <typename Word>
 struct DynConst {
     uint32_t start_pos, start_dv;      // the level's start pose, packed as above
     uint32_t goal_pos;                 // the goal cell, packed like pos
+    Word row_start;                    // row of the cell ahead of the start pose
     uint32_t tmax;
     const uint32_t *rows;              // this env's unrotated grid (frame 3) in LDS
     const uint8_t *act_lds;            // this env's column of the action ring
@@ -551,41 +562,44 @@ __device__ __forceinline__ uint32_t heading_vector(int d)
 }
 
 // Dynamics stage -> views stage, per env and step one 16-byte piece (written and read with one
-// LDS instruction each):
-//   position (X | Y << 16), forward vector (dx | dy << 16),
-//   outcome: step count if the goal was reached (else 0) | done << 31, one dword unused.
-// One env step of the dynamics stage.  The row of the cell ahead is requested first, before
-// the action is looked at (a turn does not use it); a right turn maps the forward vector
-// (dx, dy) to (-dy, dx), a left turn to (dy, -dx): one packed multiply of the swapped pair.
-// (Fetching that row a step early, for the pose the action leads to, and the action two steps
-// early, as an earlier form of this stage did, gains nothing here: a step is ~31 instructions
-// of which most wait for the one before, and a dependent instruction issues 9 cycles after its
-// producer on this chip, an LDS read returns after 60.)
+// LDS instruction each): the cell the agent is in after the action (X | Y << 16), the forward
+// vector after the action (dx | dy << 16), the episode's step count including this step -- all
+// before the reset that an episode's end brings -- and one dword unused.
+// One env step of the dynamics stage.  A right turn maps the forward vector (dx, dy) to
+// (-dy, dx), a left turn to (dy, -dx): one packed multiply of the swapped pair.  The stage
+// keeps its own state right across episode ends but publishes what it has before the reset
+// (the cell the agent moved to, the heading after the action, the step count): whether the
+// goal was reached, whether the episode ended and the pose the observation then shows follow
+// from these and the level's constants in the views stage, off the step-to-step chain.
 template <typename Word, int EPW>
-__device__ __forceinline__ void dyn_step(DynState &s, const DynConst &c, uint32_t *st)
+__device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word> &c, uint32_t *st)
 {
     const uint32_t a = s.a_next;
     s.act_off = (s.act_off + c.act_row) & c.act_mask;
     s.a_next = c.act_lds[s.act_off];        // next step's action (staged >= half a block ago)
-    const pair16 dv = as_pair(s.dv), swapped = dv.yx;
-    const uint32_t ahead = as_word(as_pair(s.pos) + dv);
-    const Word row = grid_row<Word>(c.rows, ahead >> 16);
     const bool tl = (a == 0), tr = (a == 1), f2 = (a == 2);
+    const pair16 dv = as_pair(s.dv), swapped = dv.yx;
     const uint32_t right = as_word(swapped * (pair16){-1, 1}), left = as_word(swapped * (pair16){1, -1});
     uint32_t ndv = tr ? right : s.dv;
     ndv = tl ? left : ndv;
-    // (a bit-field extract takes its position from the low 5 bits: the X half of `ahead`)
+    const uint32_t ahead = as_word(as_pair(s.pos) + dv);
+    const uint32_t next = f2 ? ahead : s.pos;
+    const Word row = s.use_start ? c.row_start : (s.use_keep ? s.row_keep : s.spec);
+    s.spec = grid_row<Word>(c.rows, as_word(as_pair(next) + as_pair(ndv)) >> 16);
     const uint32_t blocked = sizeof(Word) == 4 ? __builtin_amdgcn_ubfe((uint32_t)row, ahead, 1)
                                                : (uint32_t)(row >> (ahead & 63u)) & 1u;
-    const bool go = f2 & (blocked == 0);
-    const uint32_t moved = go ? ahead : s.pos;
+    const bool stay = f2 & (blocked != 0);
+    const uint32_t moved = stay ? s.pos : next;
     const uint32_t t1 = s.t + 1;
     const bool reached = moved == c.goal_pos;
     const bool fin = reached | (t1 >= c.tmax);
     s.pos = fin ? c.start_pos : moved;
     s.dv = fin ? c.start_dv : ndv;
     s.t = fin ? 0u : t1;
-    *(uint4 *)st = make_uint4(s.pos, s.dv, (reached ? t1 : 0u) | (fin ? 0x80000000u : 0u), 0u);
+    s.use_start = fin;
+    s.use_keep = stay;
+    s.row_keep = row;
+    *(uint4 *)st = make_uint4(moved, ndv, t1, 0u);
 }
 
 // What the views stage makes of a published pose: the heading, the position in the heading's
@@ -698,8 +712,8 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         const int e = wave * 64 + (active ? lane : 0);   // env within the workgroup
         const int n = env0 + e;
         const int last = n_steps - 1;
-        DynState s;
-        DynConst c;
+        DynState<Word> s;
+        DynConst<Word> c;
         // poses are kept in the frame of their heading between launches (pose = Xd | Yd << 8 |
         // d << 16); frame 3 is the padded grid itself
         const uint32_t pose = p.pose[n], start = p.start[n], goal3 = p.goalrot[4 * (size_t)n + 3];
@@ -728,6 +742,10 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         *(uint4 *)act_stage = load_actions<PARTIAL>(act_lane, stage_row, last, N, act_valid);
         uint4 act_regs = load_actions<PARTIAL>(act_lane, ACT_BLOCK + stage_row, last, N, act_valid);
         __syncthreads();                                             // barrier 0 (set-up)
+        c.row_start = grid_row<Word>(c.rows, as_word(as_pair(c.start_pos) + as_pair(c.start_dv)) >> 16);
+        s.row_keep = grid_row<Word>(c.rows, as_word(as_pair(s.pos) + as_pair(s.dv)) >> 16);
+        s.spec = s.row_keep;
+        s.use_start = false; s.use_keep = true;
         s.act_off = 0;
         s.a_next = c.act_lds[0];
         uint32_t *st_e = lds + L::ST + 4 * e;
@@ -775,6 +793,15 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         // between them into an indexed read of a copy on the stack)
         asm volatile("" : "+v"(goal0), "+v"(goal1), "+v"(goal2), "+v"(goal3));
         const int HPm1 = p.HP - 1, WPm1 = p.WP - 1;
+        const uint32_t tmax = (uint32_t)p.max_steps, goal_abs = goal3;      // frame 3 is the grid itself
+        uint32_t start_abs, start_dv;
+        {
+            const uint32_t start = p.start[env0 + e];
+            int X, Y;
+            frame_to_padded(p, (start >> 16) & 3, start & 255, (start >> 8) & 255, X, Y);
+            start_abs = (uint32_t)X | ((uint32_t)Y << 16);
+            start_dv = heading_vector((start >> 16) & 3);
+        }
         __syncthreads();                                             // barrier 0 (set-up)
         __syncthreads();                                             // block 0 published
         MAZE_FOR_EACH_BLOCK(
@@ -785,9 +812,11 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                     Word rows[UGVP][K];
                     _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half)) {
                         const uint32_t *st = st_lane + (par * SPB + (u0 + w) * UPL) * L::ST_SIZE;
-                        const uint4 pub = *(const uint4 *)st;
-                        f[w] = to_frame(pub.x, pub.y, goal0, goal1, goal2, goal3, HPm1, WPm1);
-                        out[w] = pub.z;
+                        const uint4 pub = *(const uint4 *)st;          // moved, forward vector, step count
+                        const bool reached = pub.x == goal_abs, fin = reached | (pub.z >= tmax);
+                        f[w] = to_frame(fin ? start_abs : pub.x, fin ? start_dv : pub.y, goal0, goal1, goal2, goal3,
+                                        HPm1, WPm1);
+                        out[w] = (reached ? pub.z : 0u) | (fin ? 0x80000000u : 0u);
                     }
                     _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half))
                         load_view_rows<K, Word, true>(lds_env, nullptr, SP, f[w].d, f[w].pos >> 16, rows[w]);
