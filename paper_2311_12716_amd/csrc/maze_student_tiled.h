@@ -103,9 +103,11 @@ struct Lds {
     static constexpr int TYPED_N = MODE == 1 ? 3 * 128 : 0;
     static constexpr int VIS = TYPED + TYPED_N;                    // [2^(2K)] 16-bit rows (visibility_table)
     static constexpr int VIS_N = MODE == 1 ? (1 << (2 * K)) / 2 : 0;
-    static constexpr int ACT = VIS + VIS_N;                        // [2][ACT_BLOCK][EPW] action bytes
-    static constexpr int ACT_ROW = EPW;                            // bytes per step
-    static constexpr int ST = ACT + 2 * V::ACT_BLOCK * EPW / 4;    // [2][SPB][EPW][4] cell, forward vector, step count, -
+    // action ring: per env the bytes of 2 * ACT_BLOCK consecutive steps, so that one dword holds
+    // the actions of four steps; an env's ring is one dword longer than that (odd pitch)
+    static constexpr int ACT = VIS + VIS_N;                        // [EPW][ACT_PITCH] dwords
+    static constexpr int ACT_PITCH = V::ACT_BLOCK / 2 + 1;         // dwords per env
+    static constexpr int ST = ACT + EPW * ACT_PITCH;               // [2][SPB][EPW][4] cell, forward vector, step count, -
     static constexpr int ST_SIZE = 4 * EPW;                        // (four dwords per env: one 16-byte access)
     static constexpr int VW = ST + 2 * SPB * ST_SIZE;              // [2][SPB][WV+2][EPW] view bits, goal, out
     static constexpr int VW_SIZE = (V::WV + 2) * EPW;
@@ -533,7 +535,6 @@ struct DynState {
     // read has returned.
     Word row_keep, spec;
     bool use_start, use_keep;
-    uint32_t act_off, a_next; // action ring cursor (bytes) and the next step's action
 };
 
 template <typename Word>
@@ -543,8 +544,6 @@ struct DynConst {
     Word row_start;                    // row of the cell ahead of the start pose
     uint32_t tmax;
     const uint32_t *rows;              // this env's unrotated grid (frame 3) in LDS
-    const uint8_t *act_lds;            // this env's column of the action ring
-    uint32_t act_mask, act_row;        // ring size - 1 and row pitch, bytes
 };
 
 // Word of row `y` of an env's unrotated grid.
@@ -572,11 +571,8 @@ __device__ __forceinline__ uint32_t heading_vector(int d)
 // goal was reached, whether the episode ended and the pose the observation then shows follow
 // from these and the level's constants in the views stage, off the step-to-step chain.
 template <typename Word, int EPW>
-__device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word> &c, uint32_t *st)
+__device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word> &c, uint32_t a, uint32_t *st)
 {
-    const uint32_t a = s.a_next;
-    s.act_off = (s.act_off + c.act_row) & c.act_mask;
-    s.a_next = c.act_lds[s.act_off];        // next step's action (staged >= half a block ago)
     const bool tl = (a == 0), tr = (a == 1), f2 = (a == 2);
     const pair16 dv = as_pair(s.dv), swapped = dv.yx;
     const uint32_t right = as_word(swapped * (pair16){-1, 1}), left = as_word(swapped * (pair16){1, -1});
@@ -728,38 +724,55 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         c.goal_pos = (goal3 & 255u) | ((goal3 >> 8) << 16);
         c.tmax = (uint32_t)p.max_steps;
         c.rows = lds + L::GRID0 + e * L::grid_stride(SP) + 3 * SP * WordOps<Word>::DW;
-        c.act_lds = (const uint8_t *)(lds + L::ACT) + e;
-        c.act_row = L::ACT_ROW;
-        c.act_mask = 2 * ACT_BLOCK * L::ACT_ROW - 1;
-        // actions: lane l of this wave stages the bytes of step block*ACT_BLOCK + l/ACT_LPR
-        // for 16 of the wave's envs (all 64 lanes stage, whatever LA is)
+        // Actions.  Global memory holds them step-major; lane l of this wave loads the 16 bytes
+        // of step block * ACT_BLOCK + l / ACT_LPR for 16 of the wave's envs (all 64 lanes load,
+        // whatever LA is) and writes them, byte by byte, into those envs' rings, where an env's
+        // consecutive steps are consecutive bytes: the step loop then reads one dword per four
+        // steps.  A block of ACT_BLOCK steps is staged half a block of them before its first
+        // step, into the half of the ring the block before the previous one has left.
         const int stage_row = lane / V::ACT_LPR;
         const int stage_col = wave * 64 + 16 * (lane % V::ACT_LPR);
         const int8_t *act_lane = actions + env0 + stage_col;
-        uint8_t *act_stage = (uint8_t *)(lds + L::ACT) + stage_row * L::ACT_ROW + stage_col;
+        uint8_t *act_stage = (uint8_t *)(lds + L::ACT) + stage_col * (4 * L::ACT_PITCH) + stage_row;
         // bytes of a row that exist from this lane's first column on (PARTIAL: may be < 16)
         const int act_valid = PARTIAL ? N - (env0 + stage_col) : 16;
-        *(uint4 *)act_stage = load_actions<PARTIAL>(act_lane, stage_row, last, N, act_valid);
+        auto stage_actions = [&](int half, const uint4 &v) {
+            const uint32_t dw[4] = {v.x, v.y, v.z, v.w};
+            _Pragma("unroll") for (int j = 0; j < 16; ++j)
+                act_stage[half * ACT_BLOCK + j * (4 * L::ACT_PITCH)] = (uint8_t)(dw[j >> 2] >> (8 * (j & 3)));
+        };
+        stage_actions(0, load_actions<PARTIAL>(act_lane, stage_row, last, N, act_valid));
         uint4 act_regs = load_actions<PARTIAL>(act_lane, ACT_BLOCK + stage_row, last, N, act_valid);
         __syncthreads();                                             // barrier 0 (set-up)
         c.row_start = grid_row<Word>(c.rows, as_word(as_pair(c.start_pos) + as_pair(c.start_dv)) >> 16);
         s.row_keep = grid_row<Word>(c.rows, as_word(as_pair(s.pos) + as_pair(s.dv)) >> 16);
         s.spec = s.row_keep;
         s.use_start = false; s.use_keep = true;
-        s.act_off = 0;
-        s.a_next = c.act_lds[0];
+        const uint32_t *act_ring = lds + L::ACT + e * L::ACT_PITCH;
+        constexpr int RING_MASK = 2 * ACT_BLOCK - 1;                 // ring length in steps - 1
+        uint32_t act_w0 = act_ring[0], act_w1 = act_ring[1];         // the actions of the block's 8 steps
+        static_assert(SPB == 8, "two action dwords per block");
         uint32_t *st_e = lds + L::ST + 4 * e;
         MAZE_FOR_EACH_BLOCK(
+            const uint32_t w0 = act_w0; const uint32_t w1 = act_w1;
             _Pragma("unroll") for (int u = 0; u < SPB; ++u) {
                 const int i = i0 + u;
-                if (!MAZE_STEP_ON(u)) continue;
-                // (idle lanes of a partly filled wave repeat env 0 of the workgroup: the same
-                // values to the same addresses; stepping all lanes keeps the flags plain masks)
-                dyn_step<Word, EPW>(s, c, st_e + (par * SPB + u) * L::ST_SIZE);
+                if (MAZE_STEP_ON(u)) {
+                    // (idle lanes of a partly filled wave repeat env 0 of the workgroup: the same
+                    // values to the same addresses; stepping all lanes keeps the flags plain masks)
+                    dyn_step<Word, EPW>(s, c, ((u < 4 ? w0 : w1) >> (8 * (u & 3))) & 255u,
+                                        st_e + (par * SPB + u) * L::ST_SIZE);
+                }
+                // the next block's actions, half a block early (staged at least half a block ago)
+                if (u == SPB / 2 - 1) {
+                    const int at = ((i0 + SPB) & RING_MASK) >> 2;
+                    act_w0 = act_ring[at];
+                    act_w1 = act_ring[at + 1];
+                }
                 // stage the next block of actions half way through the current one
                 if ((i & (ACT_BLOCK - 1)) == ACT_BLOCK / 2) {
                     const int nb = i / ACT_BLOCK + 1;
-                    *(uint4 *)(act_stage + (nb & 1) * (ACT_BLOCK * L::ACT_ROW)) = act_regs;
+                    stage_actions(nb & 1, act_regs);
                     act_regs = load_actions<PARTIAL>(act_lane, (nb + 1) * ACT_BLOCK + stage_row, last, N, act_valid);
                 }
             })
