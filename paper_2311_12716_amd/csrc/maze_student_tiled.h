@@ -564,6 +564,7 @@ __device__ __forceinline__ uint32_t heading_vector(int d)
 // LDS instruction each): the cell the agent is in after the action (X | Y << 16), the forward
 // vector after the action (dx | dy << 16), the episode's step count including this step -- all
 // before the reset that an episode's end brings -- and one dword unused.
+//
 // One env step of the dynamics stage.  A right turn maps the forward vector (dx, dy) to
 // (-dy, dx), a left turn to (dy, -dx): one packed multiply of the swapped pair.  The stage
 // keeps its own state right across episode ends but publishes what it has before the reset
@@ -582,6 +583,7 @@ __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word>
     const uint32_t next = f2 ? ahead : s.pos;
     const Word row = s.use_start ? c.row_start : (s.use_keep ? s.row_keep : s.spec);
     s.spec = grid_row<Word>(c.rows, as_word(as_pair(next) + as_pair(ndv)) >> 16);
+    // (the bit-field extract takes its position from the low 5 bits of `ahead`: its X half)
     const uint32_t blocked = sizeof(Word) == 4 ? __builtin_amdgcn_ubfe((uint32_t)row, ahead, 1)
                                                : (uint32_t)(row >> (ahead & 63u)) & 1u;
     const bool stay = f2 & (blocked != 0);
