@@ -131,6 +131,30 @@ def store_patterns(torch, env, actions, reward, done, obs, N, T, k):
     return {"store_patterns": table}
 
 
+def wave_latency(torch):
+    """What one wave on an idle compute unit pays per instruction (probe library): shader clocks
+    and nanoseconds per iteration of six small dependent or independent chains."""
+    import ctypes
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2311_12716_amd", "libmaze_storeprobe.so"))
+    lib.waveprobe_run.restype = ctypes.c_int
+    lib.waveprobe_run.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    lib.waveprobe_iterations.restype = ctypes.c_int
+    n = lib.waveprobe_iterations()
+    out = torch.zeros(13, dtype=torch.int64, device="cuda:0")
+    names = ["dependent_add", "four_independent_adds", "dependent_lds_read", "compare_select_add_chain",
+             "two_compares_scalar_and_select_chain", "lds_write_then_read"]
+    best = None
+    for _ in range(5):          # the first launches run on clocks that have not settled
+        if lib.waveprobe_run(out.data_ptr(), torch.cuda.current_stream().cuda_stream) != 0:
+            raise RuntimeError("waveprobe_run failed")
+        torch.cuda.synchronize()
+        v = out.cpu().tolist()
+        best = v if best is None or v[0] < best[0] else best
+    return {"wave_latency": {name: {"clocks_per_iteration": best[2 * j] / n, "ns_per_iteration": best[2 * j + 1] / n}
+                             for j, name in enumerate(names)},
+            "iterations": n}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -147,6 +171,8 @@ def main():
     ap.add_argument("--store-patterns", action="store_true",
                     help="only run the store-pattern probe (paper_2311_12716_amd/probe) at config 3's "
                          "geometry next to the rollout kernel and a plain fill, print its table")
+    ap.add_argument("--wave-latency", action="store_true",
+                    help="only run the single-wave latency probe (paper_2311_12716_amd/probe), print its table")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -163,6 +189,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     binding.load_library()        # fails loudly if the HIP library is not built
+    if args.wave_latency:
+        print(json.dumps(wave_latency(torch)))
+        return
     dev = "cuda:0"
     g = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
 

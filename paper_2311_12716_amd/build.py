@@ -21,8 +21,9 @@ HIPCC_FLAGS = [
     "-I" + os.path.join(ROOT, "include"),
 ]
 OBJ_DIR = os.path.join(HERE, "csrc", "_build")
-# measurement code of bench.py --store-patterns: a library of its own, not linked into the product
-PROBE_SRC = os.path.join(HERE, "probe", "store_patterns.hip")
+# measurement code of bench.py --store-patterns / --wave-latency: a library of its own, not linked
+# into the product
+PROBE_SRC = sorted(glob.glob(os.path.join(HERE, "probe", "*.hip")))
 PROBE_LIB = os.path.join(HERE, "libmaze_storeprobe.so")
 
 
@@ -69,11 +70,11 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
 
 
 def build_probe(verbose: bool = False) -> str:
-    """Compile the store-pattern probe (probe/store_patterns.hip) into its own library."""
+    """Compile the probes (probe/*.hip: store patterns, single-wave latencies) into their own library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = PROBE_LIB + f".tmp{os.getpid()}"
     flags = [f for f in HIPCC_FLAGS if not f.startswith("-I")]
-    if _run([hipcc] + flags + ["-shared", PROBE_SRC, "-o", tmp], verbose):
+    if _run([hipcc] + flags + ["-shared"] + PROBE_SRC + ["-o", tmp], verbose):
         raise RuntimeError("hipcc failed compiling libmaze_storeprobe.so")
     os.replace(tmp, PROBE_LIB)
     return PROBE_LIB
