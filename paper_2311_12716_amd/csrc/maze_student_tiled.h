@@ -554,6 +554,10 @@ __device__ __forceinline__ Word grid_row(const uint32_t *rows, uint32_t y)
     return (Word)(((uint64_t)rows[2 * y + 1] << 32) | rows[2 * y]);
 }
 
+// What the dynamics stage hands to the views stage per env and step (12 bytes in a 16-byte
+// slot: one LDS instruction each way).
+struct alignas(16) Published { uint32_t cell, dv, t; };
+
 // Forward vectors of the headings 0..3 (+x, +y, -x, -y) as (dx, dy) pairs of 16-bit numbers.
 __device__ __forceinline__ uint32_t heading_vector(int d)
 {
@@ -597,7 +601,7 @@ __device__ __forceinline__ void dyn_step(DynState<Word> &s, const DynConst<Word>
     s.use_start = fin;
     s.use_keep = stay;
     s.row_keep = row;
-    *(uint4 *)st = make_uint4(moved, ndv, t1, 0u);
+    *(Published *)st = Published{moved, ndv, t1};
 }
 
 // What the views stage makes of a published pose: the heading, the position in the heading's
@@ -827,11 +831,11 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
                     Word rows[UGVP][K];
                     _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half)) {
                         const uint32_t *st = st_lane + (par * SPB + (u0 + w) * UPL) * L::ST_SIZE;
-                        const uint4 pub = *(const uint4 *)st;          // moved, forward vector, step count
-                        const bool reached = pub.x == goal_abs, fin = reached | (pub.z >= tmax);
-                        f[w] = to_frame(fin ? start_abs : pub.x, fin ? start_dv : pub.y, goal0, goal1, goal2, goal3,
-                                        HPm1, WPm1);
-                        out[w] = (reached ? pub.z : 0u) | (fin ? 0x80000000u : 0u);
+                        const Published pub = *(const Published *)st;
+                        const bool reached = pub.cell == goal_abs, fin = reached | (pub.t >= tmax);
+                        f[w] = to_frame(fin ? start_abs : pub.cell, fin ? start_dv : pub.dv, goal0, goal1, goal2,
+                                        goal3, HPm1, WPm1);
+                        out[w] = (reached ? pub.t : 0u) | (fin ? 0x80000000u : 0u);
                     }
                     _Pragma("unroll") for (int w = 0; w < UGVP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half))
                         load_view_rows<K, Word, true>(lds_env, nullptr, SP, f[w].d, f[w].pos >> 16, rows[w]);
