@@ -460,6 +460,13 @@ def main():
         b5 = 153.0 * w5.N * w5.T
         rows["student_rollout_c5"] = {"ms": ms, "env-steps/s": w5.N * w5.T / ms * 1e3,
                                       "GB/s": b5 / ms / 1e6, "frac_of_hbm_peak": b5 / ms / 1e6 / HBM_PEAK_GBS}
+        env5.set_obs_mode(0, 1)
+        ms, mn = time_calls(torch, lambda: env5.step(a5, r5, d5, o5), 30, warmup=30)
+        rows["student_rollout_c5_occluded_obs"] = {"ms": ms, "env-steps/s": w5.N * w5.T / ms * 1e3,
+                                                   "GB/s": b5 / ms / 1e6,
+                                                   "frac_of_hbm_peak": b5 / ms / 1e6 / HBM_PEAK_GBS,
+                                                   "note": "maze_set_obs_mode(0, 1) on config 5"}
+        env5.set_obs_mode(0, 0)
         nw5 = torch.empty((w5.N,), dtype=torch.int32, device=dev)
         pl5 = torch.empty((w5.N,), dtype=torch.int32, device=dev)
         ms, mn = time_calls(torch, lambda: env5.level_metrics(nw5, pl5), 20)

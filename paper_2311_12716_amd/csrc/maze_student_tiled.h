@@ -25,8 +25,8 @@
 //   next   ("records")  block b-2: view bits -> stream record (row lookup table),
 //                                  goal cell patched in; store reward and done
 //   rest   ("stores")   block b-3: expand records to bytes, store obs
-// (one dynamics, one views and one records wave per 64 envs; every stage has at most
-// two dependent LDS round trips)
+// (one dynamics, one views and one records wave per 64 envs -- two records waves in small
+// workgroups of the observation variants; every stage has at most two dependent LDS round trips)
 // Only the dynamics wave carries a dependency from step to step, so the time per
 // step is that wave's short chain; the store waves never load from global memory
 // and the dynamics wave touches it once every 16 steps (actions, staged in LDS).
@@ -71,7 +71,6 @@ struct View {
     static constexpr int NWIN = EPW * SB / 16;     // 16-bit windows per workgroup step
     static constexpr int ROUNDS = (NWIN + 63) / 64;
     static constexpr int NC = ROUNDS < STORE_WAVES ? ROUNDS : STORE_WAVES;   // store waves
-    static constexpr int WAVES = 3 * NDYN + NC;
     // actions: one 16-byte load per lane covers 16 envs of one step, so a dynamics wave
     // stages ACT_BLOCK steps of its LA envs per load
     static constexpr int ACT_LPR = LA / 16;
@@ -665,6 +664,19 @@ __device__ __forceinline__ FramePose to_frame(uint32_t pos, uint32_t dv, uint32_
         }                                                                                  \
     }
 
+// Records waves per dynamics wave, and the waves of a rollout workgroup.  With occlusion the
+// records stage is the one that is busy all the time (98 % of a launch, every other stage under
+// 60 %).  Workgroups of 16 or 32 envs get two records waves for it, each taking half of a block's
+// passes: config 5 occluded 152 -> 100 us, 8192 envs x 256 steps occluded 58.7 -> 38.8.  At 64
+// envs per workgroup a second wave gains nothing (config 3 occluded 118 either way, and 127 ->
+// 137 us with typed bytes as well: the table reads, not the instruction issue, are the limit
+// there), and at 128 the workgroup has no threads left for one.
+template <int EPW, int MODE> constexpr int records_split() { return (MODE == 1 && EPW <= 32) ? 2 : 1; }
+template <int K, int EPW, int MODE> constexpr int rollout_waves()
+{
+    return (2 + records_split<EPW, MODE>()) * View<K, EPW>::NDYN + View<K, EPW>::NC;
+}
+
 // MODE 0: the default observation.  MODE 1: the observation variants (p.obs_occlusion: unseen
 // cells cleared in the records stage; p.obs_encoding: typed bytes in the stores stage).
 // PARTIAL: the workgroup may hold fewer than EPW envs (the last envs of a batch, n_end - env0 of
@@ -674,13 +686,14 @@ __device__ __forceinline__ FramePose to_frame(uint32_t pos, uint32_t dv, uint32_
 // output is too large for the memory-side cache to absorb, with streaming stores and paced
 // store waves.  Small launches are bound by latency and keep the plain store stage.
 template <int K, typename Word, int EPW, int MODE = 0, bool PARTIAL = false, bool BIG = false>
-__global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
+__global__ __launch_bounds__((64 * rollout_waves<K, EPW, MODE>())) void k_student_rollout(
     StudentDev p, int n_begin, int n_end, const int8_t *__restrict__ actions, int n_steps,
     float *__restrict__ reward, uint8_t *__restrict__ done, int8_t *__restrict__ obs, uint32_t pace_fp)
 {
     using V = View<K, EPW>;
     using L = Lds<K, Word, EPW, MODE>;
-    constexpr int NT = 64 * V::WAVES;
+    constexpr int RSPLIT = records_split<EPW, MODE>();
+    constexpr int NT = 64 * rollout_waves<K, EPW, MODE>();
     constexpr bool LARGE = EPW >= 64 || BIG;
     constexpr int ACT_BLOCK = V::ACT_BLOCK;
     constexpr int UGV = step_group(K * WordOps<Word>::DW + 4, 40);   // views: wall rows + pose in frame + outcome
@@ -690,7 +703,9 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
     // block at once when the workgroup has fewer than 64 envs
     constexpr int UPL = SPB % (64 / V::LA) == 0 ? 64 / V::LA : 1;
     constexpr int UGVP = UGV > SPB / UPL ? SPB / UPL : UGV;
-    constexpr int UGRP = UGR > SPB / UPL ? SPB / UPL : UGR;
+    constexpr int PASSES_R = SPB / UPL / RSPLIT;                 // passes of a records wave per block
+    static_assert(PASSES_R >= 1, "a records wave needs a pass per block");
+    constexpr int UGRP = UGR > PASSES_R ? PASSES_R : UGR;
     extern __shared__ __align__(16) uint32_t lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -851,26 +866,29 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
             })
         __syncthreads();
         __syncthreads();
-    } else if (wave < 3 * V::NDYN) {
+    } else if (wave < (2 + RSPLIT) * V::NDYN) {
         // ================================================================= records
         const int half = UPL > 1 ? lane / V::LA : 0;
         const int el = UPL > 1 ? lane % V::LA : lane;
         const bool active = el < live_lanes;
-        const int e = (wave - 2 * V::NDYN) * 64 + (active ? el : 0);
+        // (RSPLIT records waves per 64 envs: wave `rsel` of them takes that part of a block's passes)
+        const int rsel = RSPLIT > 1 ? (wave - 2 * V::NDYN) / V::NDYN : 0;
+        const int e = (wave - (2 + rsel) * V::NDYN) * 64 + (active ? el : 0);
         float *rw = reward + env0 + e + (size_t)half * N;
         uint8_t *dn = done + env0 + e + (size_t)half * N;
         const double slope = p.reward_slope;
         const uint32_t *vw_lane = lds + L::VW + half * L::VW_SIZE + e;
         uint32_t *rec_lane = lds + L::REC + half * L::REC_SIZE + e * V::REC;
         // the zero dword that ends every record is written once
-        if (active && half == 0)
+        if (active && half == 0 && rsel == 0)
             for (int sl = 0; sl < 2 * SPB; ++sl) lds[L::REC + sl * L::REC_SIZE + e * V::REC + V::ND] = 0;
         __syncthreads();                                             // barrier 0 (set-up)
         __syncthreads();                                             // block 0 published
         __syncthreads();                                             // block 0 viewed
         MAZE_FOR_EACH_BLOCK(
             if (active) {
-                _Pragma("unroll") for (int u0 = 0; u0 < SPB / UPL; u0 += UGRP) {
+                _Pragma("unroll") for (int uu = 0; uu < PASSES_R; uu += UGRP) {
+                    const int u0 = rsel * PASSES_R + uu;
                     uint32_t vw[UGRP][V::WV], g[UGRP], out[UGRP], piece[UGRP][K];
                     _Pragma("unroll") for (int w = 0; w < UGRP; ++w) if (MAZE_STEP_ON((u0 + w) * UPL + half)) {
                         const uint32_t *v = vw_lane + (par * SPB + (u0 + w) * UPL) * L::VW_SIZE;
@@ -908,7 +926,7 @@ __global__ __launch_bounds__((64 * View<K, EPW>::WAVES)) void k_student_rollout(
         __syncthreads();
     } else {
         // ================================================================== stores
-        const int cw = wave - 3 * V::NDYN;
+        const int cw = wave - (2 + RSPLIT) * V::NDYN;
         constexpr int MYR = (V::ROUNDS + V::NC - 1) / V::NC;     // rounds per store wave, at most
         Window win[MYR];
 #pragma unroll
@@ -1078,7 +1096,7 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
     const int n_end = PARTIAL ? n_begin + n_envs : n_begin + groups * EPW;
     const size_t shmem = L::bytes(p.SP);
     if (shmem > lds_budget(ctx)) return MAZE_EHIP;
-    const dim3 grid(groups), block(64 * V::WAVES);
+    const dim3 grid(groups), block(64 * rollout_waves<K, EPW, MODE>());
     // Pacing of the store waves (see the kernel's stores stage): the time one step of the launch
     // should take if the workgroups resident at once write their chunks, reward and done at
     // MAZE_PACED_GBS (MAZE_PACED_GBS_TYPED for the typed observation).  Paced are launches that
@@ -1089,7 +1107,7 @@ int launch_rollout(const maze_ctx *ctx, int n_begin, int n_envs, const int8_t *d
     const double out_bytes = (double)(n_end - n_begin) * n_steps * (V::SB + 5);
     uint32_t pace_fp = 0;
     if (!p.obs_occlusion) {
-        const size_t per_cu = max((size_t)1, min(lds_budget(ctx) / shmem, (size_t)(32 / V::WAVES)));
+        const size_t per_cu = max((size_t)1, min(lds_budget(ctx) / shmem, (size_t)(32 / rollout_waves<K, EPW, MODE>())));
         const double resident = (double)min((long long)groups, (long long)ctx->cus * (long long)per_cu);
         pace_fp = maze_pace_fp(ctx->clock_khz, resident * EPW * (V::SB + 6), out_bytes,
                                p.obs_encoding ? MAZE_PACED_GBS_TYPED : MAZE_PACED_GBS);
