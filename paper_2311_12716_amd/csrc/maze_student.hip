@@ -508,7 +508,7 @@ int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_ste
                          float *d_reward, uint8_t *d_done, int8_t *d_obs, int *covered,
                          hipStream_t st);
 
-int student_tiled_plan(int k, int N, int SP, bool variant, bool occlusion, int cus, size_t budget,
+int student_tiled_plan(int k, int N, int SP, bool typed, bool occlusion, int cus, size_t budget,
                        int *epw, size_t *lds_bytes);
 
 extern "C" int maze_rollout_plan(int N, int H, int W, int view, int encoding, int occlusion, int cus,
@@ -521,7 +521,7 @@ extern "C" int maze_rollout_plan(int N, int H, int W, int view, int encoding, in
     if (rc != MAZE_OK) return rc;
     if (cus < 1 || encoding < 0 || encoding > 1 || occlusion < 0 || occlusion > 1) return MAZE_EINVAL;
     const size_t budget = lds_per_cu > 1024 ? lds_per_cu - 1024 : 0;
-    return student_tiled_plan(view, N, d.SP, encoding || occlusion, occlusion != 0, cus, budget,
+    return student_tiled_plan(view, N, d.SP, encoding != 0, occlusion != 0, cus, budget,
                               envs_per_workgroup, lds_bytes);
 }
 

@@ -1153,26 +1153,29 @@ int launch_rest(const maze_ctx *ctx, int covered, const int8_t *d_actions, int n
 // observation), at most 64 with occlusion (the records stage is the slow one there: more
 // workgroups do better).  MAZE_EHIP if not even 32 envs fit into `budget` bytes of LDS.
 template <int K, typename Word>
-int plan_k(int N, int SP, bool variant, bool occlusion, int cus, size_t budget, int *epw, size_t *lds_bytes)
+int plan_k(int N, int SP, bool typed, bool occlusion, int cus, size_t budget, int *epw, size_t *lds_bytes)
 {
+    const bool variant = typed || occlusion;
     const size_t b128 = variant ? Lds<K, Word, 128, 1>::bytes(SP) : Lds<K, Word, 128>::bytes(SP);
     const size_t b64 = variant ? Lds<K, Word, 64, 1>::bytes(SP) : Lds<K, Word, 64>::bytes(SP);
     const size_t b32 = variant ? Lds<K, Word, 32, 1>::bytes(SP) : Lds<K, Word, 32>::bytes(SP);
     const size_t b16 = variant ? Lds<K, Word, 16, 1>::bytes(SP) : Lds<K, Word, 16>::bytes(SP);
     if (b32 > budget) return MAZE_EHIP;
     if (!occlusion && N >= 128 * (long long)cus && b128 <= budget) { *epw = 128; *lds_bytes = b128; }
-    else if (N >= 64 * (long long)cus && b64 <= budget) { *epw = 64; *lds_bytes = b64; }
+    // (the occluded view alone does better with 32 envs per workgroup and their two records
+    // waves than with 64 and one: config 3 118 -> 112 us; with typed bytes as well 128 -> 140)
+    else if (!(occlusion && !typed) && N >= 64 * (long long)cus && b64 <= budget) { *epw = 64; *lds_bytes = b64; }
     else if (N >= 16 && N <= 16 * (long long)cus) { *epw = 16; *lds_bytes = b16; }
     else { *epw = 32; *lds_bytes = b32; }
     return MAZE_OK;
 }
 
 template <int K>
-int plan_view_size(int N, int SP, bool variant, bool occlusion, int cus, size_t budget, int *epw,
+int plan_view_size(int N, int SP, bool typed, bool occlusion, int cus, size_t budget, int *epw,
                    size_t *lds_bytes)
 {
-    return SP > 32 ? plan_k<K, uint64_t>(N, SP, variant, occlusion, cus, budget, epw, lds_bytes)
-                   : plan_k<K, uint32_t>(N, SP, variant, occlusion, cus, budget, epw, lds_bytes);
+    return SP > 32 ? plan_k<K, uint64_t>(N, SP, typed, occlusion, cus, budget, epw, lds_bytes)
+                   : plan_k<K, uint32_t>(N, SP, typed, occlusion, cus, budget, epw, lds_bytes);
 }
 
 // Returns the number of envs covered (all of them for a rollout) or a negative error code.
@@ -1204,7 +1207,7 @@ int launch_k(const maze_ctx *ctx, const int8_t *d_actions, int n_steps, float *d
     const bool variant = p.obs_encoding || p.obs_occlusion;
     int epw = 0, covered = 0;
     size_t lds_bytes = 0;
-    const int rc = plan_k<K, Word>(p.N, p.SP, variant, p.obs_occlusion != 0, ctx->cus, lds_budget(ctx), &epw,
+    const int rc = plan_k<K, Word>(p.N, p.SP, p.obs_encoding != 0, p.obs_occlusion != 0, ctx->cus, lds_budget(ctx), &epw,
                                    &lds_bytes);
     if (rc != MAZE_OK) return rc;
     if (variant) {

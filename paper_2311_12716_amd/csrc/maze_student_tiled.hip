@@ -4,7 +4,7 @@
 #define MAZE_DECLARE_VIEW_SIZE(K)                                                                  \
     int student_tiled_launch_k##K(const maze_ctx *ctx, const int8_t *d_actions, int n_steps,        \
                                   float *d_reward, uint8_t *d_done, int8_t *d_obs, hipStream_t st); \
-    int student_tiled_plan_k##K(int N, int SP, bool variant, bool occlusion, int cus, size_t budget, \
+    int student_tiled_plan_k##K(int N, int SP, bool typed, bool occlusion, int cus, size_t budget, \
                                 int *epw, size_t *lds_bytes);
 MAZE_DECLARE_VIEW_SIZE(3)
 MAZE_DECLARE_VIEW_SIZE(5)
@@ -35,13 +35,13 @@ int student_tiled_launch(const maze_ctx *ctx, const int8_t *d_actions, int n_ste
 }
 
 // The shape of a rollout launch for one view size (see maze_rollout_plan in the header).
-int student_tiled_plan(int k, int N, int SP, bool variant, bool occlusion, int cus, size_t budget,
+int student_tiled_plan(int k, int N, int SP, bool typed, bool occlusion, int cus, size_t budget,
                        int *epw, size_t *lds_bytes)
 {
     switch (k) {
-    case 3: return student_tiled_plan_k3(N, SP, variant, occlusion, cus, budget, epw, lds_bytes);
-    case 5: return student_tiled_plan_k5(N, SP, variant, occlusion, cus, budget, epw, lds_bytes);
-    case 7: return student_tiled_plan_k7(N, SP, variant, occlusion, cus, budget, epw, lds_bytes);
+    case 3: return student_tiled_plan_k3(N, SP, typed, occlusion, cus, budget, epw, lds_bytes);
+    case 5: return student_tiled_plan_k5(N, SP, typed, occlusion, cus, budget, epw, lds_bytes);
+    case 7: return student_tiled_plan_k7(N, SP, typed, occlusion, cus, budget, epw, lds_bytes);
     default: *epw = 0; *lds_bytes = 0; return MAZE_OK;
     }
 }

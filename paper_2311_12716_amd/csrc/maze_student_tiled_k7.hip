@@ -8,8 +8,8 @@ int student_tiled_launch_k7(const maze_ctx *ctx, const int8_t *d_actions, int n_
     return launch_view_size<7>(ctx, d_actions, n_steps, d_reward, d_done, d_obs, st);
 }
 
-int student_tiled_plan_k7(int N, int SP, bool variant, bool occlusion, int cus, size_t budget, int *epw,
+int student_tiled_plan_k7(int N, int SP, bool typed, bool occlusion, int cus, size_t budget, int *epw,
                           size_t *lds_bytes)
 {
-    return plan_view_size<7>(N, SP, variant, occlusion, cus, budget, epw, lds_bytes);
+    return plan_view_size<7>(N, SP, typed, occlusion, cus, budget, epw, lds_bytes);
 }

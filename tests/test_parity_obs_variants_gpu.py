@@ -41,15 +41,16 @@ def test_config_3_sampled_steps(encoding, occlusion):
 @pytest.mark.parametrize("encoding,occlusion", MODES)
 def test_config_3_full_size_full_rollout(encoding, occlusion):
     """The launch bench.py times for the variant rows: 32768 envs x 256 steps, i.e. the kernels with
-    128 (typed bytes alone) and 64 (occluded) envs per workgroup through 32 full blocks of 8 steps,
-    the double-buffered stage buffers and 16 refills of the action ring; every byte compared."""
+    128 (typed bytes alone), 64 (occluded with typed bytes) and 32 (occluded alone) envs per workgroup
+    through 32 full blocks of 8 steps, the double-buffered stage buffers and 16 refills of the action ring; every byte compared."""
     run_variant(wl.config(3), encoding, occlusion)
 
 
 @pytest.mark.parametrize("T", [7, 8, 9, 16, 17, 33])
 @pytest.mark.parametrize("encoding,occlusion", MODES)
 def test_64_env_workgroups_around_block_boundaries(encoding, occlusion, T):
-    # 16384 envs: 64 envs per workgroup in every mode; rollout lengths around the 8-step blocks
+    # 16384 envs: 64 envs per workgroup with typed bytes, 32 for the occluded view alone; rollout
+    # lengths around the 8-step blocks
     # and the action ring's 16- and 32-step refills; short episodes so that resets are frequent
     w = wl.student_random(f"variant-16384-T{T}", 1000 + T, N=16384, T=T, n_walls=50, max_steps=11)
     run_variant(w, encoding, occlusion)
@@ -68,6 +69,7 @@ def test_small_workgroups_around_block_boundaries(encoding, occlusion, N, T):
 @pytest.mark.parametrize("encoding,occlusion", MODES)
 def test_largest_workgroups_around_block_boundaries(encoding, occlusion, T):
     # 32768 envs: 128 envs per workgroup (two dynamics waves) for typed bytes alone, 64 with occlusion
+    # and typed bytes, 32 with occlusion alone
     w = wl.student_random(f"variant-32768-T{T}", 2000 + T, N=32768, T=T, n_walls=40, max_steps=9)
     run_variant(w, encoding, occlusion)
 
