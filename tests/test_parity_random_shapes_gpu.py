@@ -52,6 +52,37 @@ def test_student_random_shape(seed):
     assert (n_walls_gpu.cpu().numpy() == onw).all() and (path_gpu.cpu().numpy() == opl).all()
 
 
+@pytest.mark.parametrize("seed", range(4500, 4516))
+def test_student_random_shape_large_batches(seed):
+    """The same with batch sizes around the limits at which the launcher changes the workgroup
+    size (16, 32, 64, 128 envs), odd action bytes among the actions, and the rollout cut in two at
+    a random step."""
+    rng = np.random.default_rng(seed)
+    k = int(rng.choice([3, 5, 7]))
+    H, W = int(rng.integers(2, 30)), int(rng.integers(2, 30))
+    N = int(rng.choice([4095, 4096, 4097, 4200, 8191, 8208, 16383, 16384, 16400, 32767, 32768, 33000]))
+    T = int(rng.choice([7, 9, 17, 33, 65, 66]))
+    max_steps = int(rng.choice([1, 3, 11, 50]))
+    n_walls = int(rng.integers(0, H * W - 1))
+    mode = (int(rng.integers(0, 2)), int(rng.integers(0, 2)))
+    w = wl.student_random(f"random-large-{seed}", seed, N=N, H=H, W=W, view=k, T=T, n_walls=n_walls,
+                          max_steps=max_steps)
+    odd = rng.random(w.actions.shape) < 0.05
+    w.actions[odd] = rng.integers(-128, 128, size=int(odd.sum()), dtype=np.int8)
+    note(f"{w.name}: N={N} {H}x{W} k={k} T={T} max_steps={max_steps} walls={n_walls} mode={mode}")
+    env, o = gpu_student(w), cpu_student(w)
+    env.set_obs_mode(*mode)
+    o.set_obs_mode(*mode)
+    cut = int(rng.integers(1, T))
+    acts = to_gpu(w.actions)
+    out1, out2 = env.step(acts[:cut].contiguous()), env.step(acts[cut:].contiguous())
+    torch.cuda.synchronize()
+    ref = o.step(w.actions, T)
+    assert_rollout_equal(out1, tuple(x[:cut] for x in ref), w.name + " (first call)")
+    assert_rollout_equal(out2, tuple(x[cut:] for x in ref), w.name + " (second call)")
+    assert_state_equal(env, o)
+
+
 @pytest.mark.parametrize("seed", range(5000, 5016))
 def test_editor_random_shape(seed):
     rng = np.random.default_rng(seed)
