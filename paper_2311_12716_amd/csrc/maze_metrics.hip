@@ -81,15 +81,33 @@ __global__ __launch_bounds__(256) void k_level_metrics(StudentDev p, int G, int3
     bool running = env_live;
     const int max_rounds = p.H * p.W;            // a shortest path visits no cell twice
     constexpr int CHECK = 4;                     // rounds between two looks at who is done
+    // One round of the flood.  With one env per wave (G = 64) nothing has to be masked: a lane
+    // at the wave's edge receives 0 from the shift, and the lanes of rows beyond the grid hold
+    // no free cell, so they never hold or pass on a reached one.
+    auto flood = [&](Word from) {
+        Word a = wave_shift1_word<true>(from), b = wave_shift1_word<false>(from);
+        if (G != 64) { a &= keep_a; b &= keep_b; }
+        return (Word)((from | (from << 1) | (from >> 1) | a | b) & free_cells);
+    };
     for (int round0 = 0; round0 <= max_rounds; round0 += CHECK) {
+        // the goal's bit is looked for once per CHECK rounds; the lane that finds it then
+        // replays the rounds since the last look (the wave's other lanes replay with it, their
+        // results are not used) to learn in which of them it appeared
         const Word before = reach;
+        const bool here = dist < 0 && (reach & goal_bit) != 0;       // reached by round0
 #pragma unroll
-        for (int i = 0; i < CHECK; ++i) {
-            if (dist < 0 && (reach & goal_bit) != 0) dist = round0 + i;
-            const Word a = wave_shift1_word<true>(reach) & keep_a, b = wave_shift1_word<false>(reach) & keep_b;
-            reach = (Word)((reach | (reach << 1) | (reach >> 1) | a | b) & free_cells);
-        }
+        for (int i = 0; i < CHECK; ++i) reach = flood(reach);
         const bool changed = reach != before;    // the flood only grows: no change over these rounds = none in any
+        if (here) dist = round0;
+        const bool late = dist < 0 && (reach & goal_bit) != 0;       // reached in rounds round0+1 .. round0+CHECK
+        if (__any(late)) {
+            Word again = before;
+#pragma unroll
+            for (int i = 1; i <= CHECK; ++i) {
+                again = flood(again);
+                if (late && dist < 0 && (again & goal_bit) != 0) dist = round0 + i;
+            }
+        }
         // an env is done when its goal lane has a distance or nothing changed in these rounds
         const uint64_t found = __ballot(dist >= 0) & gmask, moving = __ballot(changed) & gmask;
         if (found || !moving) running = false;
