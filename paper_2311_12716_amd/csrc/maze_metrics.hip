@@ -80,7 +80,8 @@ __global__ __launch_bounds__(256) void k_level_metrics(StudentDev p, int G, int3
     int dist = -1;                               // set by the goal's lane in the round its bit appears
     bool running = env_live;
     const int max_rounds = p.H * p.W;            // a shortest path visits no cell twice
-    constexpr int CHECK = 4;                     // rounds between two looks at who is done
+    // rounds between two looks at who is done: more on the large grids, whose paths are long
+    constexpr int CHECK = sizeof(Word) == 8 ? 16 : 4;
     // One round of the flood.  With one env per wave (G = 64) nothing has to be masked: a lane
     // at the wave's edge receives 0 from the shift, and the lanes of rows beyond the grid hold
     // no free cell, so they never hold or pass on a reached one.
